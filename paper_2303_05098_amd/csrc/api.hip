@@ -1,0 +1,240 @@
+// C-ABI entry points: argument checks, allocator, feature finalisation, run-first tuner, handle lifetime.
+#include "mo_internal.hpp"
+
+#include <chrono>
+#include <cmath>
+#include <limits>
+
+namespace mo {
+
+static thread_local int g_last_hip_error = 0;
+void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+static void *(*g_alloc)(size_t, void *, void *) = nullptr;
+static void (*g_free)(void *, void *, void *) = nullptr;
+static void *g_user = nullptr;
+
+void *dev_alloc(size_t bytes, hipStream_t s)
+{
+    if (bytes == 0) bytes = 256;
+    if (g_alloc) return g_alloc(bytes, (void *)s, g_user);
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) { set_hip_error(e); return nullptr; }
+    return p;
+}
+
+void dev_free(void *p, hipStream_t s)
+{
+    if (!p) return;
+    if (g_free) { g_free(p, (void *)s, g_user); return; }
+    (void)hipFree(p);
+}
+
+}  // namespace mo
+
+using namespace mo;
+
+extern "C" {
+
+void mo_default_params(mo_params *out)
+{
+    if (!out) return;
+    out->td_num = 1; out->td_den = 2;
+    out->hyb_num = 1; out->hyb_den = 3;
+    out->max_fill = 16;
+    out->max_slots = (int64_t)1 << 62;
+}
+
+mo_status mo_set_allocator(void *(*alloc)(size_t, void *, void *), void (*free_)(void *, void *, void *), void *user)
+{
+    if ((alloc == nullptr) != (free_ == nullptr)) return MO_E_NULL;
+    g_alloc = alloc; g_free = free_; g_user = user;
+    return MO_OK;
+}
+
+const char *mo_strerror(mo_status s)
+{
+    switch (s) {
+    case MO_OK: return "ok";
+    case MO_E_NULL: return "null pointer argument";
+    case MO_E_SHAPE: return "matrix dimensions out of range";
+    case MO_E_CSR_INVALID: return "CSR arrays violate the precondition";
+    case MO_E_FORMAT: return "unknown format id";
+    case MO_E_DTYPE: return "unknown value type";
+    case MO_E_FILL: return "format needs more padding than the parameters allow";
+    case MO_E_ALLOC: return "device allocation failed";
+    case MO_E_DEVICE: return "HIP call failed";
+    case MO_E_MODEL: return "model file unreadable or malformed";
+    case MO_E_PARAM: return "invalid parameter";
+    }
+    return "unknown status";
+}
+
+int mo_last_hip_error(void) { return g_last_hip_error; }
+
+mo_status mo_features(const mo_csr *a, const mo_params *params, double out[MO_NUM_FEATURES], mo_feature_ints *ints_opt, void *stream)
+{
+    if (!out) return MO_E_NULL;
+    MO_TRY(check_csr_args(a));
+    mo_params p;
+    MO_TRY(check_params(params, &p));
+    hipStream_t s = (hipStream_t)stream;
+    Analysis an;
+    {
+        Scratch scr(s);
+        MO_TRY(analyse(*a, p, true, &an, scr, s));
+    }
+    // Table I, from exact integers.  M * sum(len^2) - NNZ^2 equals M^2 times the mean squared deviation of the row
+    // lengths; every floating-point operation below is a single correctly rounded IEEE operation.
+    const unsigned __int128 num = (unsigned __int128)a->m * (unsigned __int128)an.sum_sq -
+                                  (unsigned __int128)a->nnz * (unsigned __int128)a->nnz;
+    const double md = (double)a->m, nd = (double)a->n, zd = (double)a->nnz;
+    const double mm = md * md;
+    const double var = (double)num / mm;
+    out[0] = md;
+    out[1] = nd;
+    out[2] = zd;
+    out[3] = zd / md;
+    const double mn = md * nd;
+    out[4] = zd / mn;
+    out[5] = (double)an.max_row;
+    out[6] = (double)an.min_row;
+    out[7] = std::sqrt(var);
+    out[8] = (double)an.n_diag;
+    out[9] = (double)an.n_true;
+    if (ints_opt) {
+        ints_opt->m = a->m; ints_opt->n = a->n; ints_opt->nnz = a->nnz;
+        ints_opt->max_row = an.max_row; ints_opt->min_row = an.min_row;
+        ints_opt->n_diag = an.n_diag; ints_opt->n_true_diag = an.n_true;
+        ints_opt->sum_sq_row = an.sum_sq;
+    }
+    return MO_OK;
+}
+
+mo_status mo_convert(const mo_csr *a, mo_format fmt, const mo_params *params, mo_matrix **out, void *stream)
+{
+    if (!out) return MO_E_NULL;
+    *out = nullptr;
+    MO_TRY(check_csr_args(a));
+    if ((int)fmt < 0 || (int)fmt >= MO_NUM_FORMATS) return MO_E_FORMAT;
+    mo_params p;
+    MO_TRY(check_params(params, &p));
+    hipStream_t s = (hipStream_t)stream;
+    Scratch scr(s);
+    Analysis an;
+    const bool want_hist = (fmt == MO_DIA || fmt == MO_HDC);
+    MO_TRY(analyse(*a, p, want_hist, &an, scr, s));
+    return convert_impl(*a, fmt, p, an, out, s);
+}
+
+mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
+{
+    if (!a || !x || !y) return MO_E_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    switch (a->fmt) {
+    case MO_COO: return spmv_coo(*a, x, y, false, s);
+    case MO_CSR: return spmv_csr(*a, x, y, false, s);
+    case MO_DIA: return spmv_dia(*a, x, y, s);
+    case MO_ELL: return spmv_ell(*a, x, y, s);
+    case MO_HYB:
+        MO_TRY(spmv_ell(*a, x, y, s));
+        return spmv_coo(*a, x, y, true, s);
+    case MO_HDC:
+        MO_TRY(spmv_dia(*a, x, y, s));
+        return spmv_csr(*a, x, y, true, s);
+    }
+    return MO_E_FORMAT;
+}
+
+mo_status mo_pick(const double ms[MO_NUM_FORMATS], mo_format *best)
+{
+    if (!ms || !best) return MO_E_NULL;
+    int b = -1;
+    for (int f = 0; f < MO_NUM_FORMATS; ++f) {
+        if (std::isnan(ms[f])) continue;
+        if (b < 0 || ms[f] < ms[b]) b = f;
+    }
+    if (b < 0) return MO_E_PARAM;
+    *best = (mo_format)b;
+    return MO_OK;
+}
+
+mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
+                  double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream)
+{
+    if (!best || !ms_per_rep) return MO_E_NULL;
+    MO_TRY(check_csr_args(a));
+    mo_params p;
+    MO_TRY(check_params(params, &p));
+    int warm = 5, reps = 50;
+    if (opts) { warm = opts->warmups; reps = opts->reps; }
+    if (warm < 0 || reps < 1) return MO_E_PARAM;
+    hipStream_t s = (hipStream_t)stream;
+    for (int f = 0; f < MO_NUM_FORMATS; ++f) {
+        ms_per_rep[f] = std::numeric_limits<double>::quiet_NaN();
+        if (convert_ms) convert_ms[f] = std::numeric_limits<double>::quiet_NaN();
+    }
+    Scratch scr(s);
+    Analysis an;
+    MO_TRY(analyse(*a, p, true, &an, scr, s));
+    const size_t sv = dtype_size(a->dtype);
+    void *x = scr.get((size_t)a->n * sv);
+    void *y = scr.get((size_t)a->m * sv);
+    if (!x || !y) return MO_E_ALLOC;
+    // x = 0 is as good as any vector for timing: no kernel here branches on values
+    MO_TRY(fill_zero(x, a->n, a->dtype, s));
+    hipEvent_t e0, e1;
+    MO_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return MO_E_DEVICE; }
+    mo_status rc = MO_OK;
+    for (int f = 0; f < MO_NUM_FORMATS && rc == MO_OK; ++f) {
+        mo_matrix *h = nullptr;
+        const auto t0 = std::chrono::steady_clock::now();
+        mo_status c = convert_impl(*a, (mo_format)f, p, an, &h, s);
+        if (c == MO_E_FILL) continue;
+        if (c != MO_OK) { rc = c; break; }
+        const auto t1 = std::chrono::steady_clock::now();
+        if (convert_ms) convert_ms[f] = std::chrono::duration<double, std::milli>(t1 - t0).count();
+        for (int i = 0; i < warm && rc == MO_OK; ++i) rc = mo_spmv(h, x, y, s);
+        if (rc == MO_OK && hipEventRecord(e0, s) != hipSuccess) rc = MO_E_DEVICE;
+        for (int i = 0; i < reps && rc == MO_OK; ++i) rc = mo_spmv(h, x, y, s);
+        if (rc == MO_OK && hipEventRecord(e1, s) != hipSuccess) rc = MO_E_DEVICE;
+        if (rc == MO_OK && hipEventSynchronize(e1) != hipSuccess) rc = MO_E_DEVICE;
+        float ms = 0.f;
+        if (rc == MO_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = MO_E_DEVICE;
+        if (rc == MO_OK) ms_per_rep[f] = (double)ms / (double)reps;
+        (void)hipStreamSynchronize(s);
+        mo_matrix_free(h);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != MO_OK) return rc;
+    return mo_pick(ms_per_rep, best);
+}
+
+mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out)
+{
+    if (!a || !out) return MO_E_NULL;
+    out->fmt = a->fmt; out->dtype = a->dtype;
+    out->m = a->m; out->n = a->n; out->nnz = a->nnz; out->ld = a->ld;
+    out->nd = a->nd; out->k = a->k; out->nnz_coo = a->nnz_coo; out->nnz_csr = a->nnz_csr;
+    const bool dia = a->fmt == MO_DIA || a->fmt == MO_HDC;
+    const bool ell = a->fmt == MO_ELL || a->fmt == MO_HYB;
+    const bool coo = a->fmt == MO_COO || a->fmt == MO_HYB;
+    const bool csr = a->fmt == MO_CSR || a->fmt == MO_HDC;
+    out->dia_off = dia ? a->dia_off : nullptr; out->dia_val = dia ? a->dia_val : nullptr;
+    out->ell_col = ell ? a->ell_col : nullptr; out->ell_val = ell ? a->ell_val : nullptr;
+    out->coo_row = coo ? a->coo_row : nullptr; out->coo_col = coo ? a->coo_col : nullptr; out->coo_val = coo ? a->coo_val : nullptr;
+    out->csr_row_ptr = csr ? a->csr_row_ptr : nullptr; out->csr_col = csr ? a->csr_col : nullptr; out->csr_val = csr ? a->csr_val : nullptr;
+    return MO_OK;
+}
+
+void mo_matrix_free(mo_matrix *a)
+{
+    if (!a) return;
+    for (void *p : a->owned) dev_free(p, a->home);
+    delete a;
+}
+
+}  // extern "C"

@@ -1,0 +1,469 @@
+// CSR -> {COO, DIA, ELL, HYB, HDC} on the device (formats: Section II-B).
+//
+// Every conversion is integer bookkeeping plus copies of the stored values, so the produced arrays are fully
+// determined by the input: offsets ascending, row entries in ascending column order, padding col = -1 / val = +0.
+// Rows are mapped one per lane, which makes the writes into the slot-major ELL slabs and the diagonal-major DIA
+// slabs coalesced; the tail of a row longer than SHORT_ROW entries is handled by the whole wave.
+#include "dev_common.hpp"
+#include "mo_internal.hpp"
+
+#include <cmath>
+#include <new>
+
+namespace mo {
+
+constexpr int CB = 256;
+constexpr int SHORT_ROW = 32;
+
+// ------------------------------------------------------------------ generic row walker
+// Calls f(row, p, s) for every stored entry p of the rows owned by this wave (one row per lane), s = position of
+// the entry inside its row.  Entries s < SHORT_ROW lane-per-row; later entries with lanes over consecutive p.
+template <class F>
+__device__ __forceinline__ void walk_rows(bool rv, int64_t row, int64_t lo, int64_t hi, F f)
+{
+    const int64_t len = hi - lo;
+    const int sl = (int)(len < SHORT_ROW ? len : SHORT_ROW);
+    const int wmax = wave_max(rv ? sl : 0);
+    for (int k = 0; k < wmax; ++k)
+        if (rv && k < sl) f(row, lo + k, (int64_t)k);
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+    const int lane = lane_id();
+    while (longmask) {
+        const int l = __ffsll((unsigned long long)longmask) - 1;
+        longmask &= longmask - 1;
+        const int64_t r = __shfl(row, l, WAVE);
+        const int64_t rlo = __shfl(lo, l, WAVE);
+        const int64_t rhi = __shfl(hi, l, WAVE);
+        for (int64_t q = rlo + SHORT_ROW + lane; q < rhi; q += WAVE) f(r, q, q - rlo);
+    }
+}
+
+__global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+template <typename T>
+__global__ void k_fill_val(T *p, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = (T)0;
+}
+
+// ------------------------------------------------------------------ COO
+template <typename T>
+__global__ __launch_bounds__(CB) void k_csr_to_coo(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+                                                    const T *__restrict__ val, int64_t m, int32_t *__restrict__ orow,
+                                                    int32_t *__restrict__ ocol, T *__restrict__ oval)
+{
+    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
+    const bool rv = row < m;
+    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
+    walk_rows(rv, row, lo, hi, [&](int64_t r, int64_t p, int64_t) {
+        orow[p] = (int32_t)r;
+        ocol[p] = col_idx[p];
+        oval[p] = val[p];
+    });
+}
+
+// ------------------------------------------------------------------ diagonal selection
+// flag[i] = 1 for every diagonal kept by the DIA part: all non-empty ones (DIA) or the true ones (HDC).
+__global__ __launch_bounds__(CB) void k_flag_diag(const uint32_t *__restrict__ hist, int64_t nd, int all_nonempty,
+                                                   unsigned long long thr_rhs, unsigned long long td_den, int32_t *__restrict__ flag)
+{
+    const int64_t i = (int64_t)blockIdx.x * CB + threadIdx.x;
+    if (i >= nd) return;
+    const unsigned long long c = hist[i];
+    flag[i] = (c >= 1ull && (all_nonempty || c * td_den >= thr_rhs)) ? 1 : 0;
+}
+
+// pos[] = exclusive scan of flag[].  Writes the ascending offset list and turns pos into the slot map
+// (slot index of a kept diagonal, -1 otherwise), in place.
+__global__ __launch_bounds__(CB) void k_offsets_and_slots(const int32_t *__restrict__ flag, int32_t *__restrict__ pos, int64_t nd,
+                                                           int64_t m, int32_t *__restrict__ off)
+{
+    const int64_t i = (int64_t)blockIdx.x * CB + threadIdx.x;
+    if (i >= nd) return;
+    if (flag[i]) off[pos[i]] = (int32_t)(i - (m - 1));
+    else pos[i] = -1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+                                                  const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
+                                                  int64_t ld, T *__restrict__ dval)
+{
+    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
+    const bool rv = row < m;
+    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
+    walk_rows(rv, row, lo, hi, [&](int64_t r, int64_t p, int64_t) {
+        const int k = slot[(int64_t)col_idx[p] - r + (m - 1)];
+        if (k >= 0) dval[(int64_t)k * ld + r] = val[p];
+    });
+}
+
+// ------------------------------------------------------------------ ELL (and the ELL part of HYB)
+// Entries at position s < K go to slot s; entries at s >= K (HYB only) go to the COO part at
+// coo_ptr[row] + (s - K).  Slots s in [len, K) receive the padding markers.
+template <typename T>
+__global__ __launch_bounds__(CB) void k_fill_ell(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+                                                  const T *__restrict__ val, int64_t m, int64_t K, int64_t ld,
+                                                  int32_t *__restrict__ ecol, T *__restrict__ eval,
+                                                  const int32_t *__restrict__ coo_ptr, int32_t *__restrict__ crow,
+                                                  int32_t *__restrict__ ccol, T *__restrict__ cval)
+{
+    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
+    const bool rv = row < m;
+    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
+    if (row < ld) {
+        for (int64_t s = (hi - lo); s < K; ++s) {
+            ecol[s * ld + row] = -1;
+            eval[s * ld + row] = (T)0;
+        }
+    }
+    walk_rows(rv, row, lo, hi, [&](int64_t r, int64_t p, int64_t s) {
+        if (s < K) {
+            ecol[s * ld + r] = col_idx[p];
+            eval[s * ld + r] = val[p];
+        } else {
+            const int64_t q = (int64_t)coo_ptr[r] + (s - K);
+            crow[q] = (int32_t)r;
+            ccol[q] = col_idx[p];
+            cval[q] = val[p];
+        }
+    });
+}
+
+// Histogram of row lengths (equal lengths inside a wave are merged before the atomic) and, per row, the number of
+// entries beyond K that spill into the COO part when K >= 0.
+__global__ __launch_bounds__(CB) void k_len_hist(const int32_t *__restrict__ row_ptr, int64_t m, uint32_t *__restrict__ lhist)
+{
+    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
+    const bool rv = row < m;
+    const int key = rv ? (row_ptr[row + 1] - row_ptr[row]) : -1;
+    const int lane = lane_id();
+    uint64_t todo = ballot64(rv);
+    while (todo) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const int lkey = __shfl(key, leader, WAVE);
+        const uint64_t same = ballot64(rv && key == lkey) & todo;
+        if (lane == leader) atomicAdd(&lhist[lkey], (uint32_t)__popcll(same));
+        todo &= ~same;
+    }
+}
+
+__global__ __launch_bounds__(CB) void k_surplus(const int32_t *__restrict__ row_ptr, int64_t m, int64_t K, int32_t *__restrict__ cnt)
+{
+    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
+    if (row >= m) return;
+    const int64_t len = row_ptr[row + 1] - row_ptr[row];
+    cnt[row] = (int32_t)(len > K ? len - K : 0);
+}
+
+// ------------------------------------------------------------------ HDC remainder
+// FILL = false: cnt[row] = number of entries of the row that are not on a kept diagonal.
+// FILL = true : those entries are written, in row order, to the CSR part starting at rest_ptr[row].
+template <typename T, bool FILL>
+__global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+                                                  const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
+                                                  int32_t *__restrict__ cnt, const int32_t *__restrict__ rest_ptr,
+                                                  int32_t *__restrict__ rcol, T *__restrict__ rval)
+{
+    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
+    const bool rv = row < m;
+    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
+    const int64_t len = hi - lo;
+    const int sl = (int)(len < SHORT_ROW ? len : SHORT_ROW);
+    const int wmax = wave_max(rv ? sl : 0);
+    const int64_t base = (FILL && rv) ? rest_ptr[row] : 0;
+    int64_t mine = 0;
+    for (int k = 0; k < wmax; ++k) {
+        if (rv && k < sl) {
+            const int32_t c = col_idx[lo + k];
+            if (slot[(int64_t)c - row + (m - 1)] < 0) {
+                if (FILL) { rcol[base + mine] = c; rval[base + mine] = val[lo + k]; }
+                ++mine;
+            }
+        }
+    }
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+    const int lane = lane_id();
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (WAVE - lane));
+    while (longmask) {
+        const int l = __ffsll((unsigned long long)longmask) - 1;
+        longmask &= longmask - 1;
+        const int64_t r = __shfl(row, l, WAVE);
+        const int64_t rlo = __shfl(lo, l, WAVE), rhi = __shfl(hi, l, WAVE);
+        int64_t run = __shfl(mine, l, WAVE);
+        const int64_t rbase = __shfl(base, l, WAVE);
+        for (int64_t q0 = rlo + SHORT_ROW; q0 < rhi; q0 += WAVE) {
+            const int64_t q = q0 + lane;
+            bool rest = false;
+            int32_t c = 0;
+            if (q < rhi) {
+                c = col_idx[q];
+                rest = slot[(int64_t)c - r + (m - 1)] < 0;
+            }
+            const uint64_t mask = ballot64(rest);
+            if (FILL && rest) {
+                const int64_t pos = rbase + run + __popcll(mask & below);
+                rcol[pos] = c;
+                rval[pos] = val[q];
+            }
+            run += __popcll(mask);
+        }
+        if (lane == l) mine = run;
+    }
+    if (!FILL && rv) cnt[row] = (int32_t)mine;
+}
+
+// ------------------------------------------------------------------ host side
+static unsigned blocks_for(int64_t n) { return (unsigned)((n + CB - 1) / CB > 0 ? (n + CB - 1) / CB : 1); }
+static unsigned fill_grid(int64_t n)
+{
+    int64_t g = (n + (int64_t)CB * 8 - 1) / ((int64_t)CB * 8);
+    if (g < 1) g = 1;
+    if (g > 8192) g = 8192;
+    return (unsigned)g;
+}
+
+mo_status check_csr_args(const mo_csr *a)
+{
+    if (!a) return MO_E_NULL;
+    if (a->dtype != MO_F32 && a->dtype != MO_F64) return MO_E_DTYPE;
+    if (a->m < 1 || a->n < 1 || a->nnz < 0) return MO_E_SHAPE;
+    if (a->nnz > 2147483647LL || a->m + a->n > 2147483647LL) return MO_E_SHAPE;
+    if (!a->row_ptr) return MO_E_NULL;
+    if (a->nnz > 0 && (!a->col_idx || !a->val)) return MO_E_NULL;
+    return MO_OK;
+}
+
+mo_status check_params(const mo_params *in, mo_params *out)
+{
+    mo_default_params(out);
+    if (in) *out = *in;
+    if (out->td_den <= 0 || out->hyb_den <= 0 || out->td_num < 0 || out->hyb_num < 0 || out->max_fill < 0 || out->max_slots < 0)
+        return MO_E_PARAM;
+    return MO_OK;
+}
+
+bool slab_feasible(int64_t width, int64_t m, int64_t nnz, const mo_params &p)
+{
+    const __int128 slots = (__int128)width * (__int128)m;
+    if (slots > (__int128)p.max_fill * (__int128)nnz) return false;
+    if (slots > (__int128)p.max_slots) return false;
+    return true;
+}
+
+namespace {
+
+struct Builder {
+    mo_matrix *h;
+    hipStream_t s;
+    bool failed = false;
+    Builder(hipStream_t st) : h(new (std::nothrow) mo_matrix()), s(st) { if (h) h->home = st; }
+    ~Builder() { if (h) release(); }
+    void *own(size_t bytes)
+    {
+        void *p = dev_alloc(bytes, s);
+        if (!p) { failed = true; return nullptr; }
+        h->owned.push_back(p);
+        return p;
+    }
+    void release()
+    {
+        for (void *p : h->owned) dev_free(p, s);
+        delete h;
+        h = nullptr;
+    }
+    mo_matrix *take() { mo_matrix *r = h; h = nullptr; return r; }
+};
+
+int pick_lanes(int64_t nnz, int64_t m)
+{
+    const double avg = m > 0 ? (double)nnz / (double)m : 0.0;
+    int lanes = 2;
+    while (lanes < 64 && (double)lanes < avg) lanes <<= 1;
+    return lanes;
+}
+
+// Slot map for the DIA part: offsets (ascending) into h->dia_off, slot[] (m + n - 1 ints, scratch) for the fill.
+template <typename T>
+mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an, bool all_nonempty, int64_t nd,
+                         Builder &b, Scratch &scr, int32_t **slot_out)
+{
+    hipStream_t s = b.s;
+    const int64_t ndiag = a.m + a.n - 1;
+    int32_t *flag = (int32_t *)scr.get((size_t)ndiag * 4);
+    int32_t *pos = (int32_t *)scr.get((size_t)(ndiag + 1) * 4);
+    void *tmp = scr.get(scan_tmp_bytes(ndiag));
+    if (!flag || !pos || !tmp) return MO_E_ALLOC;
+    mo_matrix *h = b.h;
+    h->nd = nd;
+    h->dia_off = (int32_t *)b.own((size_t)(nd > 0 ? nd : 1) * 4);
+    h->dia_val = b.own((size_t)(nd > 0 ? nd : 1) * (size_t)h->ld * sizeof(T));
+    if (b.failed) return MO_E_ALLOC;
+    const int64_t mn = a.m < a.n ? a.m : a.n;
+    hipLaunchKernelGGL(k_flag_diag, dim3(blocks_for(ndiag)), dim3(CB), 0, s, an.hist, ndiag, all_nonempty ? 1 : 0,
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, flag);
+    MO_LAUNCH_CHECK();
+    MO_TRY(exclusive_scan_i32(flag, pos, ndiag, tmp, s));
+    hipLaunchKernelGGL(k_offsets_and_slots, dim3(blocks_for(ndiag)), dim3(CB), 0, s, flag, pos, ndiag, a.m, h->dia_off);
+    MO_LAUNCH_CHECK();
+    if (nd > 0) {
+        hipLaunchKernelGGL(k_fill_val<T>, dim3(fill_grid(nd * h->ld)), dim3(CB), 0, s, (T *)h->dia_val, nd * h->ld);
+        MO_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_fill_dia<T>, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.col_idx, (const T *)a.val, a.m,
+                           pos, h->ld, (T *)h->dia_val);
+        MO_LAUNCH_CHECK();
+    }
+    *slot_out = pos;
+    return MO_OK;
+}
+
+void setup_coo_tiles(Builder &b, size_t sv)
+{
+    mo_matrix *h = b.h;
+    h->coo_tiles = (h->nnz_coo + COO_TILE - 1) / COO_TILE;
+    const int64_t t = h->coo_tiles > 0 ? h->coo_tiles : 1;
+    h->coo_carry_row = (int32_t *)b.own((size_t)t * 4);
+    h->coo_carry_val = b.own((size_t)t * sv);
+}
+
+template <typename T>
+mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, const Analysis &an, mo_matrix **out, hipStream_t s)
+{
+    Builder b(s);
+    if (!b.h) return MO_E_ALLOC;
+    mo_matrix *h = b.h;
+    Scratch scr(s);
+    h->fmt = fmt; h->dtype = a.dtype; h->m = a.m; h->n = a.n; h->nnz = a.nnz;
+    h->ld = (a.m + 63) & ~(int64_t)63;
+    const T *aval = (const T *)a.val;
+    const unsigned row_blocks = blocks_for(a.m);
+
+    switch (fmt) {
+    case MO_CSR: {
+        h->csr_row_ptr = a.row_ptr; h->csr_col = a.col_idx; h->csr_val = a.val; h->nnz_csr = a.nnz;
+        h->csr_lanes = pick_lanes(a.nnz, a.m);
+        h->csr_max_row = an.max_row;
+        break;
+    }
+    case MO_COO: {
+        h->nnz_coo = a.nnz;
+        const size_t e = (size_t)(a.nnz > 0 ? a.nnz : 1);
+        h->coo_row = (int32_t *)b.own(e * 4);
+        h->coo_col = (int32_t *)b.own(e * 4);
+        h->coo_val = b.own(e * sizeof(T));
+        setup_coo_tiles(b, sizeof(T));
+        if (b.failed) return MO_E_ALLOC;
+        hipLaunchKernelGGL(k_csr_to_coo<T>, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, h->coo_row,
+                           h->coo_col, (T *)h->coo_val);
+        MO_LAUNCH_CHECK();
+        break;
+    }
+    case MO_DIA: {
+        if (!slab_feasible(an.n_diag, a.m, a.nnz, p)) return MO_E_FILL;
+        int32_t *slot = nullptr;
+        MO_TRY(build_dia_part<T>(a, p, an, true, an.n_diag, b, scr, &slot));
+        break;
+    }
+    case MO_ELL:
+    case MO_HYB: {
+        int64_t K = an.max_row;
+        int32_t *coo_ptr = nullptr;
+        if (fmt == MO_ELL) {
+            if (!slab_feasible(K, a.m, a.nnz, p)) return MO_E_FILL;
+        } else {
+            // K_H from the histogram of row lengths: largest k with #{len >= k} * den >= m * num.
+            const int64_t nh = an.max_row + 1;
+            uint32_t *lhist = (uint32_t *)scr.get((size_t)nh * 4);
+            if (!lhist) return MO_E_ALLOC;
+            hipLaunchKernelGGL(k_fill_i32, dim3(fill_grid(nh)), dim3(CB), 0, s, (int32_t *)lhist, nh, 0);
+            MO_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_len_hist, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.m, lhist);
+            MO_LAUNCH_CHECK();
+            std::vector<uint32_t> hh((size_t)nh);
+            MO_HIP(hipMemcpyAsync(hh.data(), lhist, (size_t)nh * 4, hipMemcpyDeviceToHost, s));
+            MO_HIP(hipStreamSynchronize(s));
+            const __int128 need = (__int128)a.m * (__int128)p.hyb_num;
+            int64_t rows_ge = 0;   // rows with len >= k, walking k downwards
+            K = 0;
+            for (int64_t k = an.max_row; k >= 1; --k) {
+                rows_ge += hh[(size_t)k];
+                if ((__int128)rows_ge * (__int128)p.hyb_den >= need) { K = k; break; }
+            }
+            int64_t surplus = 0;
+            for (int64_t len = K + 1; len <= an.max_row; ++len) surplus += (int64_t)hh[(size_t)len] * (len - K);
+            h->nnz_coo = surplus;
+            const size_t e = (size_t)(surplus > 0 ? surplus : 1);
+            h->coo_row = (int32_t *)b.own(e * 4);
+            h->coo_col = (int32_t *)b.own(e * 4);
+            h->coo_val = b.own(e * sizeof(T));
+            setup_coo_tiles(b, sizeof(T));
+            int32_t *cnt = (int32_t *)scr.get((size_t)a.m * 4);
+            coo_ptr = (int32_t *)scr.get((size_t)(a.m + 1) * 4);
+            void *tmp = scr.get(scan_tmp_bytes(a.m));
+            if (b.failed || !cnt || !coo_ptr || !tmp) return MO_E_ALLOC;
+            hipLaunchKernelGGL(k_surplus, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.m, K, cnt);
+            MO_LAUNCH_CHECK();
+            MO_TRY(exclusive_scan_i32(cnt, coo_ptr, a.m, tmp, s));
+        }
+        h->k = K;
+        const size_t slots = (size_t)(K > 0 ? K : 1) * (size_t)h->ld;
+        h->ell_col = (int32_t *)b.own(slots * 4);
+        h->ell_val = b.own(slots * sizeof(T));
+        if (b.failed) return MO_E_ALLOC;
+        hipLaunchKernelGGL(k_fill_ell<T>, dim3(blocks_for(h->ld)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, K, h->ld,
+                           h->ell_col, (T *)h->ell_val, coo_ptr, h->coo_row, h->coo_col, (T *)h->coo_val);
+        MO_LAUNCH_CHECK();
+        break;
+    }
+    case MO_HDC: {
+        int32_t *slot = nullptr;
+        MO_TRY(build_dia_part<T>(a, p, an, false, an.n_true, b, scr, &slot));
+        int32_t *cnt = (int32_t *)scr.get((size_t)a.m * 4);
+        int32_t *rest_ptr = (int32_t *)b.own((size_t)(a.m + 1) * 4);
+        void *tmp = scr.get(scan_tmp_bytes(a.m));
+        if (b.failed || !cnt || !tmp) return MO_E_ALLOC;
+        hipLaunchKernelGGL((k_hdc_rest<T, false>), dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot, cnt,
+                           (const int32_t *)nullptr, (int32_t *)nullptr, (T *)nullptr);
+        MO_LAUNCH_CHECK();
+        MO_TRY(exclusive_scan_i32(cnt, rest_ptr, a.m, tmp, s));
+        int32_t total = 0;
+        MO_HIP(hipMemcpyAsync(&total, rest_ptr + a.m, 4, hipMemcpyDeviceToHost, s));
+        MO_HIP(hipStreamSynchronize(s));
+        h->nnz_csr = total;
+        const size_t e = (size_t)(total > 0 ? total : 1);
+        int32_t *rcol = (int32_t *)b.own(e * 4);
+        T *rval = (T *)b.own(e * sizeof(T));
+        if (b.failed) return MO_E_ALLOC;
+        hipLaunchKernelGGL((k_hdc_rest<T, true>), dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot,
+                           (int32_t *)nullptr, rest_ptr, rcol, rval);
+        MO_LAUNCH_CHECK();
+        h->csr_row_ptr = rest_ptr; h->csr_col = rcol; h->csr_val = rval;
+        h->csr_lanes = pick_lanes(total, a.m);
+        h->csr_max_row = an.max_row;
+        break;
+    }
+    default:
+        return MO_E_FORMAT;
+    }
+    // scratch is released after the kernels that use it: the allocator contract is stream-ordered
+    MO_HIP(hipStreamSynchronize(s));
+    *out = b.take();
+    return MO_OK;
+}
+
+}  // namespace
+
+mo_status convert_impl(const mo_csr &a, mo_format fmt, const mo_params &p, const Analysis &an, mo_matrix **out, hipStream_t s)
+{
+    if (a.dtype == MO_F32) return convert_typed<float>(a, fmt, p, an, out, s);
+    return convert_typed<double>(a, fmt, p, an, out, s);
+}
+
+}  // namespace mo

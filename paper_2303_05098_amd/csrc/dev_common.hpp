@@ -1,0 +1,62 @@
+// Device-side helpers for gfx950 (64-lane wavefronts, 8 XCDs).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace mo {
+
+constexpr int WAVE = 64;
+constexpr int NUM_XCD = 8;
+
+// Workgroups are handed to the 8 XCDs round-robin by their linear id.  Each XCD has its own L2, so neighbouring
+// row blocks should land on the same XCD: this maps the hardware block id to a logical block id such that XCD x
+// owns one contiguous run of logical blocks.  A bijection on [0, nb) for any nb.
+__device__ __forceinline__ int64_t xcd_block(int64_t bid, int64_t nb)
+{
+    const int64_t q = nb / NUM_XCD, r = nb % NUM_XCD;
+    const int64_t x = bid % NUM_XCD, j = bid / NUM_XCD;
+    return x * q + (x < r ? x : r) + j;
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (WAVE - 1)); }
+
+// Sum over aligned groups of `width` lanes (power of two, <= 64); every lane of the group gets lane-0-valid sum.
+template <typename T>
+__device__ __forceinline__ T group_sum_down(T v, int width)
+{
+    for (int off = width >> 1; off > 0; off >>= 1) v += __shfl_down(v, off, width);
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_max(T v)
+{
+    for (int off = WAVE / 2; off > 0; off >>= 1) {
+        T o = __shfl_xor(v, off, WAVE);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_min(T v)
+{
+    for (int off = WAVE / 2; off > 0; off >>= 1) {
+        T o = __shfl_xor(v, off, WAVE);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v)
+{
+    for (int off = WAVE / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    return v;
+}
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+
+}  // namespace mo

@@ -1,0 +1,207 @@
+// Feature extraction kernels (Table I; Sections IV-A and VI-C) and CSR validation.
+//
+// Two traversals give every integer the ten features need: one over row_ptr (max, min, sum of squares of the row
+// lengths, all in one pass as Section VI-C asks) and one over col_idx (entries per diagonal d = col - row).  Both
+// also check the CSR precondition, and both clamp what they read so that a malformed matrix can never make a kernel
+// index outside the arrays it was given.  All arithmetic is integer, so results do not depend on scheduling.
+#include "dev_common.hpp"
+#include "mo_internal.hpp"
+
+namespace mo {
+
+struct Counters {
+    unsigned long long max_row, min_row, sum_sq, n_diag, n_true;
+    unsigned int err;
+    unsigned int pad;
+};
+
+constexpr int FB = 256;        // threads per block
+constexpr int SHORT_ROW = 32;  // entries of a row handled lane-per-row; the rest is walked by the whole wave
+
+__global__ void k_init_counters(Counters *c)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        c->max_row = 0ull; c->min_row = ~0ull; c->sum_sq = 0ull; c->n_diag = 0ull; c->n_true = 0ull; c->err = 0u; c->pad = 0u;
+    }
+}
+
+__global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+// F1: one pass over row_ptr.
+__global__ __launch_bounds__(FB) void k_row_stats(const int32_t *__restrict__ row_ptr, int64_t m, int64_t nnz, Counters *ctr)
+{
+    unsigned long long mx = 0ull, mn = ~0ull, sq = 0ull;
+    bool err = false;
+    const int64_t stride = (int64_t)gridDim.x * FB;
+    for (int64_t i = (int64_t)blockIdx.x * FB + threadIdx.x; i < m; i += stride) {
+        const int64_t a = row_ptr[i], b = row_ptr[i + 1];
+        if (i == 0 && a != 0) err = true;
+        if (i == m - 1 && b != nnz) err = true;
+        if (b < a || a < 0 || b > nnz) err = true;
+        const unsigned long long len = b > a ? (unsigned long long)(b - a) : 0ull;
+        mx = len > mx ? len : mx;
+        mn = len < mn ? len : mn;
+        sq += len * len;
+    }
+    mx = wave_max(mx); mn = wave_min(mn); sq = wave_sum(sq);
+    __shared__ unsigned long long s_mx[FB / WAVE], s_mn[FB / WAVE], s_sq[FB / WAVE];
+    __shared__ int s_err;
+    if (threadIdx.x == 0) s_err = 0;
+    __syncthreads();
+    if (err) s_err = 1;
+    if (lane_id() == 0) { s_mx[threadIdx.x / WAVE] = mx; s_mn[threadIdx.x / WAVE] = mn; s_sq[threadIdx.x / WAVE] = sq; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < FB / WAVE; ++w) {
+            mx = s_mx[w] > mx ? s_mx[w] : mx;
+            mn = s_mn[w] < mn ? s_mn[w] : mn;
+            sq += s_sq[w];
+        }
+        atomicMax(&ctr->max_row, mx);
+        atomicMin(&ctr->min_row, mn);
+        atomicAdd(&ctr->sum_sq, sq);
+        if (s_err) atomicOr(&ctr->err, 1u);
+    }
+}
+
+// F2: one pass over col_idx.  Lane l of a wave owns row r0 + l and walks its first SHORT_ROW entries, so for banded
+// and stencil matrices all lanes meet the same diagonal in the same step; equal keys are merged inside the wave
+// (ballot + one atomic per distinct key, at most two merge rounds, then plain atomics) before they reach memory.
+// The tail of a longer row is walked by the whole wave with coalesced loads; entries of one row lie on distinct
+// diagonals, so nothing is there to merge.
+template <bool DO_HIST>
+__global__ __launch_bounds__(FB) void k_diag_hist(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+                                                   int64_t m, int64_t n, int64_t nnz, uint32_t *__restrict__ hist, Counters *ctr)
+{
+    const int64_t row = (int64_t)blockIdx.x * FB + threadIdx.x;
+    const bool rv = row < m;
+    int64_t lo = 0, hi = 0;
+    if (rv) {
+        lo = row_ptr[row]; hi = row_ptr[row + 1];
+        lo = lo < 0 ? 0 : (lo > nnz ? nnz : lo);
+        hi = hi < lo ? lo : (hi > nnz ? nnz : hi);
+    }
+    const int64_t len = hi - lo;
+    const int short_len = (int)(len < SHORT_ROW ? len : SHORT_ROW);
+    const int wmax = wave_max(short_len);
+    const int lane = lane_id();
+    bool err = false;
+    int64_t prev = -1;
+    for (int k = 0; k < wmax; ++k) {
+        const bool act = k < short_len;
+        const int64_t c = act ? (int64_t)col_idx[lo + k] : 0;
+        const bool ok = act && c >= 0 && c < n && c > prev;
+        if (act && !ok) err = true;
+        if (act) prev = c;
+        if (DO_HIST) {
+            const int key = ok ? (int)(c - row + (m - 1)) : -1;
+            uint64_t todo = ballot64(ok);
+            int rounds = 0;
+            while (todo) {
+                if (rounds == 2) {
+                    if ((todo >> lane) & 1ull) atomicAdd(&hist[key], 1u);
+                    break;
+                }
+                const int leader = __ffsll((unsigned long long)todo) - 1;
+                const int lkey = __shfl(key, leader, WAVE);
+                const uint64_t same = ballot64(ok && key == lkey) & todo;
+                if (lane == leader) atomicAdd(&hist[lkey], (uint32_t)__popcll(same));
+                todo &= ~same;
+                ++rounds;
+            }
+        }
+    }
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+    while (longmask) {
+        const int l = __ffsll((unsigned long long)longmask) - 1;
+        longmask &= longmask - 1;
+        const int64_t r = __shfl(row, l, WAVE);
+        const int64_t rlo = __shfl(lo, l, WAVE) + SHORT_ROW;
+        const int64_t rhi = __shfl(hi, l, WAVE);
+        for (int64_t q = rlo + lane; q < rhi; q += WAVE) {
+            const int64_t c = col_idx[q], cp = col_idx[q - 1];
+            const bool ok = c >= 0 && c < n && c > cp;
+            if (!ok) err = true;
+            else if (DO_HIST) atomicAdd(&hist[c - r + (m - 1)], 1u);
+        }
+    }
+    if (err) atomicOr(&ctr->err, 2u);
+}
+
+// N_D = diagonals with at least one entry; N_TD = non-empty diagonals with cnt * td_den >= min(m, n) * td_num.
+__global__ __launch_bounds__(FB) void k_diag_count(const uint32_t *__restrict__ hist, int64_t nd, unsigned long long thr_rhs,
+                                                    unsigned long long td_den, Counters *ctr)
+{
+    unsigned long long c_nd = 0, c_td = 0;
+    const int64_t stride = (int64_t)gridDim.x * FB;
+    for (int64_t i = (int64_t)blockIdx.x * FB + threadIdx.x; i < nd; i += stride) {
+        const unsigned long long c = hist[i];
+        if (c >= 1ull) {
+            ++c_nd;
+            if (c * td_den >= thr_rhs) ++c_td;
+        }
+    }
+    c_nd = wave_sum(c_nd); c_td = wave_sum(c_td);
+    if (lane_id() == 0 && (c_nd | c_td)) {
+        atomicAdd(&ctr->n_diag, c_nd);
+        atomicAdd(&ctr->n_true, c_td);
+    }
+}
+
+static int grid_for(int64_t n, int per_block, int cap)
+{
+    int64_t g = (n + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis *out, Scratch &scratch, hipStream_t s)
+{
+    Counters *ctr = (Counters *)scratch.get(sizeof(Counters));
+    if (!ctr) return MO_E_ALLOC;
+    const int64_t ndiag = a.m + a.n - 1;
+    uint32_t *hist = nullptr;
+    if (want_hist) {
+        hist = (uint32_t *)scratch.get((size_t)ndiag * sizeof(uint32_t));
+        if (!hist) return MO_E_ALLOC;
+    }
+    hipLaunchKernelGGL(k_init_counters, dim3(1), dim3(64), 0, s, ctr);
+    MO_LAUNCH_CHECK();
+    if (want_hist) {
+        hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, 0u);
+        MO_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(k_row_stats, dim3(grid_for(a.m, FB * 4, 2048)), dim3(FB), 0, s, a.row_ptr, a.m, a.nnz, ctr);
+    MO_LAUNCH_CHECK();
+    const int64_t row_blocks = (a.m + FB - 1) / FB;   // m <= 2^31 - 1, so this fits a grid dimension
+    if (want_hist)
+        hipLaunchKernelGGL(k_diag_hist<true>, dim3((unsigned)row_blocks), dim3(FB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, ctr);
+    else
+        hipLaunchKernelGGL(k_diag_hist<false>, dim3((unsigned)row_blocks), dim3(FB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, ctr);
+    MO_LAUNCH_CHECK();
+    if (want_hist) {
+        const int64_t mn = a.m < a.n ? a.m : a.n;
+        hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 2048)), dim3(FB), 0, s, hist, ndiag,
+                           (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
+        MO_LAUNCH_CHECK();
+    }
+    Counters h;
+    MO_HIP(hipMemcpyAsync(&h, ctr, sizeof(Counters), hipMemcpyDeviceToHost, s));
+    MO_HIP(hipStreamSynchronize(s));
+    if (h.err) return MO_E_CSR_INVALID;
+    out->max_row = (int64_t)h.max_row;
+    out->min_row = (int64_t)h.min_row;
+    out->sum_sq = h.sum_sq;
+    out->n_diag = (int64_t)h.n_diag;
+    out->n_true = (int64_t)h.n_true;
+    out->hist = hist;
+    return MO_OK;
+}
+
+}  // namespace mo

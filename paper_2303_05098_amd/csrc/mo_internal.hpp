@@ -1,0 +1,127 @@
+// Internal declarations shared by the library's translation units (host side).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "mo.h"
+
+namespace mo {
+
+// ---------------------------------------------------------------- errors
+void set_hip_error(hipError_t e);
+
+#define MO_HIP(call)                                        \
+    do {                                                    \
+        hipError_t mo_e_ = (call);                          \
+        if (mo_e_ != hipSuccess) {                          \
+            ::mo::set_hip_error(mo_e_);                     \
+            return MO_E_DEVICE;                             \
+        }                                                   \
+    } while (0)
+
+#define MO_TRY(call)                                        \
+    do {                                                    \
+        mo_status mo_s_ = (call);                           \
+        if (mo_s_ != MO_OK) return mo_s_;                   \
+    } while (0)
+
+// Launch check: catches bad launch configurations right away.
+#define MO_LAUNCH_CHECK() MO_HIP(hipGetLastError())
+
+// ---------------------------------------------------------------- device memory
+void *dev_alloc(size_t bytes, hipStream_t s);   // never returns NULL for bytes == 0 (allocates 256 B)
+void dev_free(void *p, hipStream_t s);
+
+// Scoped scratch: everything allocated through it is released when it goes out of scope.
+struct Scratch {
+    hipStream_t s;
+    std::vector<void *> ptrs;
+    explicit Scratch(hipStream_t st) : s(st) {}
+    ~Scratch() { for (void *p : ptrs) dev_free(p, s); }
+    void *get(size_t bytes) {
+        void *p = dev_alloc(bytes, s);
+        if (p) ptrs.push_back(p);
+        return p;
+    }
+    Scratch(const Scratch &) = delete;
+    Scratch &operator=(const Scratch &) = delete;
+};
+
+// ---------------------------------------------------------------- handle
+constexpr int CSR_TILE = 2048;        // entries per CSR work tile
+constexpr int COO_TILE = 2048;        // entries per COO work tile
+
+enum CsrKernel : int32_t { CSR_K_VECTOR = 0, CSR_K_TILED = 1 };
+
+}  // namespace mo
+
+struct mo_matrix {
+    mo_format fmt = MO_CSR;
+    mo_dtype dtype = MO_F64;
+    int64_t m = 0, n = 0, nnz = 0, ld = 0;
+    // DIA part
+    int64_t nd = 0;
+    int32_t *dia_off = nullptr;
+    void *dia_val = nullptr;
+    // ELL part
+    int64_t k = 0;
+    int32_t *ell_col = nullptr;
+    void *ell_val = nullptr;
+    // COO part
+    int64_t nnz_coo = 0;
+    int32_t *coo_row = nullptr, *coo_col = nullptr;
+    void *coo_val = nullptr;
+    // CSR part (borrowed for MO_CSR, owned for MO_HDC)
+    int64_t nnz_csr = 0;
+    const int32_t *csr_row_ptr = nullptr, *csr_col = nullptr;
+    const void *csr_val = nullptr;
+    // launch data derived at conversion time (not part of the format)
+    int32_t csr_lanes = 1;            // lanes per row of the vector CSR kernel
+    int64_t csr_max_row = 0;
+    int64_t coo_tiles = 0;
+    int32_t *coo_carry_row = nullptr; // one per COO tile
+    void *coo_carry_val = nullptr;
+    // everything this handle owns
+    std::vector<void *> owned;
+    hipStream_t home = nullptr;
+};
+
+namespace mo {
+
+// ---------------------------------------------------------------- analysis (features.hip)
+struct Analysis {
+    int64_t max_row = 0, min_row = 0;
+    uint64_t sum_sq = 0;
+    int64_t n_diag = 0, n_true = 0;
+    uint32_t *hist = nullptr;  // device, m + n - 1 counters (only when requested); owned by the Scratch passed in
+};
+
+// Validates the CSR arrays and gathers the row statistics; with want_hist also the per-diagonal counts and the
+// two diagonal features.  Synchronises the stream.
+mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis *out, Scratch &scratch, hipStream_t s);
+
+// ---------------------------------------------------------------- conversions (convert.hip)
+mo_status convert_impl(const mo_csr &a, mo_format fmt, const mo_params &p, const Analysis &an, mo_matrix **out, hipStream_t s);
+mo_status check_csr_args(const mo_csr *a);
+mo_status check_params(const mo_params *in, mo_params *out);
+// exact integer feasibility of a DIA / ELL slab
+bool slab_feasible(int64_t width, int64_t m, int64_t nnz, const mo_params &p);
+
+// ---------------------------------------------------------------- scans (scan.hip)
+// out[i] = sum_{j<i} in[j] for i in [0, n]; out has n + 1 entries (out[n] = total).  tmp: >= scan_tmp_bytes(n).
+size_t scan_tmp_bytes(int64_t n);
+mo_status exclusive_scan_i32(const int32_t *in, int32_t *out, int64_t n, void *tmp, hipStream_t s);
+
+// ---------------------------------------------------------------- SpMV launchers (spmv_*.hip)
+mo_status spmv_csr(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s);
+mo_status spmv_coo(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s);
+mo_status spmv_dia(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+mo_status spmv_ell(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s);
+
+inline size_t dtype_size(mo_dtype d) { return d == MO_F32 ? 4 : 8; }
+
+}  // namespace mo

@@ -1,0 +1,180 @@
+// COO SpMV (Section II-B: one (row, col, value) triple per stored entry).  The library always produces
+// (row, col)-sorted COO, so y[row] = sum over the run of equal rows.  The reduction is a segmented sum with a fixed
+// association order and no floating-point atomics, so results are bit-identical from run to run:
+//   1. every thread owns COO_STRIP consecutive entries, loads them with wide loads, gathers x and reduces the runs
+//      inside its strip in registers;
+//   2. runs that cross strips are finished through a small LDS table by the thread that holds the head of the run;
+//   3. a run that crosses a tile boundary leaves its continuation in a per-tile carry slot, added by k_coo_fixup.
+// Exactly one thread of the whole grid writes y[row] in step 1/2, and one thread adds the carries in step 3.
+#include "dev_common.hpp"
+#include "mo_internal.hpp"
+
+namespace mo {
+
+constexpr int COO_B = 256;
+constexpr int COO_STRIP = COO_TILE / COO_B;   // 8 entries per thread
+static_assert(COO_STRIP == 8, "strip loads below are written for 8 entries per thread");
+
+template <typename T>
+__global__ void k_zero(T *__restrict__ p, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = (T)0;
+}
+
+template <typename T> struct Vec2;
+template <> struct Vec2<double> { using type = double2; };
+template <> struct Vec2<float> { using type = float2; };
+
+template <typename T, bool ACC>
+__global__ __launch_bounds__(COO_B) void k_coo_tile(const int32_t *__restrict__ row, const int32_t *__restrict__ col,
+                                                     const T *__restrict__ val, int64_t nnz, const T *__restrict__ x,
+                                                     T *__restrict__ y, int32_t *__restrict__ carry_row, T *__restrict__ carry_val)
+{
+    __shared__ int s_first[COO_B + 1];
+    __shared__ int s_last[COO_B];
+    __shared__ int s_closed[COO_B];
+    __shared__ T s_lead[COO_B];
+
+    const int64_t tile = xcd_block(blockIdx.x, gridDim.x);
+    const int64_t base = tile * COO_TILE;
+    const int t = threadIdx.x;
+    const int64_t p0 = base + (int64_t)t * COO_STRIP;
+
+    int r[COO_STRIP];
+    T pr[COO_STRIP];
+    if (p0 + COO_STRIP <= nnz) {
+        const int4 ra = *reinterpret_cast<const int4 *>(row + p0), rb = *reinterpret_cast<const int4 *>(row + p0 + 4);
+        const int4 ca = *reinterpret_cast<const int4 *>(col + p0), cb = *reinterpret_cast<const int4 *>(col + p0 + 4);
+        using V2 = typename Vec2<T>::type;
+        V2 v[COO_STRIP / 2];
+#pragma unroll
+        for (int q = 0; q < COO_STRIP / 2; ++q) v[q] = *reinterpret_cast<const V2 *>(val + p0 + 2 * q);
+        r[0] = ra.x; r[1] = ra.y; r[2] = ra.z; r[3] = ra.w; r[4] = rb.x; r[5] = rb.y; r[6] = rb.z; r[7] = rb.w;
+        const int c[COO_STRIP] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
+        T xv[COO_STRIP];
+#pragma unroll
+        for (int q = 0; q < COO_STRIP; ++q) xv[q] = x[c[q]];
+#pragma unroll
+        for (int q = 0; q < COO_STRIP / 2; ++q) { pr[2 * q] = v[q].x * xv[2 * q]; pr[2 * q + 1] = v[q].y * xv[2 * q + 1]; }
+    } else {
+#pragma unroll
+        for (int q = 0; q < COO_STRIP; ++q) {
+            const int64_t p = p0 + q;
+            if (p < nnz) { r[q] = row[p]; pr[q] = val[p] * x[col[p]]; }
+            else { r[q] = -1; pr[q] = (T)0; }
+        }
+    }
+
+    // runs inside the strip
+    int cur = r[0];
+    T acc = pr[0];
+    bool leading = true, lead_closed = false, has_tail = false;
+    T lead_sum = (T)0;
+#pragma unroll
+    for (int q = 1; q < COO_STRIP; ++q) {
+        if (r[q] == cur) {
+            acc += pr[q];
+        } else {
+            if (leading) { lead_sum = acc; lead_closed = true; leading = false; }
+            else if (cur >= 0) { if (ACC) y[cur] += acc; else y[cur] = acc; }   // a run that starts and ends in this strip
+            cur = r[q];
+            acc = pr[q];
+        }
+    }
+    if (leading) lead_sum = acc; else has_tail = true;
+    const int tail_row = cur;
+    const T tail_sum = acc;
+
+    s_first[t] = r[0];
+    s_last[t] = r[COO_STRIP - 1];
+    s_closed[t] = lead_closed ? 1 : 0;
+    s_lead[t] = lead_sum;
+    if (t == 0) s_first[COO_B] = -2;
+    __syncthreads();
+
+    // the run that reaches the end of this strip and started inside it
+    if (has_tail && tail_row >= 0) {
+        T total = tail_sum;
+        for (int u = t + 1; s_first[u] == tail_row; ++u) {
+            total += s_lead[u];
+            if (s_closed[u]) break;
+        }
+        if (ACC) y[tail_row] += total; else y[tail_row] = total;
+    }
+    // the run at the start of this strip, when its head is here (or, for thread 0, possibly in an earlier tile)
+    const int before = (t == 0) ? (base > 0 ? row[base - 1] : -1) : s_last[t - 1];
+    const bool head_here = r[0] != before;
+    if (r[0] >= 0 && (head_here || t == 0)) {
+        T total = lead_sum;
+        if (!lead_closed) {
+            for (int u = t + 1; s_first[u] == r[0]; ++u) {
+                total += s_lead[u];
+                if (s_closed[u]) break;
+            }
+        }
+        if (head_here) { if (ACC) y[r[0]] += total; else y[r[0]] = total; }
+        else { carry_val[tile] = total; }
+    }
+    if (t == 0) carry_row[tile] = (r[0] >= 0 && !head_here) ? r[0] : -1;
+}
+
+// Adds the carries: a chain of consecutive tiles with the same carry row is summed in tile order by the thread of
+// its first tile.
+template <typename T>
+__global__ void k_coo_fixup(const int32_t *__restrict__ carry_row, const T *__restrict__ carry_val, int64_t tiles, T *__restrict__ y)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= tiles) return;
+    const int r = carry_row[k];
+    if (r < 0) return;
+    if (k > 0 && carry_row[k - 1] == r) return;
+    T total = carry_val[k];
+    for (int64_t u = k + 1; u < tiles && carry_row[u] == r; ++u) total += carry_val[u];
+    y[r] += total;
+}
+
+template <typename T>
+static mo_status zero_typed(void *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return MO_OK;
+    int64_t g = (n + 2047) / 2048;
+    if (g > 4096) g = 4096;
+    hipLaunchKernelGGL(k_zero<T>, dim3((unsigned)g), dim3(256), 0, s, (T *)p, n);
+    MO_LAUNCH_CHECK();
+    return MO_OK;
+}
+
+mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s)
+{
+    return dt == MO_F32 ? zero_typed<float>(p, n_elems, s) : zero_typed<double>(p, n_elems, s);
+}
+
+template <typename T>
+static mo_status coo_typed(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s)
+{
+    if (!accumulate) MO_TRY(zero_typed<T>(y, a.m, s));
+    if (a.nnz_coo <= 0) return MO_OK;
+    const unsigned tiles = (unsigned)a.coo_tiles;
+    if (accumulate)
+        hipLaunchKernelGGL((k_coo_tile<T, true>), dim3(tiles), dim3(COO_B), 0, s, a.coo_row, a.coo_col, (const T *)a.coo_val,
+                           a.nnz_coo, (const T *)x, (T *)y, a.coo_carry_row, (T *)a.coo_carry_val);
+    else
+        hipLaunchKernelGGL((k_coo_tile<T, false>), dim3(tiles), dim3(COO_B), 0, s, a.coo_row, a.coo_col, (const T *)a.coo_val,
+                           a.nnz_coo, (const T *)x, (T *)y, a.coo_carry_row, (T *)a.coo_carry_val);
+    MO_LAUNCH_CHECK();
+    if (tiles > 1) {
+        hipLaunchKernelGGL(k_coo_fixup<T>, dim3((tiles + 255) / 256), dim3(256), 0, s, a.coo_carry_row, (const T *)a.coo_carry_val,
+                           (int64_t)tiles, (T *)y);
+        MO_LAUNCH_CHECK();
+    }
+    return MO_OK;
+}
+
+mo_status spmv_coo(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s)
+{
+    return a.dtype == MO_F32 ? coo_typed<float>(a, x, y, accumulate, s) : coo_typed<double>(a, x, y, accumulate, s);
+}
+
+}  // namespace mo

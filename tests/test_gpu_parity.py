@@ -1,0 +1,269 @@
+"""GPU parity: HIP library vs CPU oracle through the C ABI, element by element, on seeded inputs that span
+several tiles and a ragged tail; plus the edge cases of every call."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref
+from paper_2303_05098_amd import mo, synth
+from tests.gpu_util import TOL, gpu_spmv, oracle_inputs, try_convert, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def small_cases():
+    """(name, m, n, row_ptr, col_idx, val) — sizes the oracle finishes in seconds."""
+    out = [("c1", *synth.config(1)),
+           ("c2s", *synth.config(2, 0.19)),          # 24^3 = 13824 rows, 27-point
+           ("c3s", *synth.config(3, 1 / 64)),        # 16384 rows lognormal, long rows cross tiles
+           ("c4s", *synth.config(4, 1 / 64)),        # 65536 rows banded + scatter
+           ("uni", *synth.uniform_rows(5000, 3, 77)),
+           ("rect_wide", *synth.random_csr(300, 1000, 0.02, 5, 0.3)),
+           ("rect_tall", *synth.random_csr(1000, 130, 0.05, 6, 0.1)),
+           ("one_row", *synth.random_csr(1, 5000, 0.7, 7)),
+           ("one_col", *synth.random_csr(700, 1, 0.5, 8)),
+           ("dense", *synth.random_csr(70, 70, 1.1, 9)),
+           ("tiny", *synth.random_csr(3, 3, 0.5, 10))]
+    # empty matrix and a matrix whose only entries sit in the last row
+    out.append(("empty", 5, 7, np.zeros(6, np.int32), np.zeros(0, np.int32), np.zeros(0)))
+    out.append(("last_row", 4000, 4000, np.concatenate([np.zeros(4000, np.int32), [3]]).astype(np.int32),
+                np.array([0, 17, 3999], np.int32), np.array([1.0, -2.0, 0.5])))
+    # one very long row between short ones (crosses many COO/CSR tiles)
+    m, n, rp, ci, v = synth.uniform_rows(3000, 2, 12)
+    lens = np.diff(rp).astype(np.int64)
+    lens[1500] = 3000
+    rp2 = np.zeros(m + 1, np.int64)
+    np.cumsum(lens, out=rp2[1:])
+    ci2 = np.concatenate([ci[:rp[1500]], np.arange(3000, dtype=np.int32), ci[rp[1501]:]])
+    v2 = synth.uniform_pm1(13, 0, np.arange(ci2.shape[0]))
+    out.append(("long_row", m, n, rp2.astype(np.int32), ci2.astype(np.int32), v2))
+    return out
+
+
+CASES = small_cases()
+IDS = [c[0] for c in CASES]
+
+
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_features_bit_exact(case):
+    name, m, n, rp, ci, v = case
+    a = upload(m, n, rp, ci, v)
+    ti, tj, _ = ref.csr_to_triplets(rp, ci, v)
+    for td in ((1, 2), (1, 16)):
+        f, ints = mo.mo_features(a, dict(td_num=td[0], td_den=td[1]))
+        fo, io = ref.features(m, n, ti, tj, td)
+        assert f.tobytes() == fo.tobytes(), (f, fo)
+        assert ints == io
+
+
+def check_arrays(name, e, m, n, ti, tj, ta, params, hyb=(1, 3), td=(1, 2)):
+    fmt = e["fmt"]
+    if fmt == mo.MO_COO:
+        r, c, v = ref.to_coo(ti, tj, ta)
+        assert np.array_equal(e["coo_row"], r) and np.array_equal(e["coo_col"], c)
+        assert e["coo_val"].astype(np.float64).tobytes() == v.tobytes()
+    if fmt == mo.MO_DIA:
+        off, val = ref.to_dia(m, n, ti, tj, ta)
+        assert e["nd"] == off.shape[0] and np.array_equal(e["dia_off"], off)
+        assert e["dia_val"][:, :m].astype(np.float64).tobytes() == val.tobytes()
+    if fmt == mo.MO_ELL:
+        k, col, val = ref.to_ell(m, ti, tj, ta)
+        assert e["k"] == k
+        assert np.array_equal(e["ell_col"][:, :m], col)
+        assert e["ell_val"][:, :m].astype(np.float64).tobytes() == val.tobytes()
+    if fmt == mo.MO_HYB:
+        h = ref.to_hyb(m, ti, tj, ta, hyb)
+        assert e["k"] == h["k"] and e["nnz_coo"] == h["coo_row"].shape[0]
+        assert np.array_equal(e["ell_col"][:, :m], h["ell_col"])
+        assert e["ell_val"][:, :m].astype(np.float64).tobytes() == h["ell_val"].tobytes()
+        assert np.array_equal(e["coo_row"], h["coo_row"]) and np.array_equal(e["coo_col"], h["coo_col"])
+        assert e["coo_val"].astype(np.float64).tobytes() == h["coo_val"].tobytes()
+    if fmt == mo.MO_HDC:
+        h = ref.to_hdc(m, n, ti, tj, ta, td)
+        assert e["nd"] == h["dia_off"].shape[0] and np.array_equal(e["dia_off"], h["dia_off"])
+        assert e["dia_val"][:, :m].astype(np.float64).tobytes() == h["dia_val"].tobytes()
+        assert np.array_equal(e["csr_row_ptr"], h["csr_row_ptr"]) and np.array_equal(e["csr_col"], h["csr_col"])
+        assert e["csr_val"].astype(np.float64).tobytes() == h["csr_val"].tobytes()
+        assert e["nnz_csr"] == h["csr_col"].shape[0]
+    if fmt == mo.MO_CSR:
+        assert np.array_equal(e["csr_row_ptr"], rp_of(ti, m)) and np.array_equal(e["csr_col"], tj)
+
+
+def rp_of(ti, m):
+    rp = np.zeros(m + 1, np.int64)
+    np.cumsum(np.bincount(ti, minlength=m), out=rp[1:])
+    return rp.astype(np.int32)
+
+
+def oracle_feasible(fmt, m, n, ti, tj, max_fill=16):
+    nnz = ti.shape[0]
+    if fmt == mo.MO_DIA:
+        f, _ = ref.features(m, n, ti, tj)
+        return ref.feasible(int(f[8]) * m, nnz, max_fill)
+    if fmt == mo.MO_ELL:
+        return ref.feasible(ref.max_row(m, ti) * m, nnz, max_fill)
+    return True
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32], ids=["f64", "f32"])
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_convert_and_spmv(case, dtype):
+    name, m, n, rp, ci, v = case
+    a = upload(m, n, rp, ci, v, dtype)
+    x = synth.make_x(n, 3)
+    ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, dtype)
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, xo)
+    # a looser padding limit than the default so that DIA / ELL are exercised on more of the small cases
+    params = dict(max_fill=256)
+    ys = {}
+    for fmt in range(6):
+        h = try_convert(a, fmt, params)
+        assert (h is not None) == oracle_feasible(fmt, m, n, ti, tj, 256), mo.FORMAT_NAMES[fmt]
+        if h is None:
+            continue
+        e = h.export()
+        assert (e["m"], e["n"], e["nnz"], e["fmt"]) == (m, n, rp[-1], fmt)
+        check_arrays(name, e, m, n, ti, tj, ta, params)
+        y = gpu_spmv(h, x, m, dtype)
+        err, zeros_ok = ref.spmv_error(y, y_ref, mag)
+        assert err <= TOL[dtype], (mo.FORMAT_NAMES[fmt], err)
+        assert zeros_ok, mo.FORMAT_NAMES[fmt]
+        # bit-identical on a second run (no floating-point atomics anywhere)
+        assert gpu_spmv(h, x, m, dtype).tobytes() == y.tobytes()
+        ys[fmt] = y.astype(np.float64)
+        h.free()
+    for fmt in ys:
+        nz = mag > 0
+        if nz.any():
+            assert np.max(np.abs(ys[fmt][nz] - ys[mo.MO_CSR][nz]) / mag[nz]) <= 2 * TOL[dtype]
+
+
+@pytest.mark.parametrize("case", CASES, ids=IDS)
+def test_default_fill_limit_matches_oracle(case):
+    name, m, n, rp, ci, v = case
+    a = upload(m, n, rp, ci, v)
+    ti, tj, _ = ref.csr_to_triplets(rp, ci, v)
+    for fmt in (mo.MO_DIA, mo.MO_ELL):
+        h = try_convert(a, fmt)
+        assert (h is not None) == oracle_feasible(fmt, m, n, ti, tj), mo.FORMAT_NAMES[fmt]
+        if h is not None:
+            h.free()
+
+
+@pytest.mark.parametrize("params,hyb,td", [(dict(hyb_num=1, hyb_den=2, td_num=1, td_den=8), (1, 2), (1, 8)),
+                                            (dict(hyb_num=0, hyb_den=1, td_num=1, td_den=1), (0, 1), (1, 1)),
+                                            (dict(hyb_num=3, hyb_den=2, td_num=0, td_den=1), (3, 2), (0, 1))])
+@pytest.mark.parametrize("cname", ["c3s", "c4s", "rect_wide"])
+def test_hybrid_parameters(cname, params, hyb, td):
+    name, m, n, rp, ci, v = CASES[IDS.index(cname)]
+    a = upload(m, n, rp, ci, v)
+    ti, tj, ta = ref.csr_to_triplets(rp, ci, v)
+    x = synth.make_x(n, 4)
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, x)
+    for fmt in (mo.MO_HYB, mo.MO_HDC):
+        h = mo.mo_convert(a, fmt, params)
+        check_arrays(name, h.export(), m, n, ti, tj, ta, params, hyb, td)
+        err, zeros_ok = ref.spmv_error(gpu_spmv(h, x, m, np.float64), y_ref, mag)
+        assert err <= 1e-13 and zeros_ok
+        h.free()
+
+
+def test_c1_unit_vector_and_ones():
+    m, n, rp, ci, v = synth.config(1)
+    a = upload(m, n, rp, ci, v)
+    for fmt in range(6):
+        h = mo.mo_convert(a, fmt)
+        y = gpu_spmv(h, np.ones(n), m, np.float64)
+        r = np.arange(m)
+        nb = (r % 64 == 0).astype(int) + (r % 64 == 63) + (r // 64 == 0) + (r // 64 == 63)
+        assert np.array_equal(y, nb.astype(np.float64))
+        e = np.zeros(n)
+        e[1000] = 1.0
+        y = gpu_spmv(h, e, m, np.float64)
+        want = np.zeros(m)
+        want[[1000 - 64, 999, 1000, 1001, 1064]] = [-1, -1, 4, -1, -1]
+        assert np.array_equal(y, want)
+        h.free()
+
+
+def bad_csr(kind):
+    m, n, rp, ci, v = synth.random_csr(200, 150, 0.1, 21)
+    rp, ci = rp.copy(), ci.copy()
+    if kind == "rp0":
+        rp[0] = 1
+    elif kind == "rp_decreasing":
+        rp[50], rp[51] = rp[51] + 3, rp[50]
+    elif kind == "rp_last":
+        rp[-1] -= 1
+    elif kind == "rp_beyond":
+        rp[100] = rp[-1] + 1000
+    elif kind == "rp_negative":
+        rp[10] = -5
+    elif kind == "col_high":
+        ci[37] = n
+    elif kind == "col_negative":
+        ci[37] = -1
+    elif kind == "col_unsorted":
+        p = int(np.nonzero(np.diff(rp) >= 2)[0][0])
+        s = rp[p]
+        ci[s], ci[s + 1] = ci[s + 1], ci[s]
+    elif kind == "col_duplicate":
+        p = int(np.nonzero(np.diff(rp) >= 2)[0][0])
+        ci[rp[p] + 1] = ci[rp[p]]
+    elif kind == "long_row_unsorted":
+        m, n, rp, ci, v = synth.random_csr(4, 400, 0.9, 22)
+        ci = ci.copy()
+        ci[rp[2] + 200], ci[rp[2] + 201] = ci[rp[2] + 201], ci[rp[2] + 200]
+    return m, n, rp, ci, v
+
+
+@pytest.mark.parametrize("kind", ["rp0", "rp_decreasing", "rp_last", "rp_beyond", "rp_negative", "col_high", "col_negative",
+                                  "col_unsorted", "col_duplicate", "long_row_unsorted"])
+def test_invalid_csr_is_rejected(kind):
+    m, n, rp, ci, v = bad_csr(kind)
+    a = upload(m, n, rp, ci, v)
+    with pytest.raises(mo.MoError) as e:
+        mo.mo_features(a)
+    assert e.value.status == mo.MO_E_CSR_INVALID
+    for fmt in range(6):
+        with pytest.raises(mo.MoError) as e:
+            mo.mo_convert(a, fmt)
+        assert e.value.status == mo.MO_E_CSR_INVALID
+    with pytest.raises(mo.MoError) as e:
+        mo.mo_tune(a, reps=1, warmups=0)
+    assert e.value.status == mo.MO_E_CSR_INVALID
+
+
+@pytest.mark.parametrize("cname", ["c1", "c3s", "c4s", "empty"])
+def test_tune_bookkeeping(cname):
+    name, m, n, rp, ci, v = CASES[IDS.index(cname)]
+    a = upload(m, n, rp, ci, v)
+    ti, tj, _ = ref.csr_to_triplets(rp, ci, v)
+    best, ms, cv = mo.mo_tune(a, warmups=1, reps=3)
+    for fmt in range(6):
+        assert (not np.isnan(ms[fmt])) == oracle_feasible(fmt, m, n, ti, tj), mo.FORMAT_NAMES[fmt]
+        assert np.isnan(ms[fmt]) == np.isnan(cv[fmt])
+    assert best == ref.pick(ms) == mo.mo_pick(ms)
+    assert np.all(ms[~np.isnan(ms)] > 0)
+
+
+def test_other_stream_and_default_allocator():
+    m, n, rp, ci, v = synth.config(2, 0.1)
+    a = upload(m, n, rp, ci, v)
+    ti, tj, ta = ref.csr_to_triplets(rp, ci, v)
+    x = synth.make_x(n, 9)
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, x)
+    s = torch.cuda.Stream()
+    xd = torch.as_tensor(x).cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        for fmt in range(6):
+            h = mo.mo_convert(a, fmt, stream=s)
+            y = torch.empty(m, dtype=torch.float64, device="cuda")
+            mo.mo_spmv(h, xd, y, stream=s)
+            s.synchronize()
+            err, ok = ref.spmv_error(y.cpu().numpy(), y_ref, mag)
+            assert err <= 1e-13 and ok
+            h.free()
