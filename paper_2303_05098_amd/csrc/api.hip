@@ -139,10 +139,12 @@ mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
     case MO_ELL: return spmv_ell(*a, x, y, s);
     case MO_HYB:
         MO_TRY(spmv_ell(*a, x, y, s));
-        return spmv_coo(*a, x, y, true, s);
+        return a->nnz_coo > 0 ? spmv_coo(*a, x, y, true, s) : MO_OK;
     case MO_HDC:
+        if (a->nd == 0) return spmv_csr(*a, x, y, false, s);
+        if (a->csr_max_row <= HDC_FUSED_MAX_ROW) return spmv_hdc_fused(*a, x, y, s);
         MO_TRY(spmv_dia(*a, x, y, s));
-        return spmv_csr(*a, x, y, true, s);
+        return a->nnz_csr > 0 ? spmv_csr(*a, x, y, true, s) : MO_OK;
     }
     return MO_E_FORMAT;
 }

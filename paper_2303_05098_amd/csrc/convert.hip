@@ -8,6 +8,7 @@
 #include "mo_internal.hpp"
 
 #include <cmath>
+#include <cstdlib>
 #include <new>
 
 namespace mo {
@@ -282,12 +283,26 @@ struct Builder {
     mo_matrix *take() { mo_matrix *r = h; h = nullptr; return r; }
 };
 
-int pick_lanes(int64_t nnz, int64_t m)
+// Launch plan of a CSR part (MO_CSR itself, or the remainder of HDC).
+mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, int64_t max_row)
 {
+    mo_matrix *h = b.h;
+    h->csr_max_row = max_row;
     const double avg = m > 0 ? (double)nnz / (double)m : 0.0;
     int lanes = 2;
     while (lanes < 64 && (double)lanes < avg) lanes <<= 1;
-    return lanes;
+    h->csr_lanes = lanes;
+    // lanes per row: the rows of one tile (about CSR_TILE / avg) should fit one pass of 256 / g rows
+    int g = 1;
+    while (g < 16 && avg > 10.0 * g) g <<= 1;
+    h->csr_group = g;
+    h->csr_tiles = csr_tile_count(nnz, max_row, CSR_TILE);
+    if (h->csr_tiles > 0) {
+        h->csr_tile_rp = (int32_t *)b.own((size_t)(h->csr_tiles + 1) * 8);
+        if (b.failed) return MO_E_ALLOC;
+        MO_TRY(csr_build_tiles(row_ptr, m, nnz, h->csr_tiles, CSR_TILE, h->csr_tile_rp, b.s));
+    }
+    return MO_OK;
 }
 
 // Slot map for the DIA part: offsets (ascending) into h->dia_off, slot[] (m + n - 1 ints, scratch) for the fill.
@@ -321,6 +336,30 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         MO_LAUNCH_CHECK();
     }
     *slot_out = pos;
+    // launch plan for the LDS-staged SpMV kernel: needs the offsets on the host
+    if (nd > 0) {
+        std::vector<int32_t> hoff((size_t)nd);
+        MO_HIP(hipMemcpyAsync(hoff.data(), h->dia_off, (size_t)nd * 4, hipMemcpyDeviceToHost, s));
+        MO_HIP(hipStreamSynchronize(s));
+        int block = 512, rows = sizeof(T) == 4 ? 2 : 1;
+        if (const char *e = getenv("MO_DIA_BLOCK")) block = atoi(e);
+        if (const char *e = getenv("MO_DIA_ROWS")) rows = atoi(e) == 2 ? 2 : 1;
+        std::vector<int32_t> xpos, cl;
+        int64_t elems = 0;
+        if ((block == 256 || block == 512) &&
+            plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems)) {
+            h->dia_xpos = (int32_t *)b.own(xpos.size() * 4);
+            h->dia_clusters = (int32_t *)b.own(cl.size() * 4);
+            if (b.failed) return MO_E_ALLOC;
+            MO_HIP(hipMemcpyAsync(h->dia_xpos, xpos.data(), xpos.size() * 4, hipMemcpyHostToDevice, s));
+            MO_HIP(hipMemcpyAsync(h->dia_clusters, cl.data(), cl.size() * 4, hipMemcpyHostToDevice, s));
+            MO_HIP(hipStreamSynchronize(s));   // the host vectors go out of scope
+            h->dia_block = block;
+            h->dia_rows = rows;
+            h->dia_ncl = (int32_t)(cl.size() / 3);
+            h->dia_lds_elems = elems;
+        }
+    }
     return MO_OK;
 }
 
@@ -348,8 +387,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
     switch (fmt) {
     case MO_CSR: {
         h->csr_row_ptr = a.row_ptr; h->csr_col = a.col_idx; h->csr_val = a.val; h->nnz_csr = a.nnz;
-        h->csr_lanes = pick_lanes(a.nnz, a.m);
-        h->csr_max_row = an.max_row;
+        MO_TRY(plan_csr(b, a.row_ptr, a.m, a.nnz, an.max_row));
         break;
     }
     case MO_COO: {
@@ -445,8 +483,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
                            (int32_t *)nullptr, rest_ptr, rcol, rval);
         MO_LAUNCH_CHECK();
         h->csr_row_ptr = rest_ptr; h->csr_col = rcol; h->csr_val = rval;
-        h->csr_lanes = pick_lanes(total, a.m);
-        h->csr_max_row = an.max_row;
+        MO_TRY(plan_csr(b, rest_ptr, a.m, total, an.max_row));
         break;
     }
     default:

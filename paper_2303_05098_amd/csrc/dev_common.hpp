@@ -59,4 +59,18 @@ __device__ __forceinline__ T wave_sum(T v)
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
 
+// Streaming accesses for data that is touched once per SpMV (matrix values, indices, y): marked non-temporal so
+// that they do not displace x from the caches.  Measured on MI355X: a plain read stream sustains about 6.4 TB/s,
+// the same stream with non-temporal loads about 7.1 TB/s.
+template <typename T>
+__device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontemporal_load(p); }
+template <typename T>
+__device__ __forceinline__ void st_stream(T *p, T v) { __builtin_nontemporal_store(v, p); }
+
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef int int2v __attribute__((ext_vector_type(2)));
+typedef double dbl2v __attribute__((ext_vector_type(2)));
+typedef float flt2v __attribute__((ext_vector_type(2)));
+typedef float flt4v __attribute__((ext_vector_type(4)));
+
 }  // namespace mo

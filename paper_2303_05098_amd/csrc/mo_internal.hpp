@@ -52,9 +52,9 @@ struct Scratch {
 
 // ---------------------------------------------------------------- handle
 constexpr int CSR_TILE = 2048;        // entries per CSR work tile
+constexpr int CSR_TILE_SLACK = 256;   // longest row the tiled CSR kernel accepts (LDS holds CSR_TILE + slack entries)
 constexpr int COO_TILE = 2048;        // entries per COO work tile
 
-enum CsrKernel : int32_t { CSR_K_VECTOR = 0, CSR_K_TILED = 1 };
 
 }  // namespace mo
 
@@ -66,6 +66,12 @@ struct mo_matrix {
     int64_t nd = 0;
     int32_t *dia_off = nullptr;
     void *dia_val = nullptr;
+    // x windows the DIA kernels stage in LDS (launch data, derived from dia_off at conversion time)
+    int32_t dia_block = 0;            // threads per block of the LDS kernel; 0 = direct kernel
+    int32_t dia_rows = 1;             // rows per thread of the LDS kernel
+    int32_t dia_ncl = 0;
+    int64_t dia_lds_elems = 0;
+    int32_t *dia_xpos = nullptr, *dia_clusters = nullptr;
     // ELL part
     int64_t k = 0;
     int32_t *ell_col = nullptr;
@@ -81,6 +87,9 @@ struct mo_matrix {
     // launch data derived at conversion time (not part of the format)
     int32_t csr_lanes = 1;            // lanes per row of the vector CSR kernel
     int64_t csr_max_row = 0;
+    int64_t csr_tiles = 0;            // > 0: tiled CSR kernel with csr_group lanes per row
+    int32_t csr_group = 1;
+    int32_t *csr_tile_rp = nullptr;   // (first row, its row_ptr) per tile, tiles + 1 pairs
     int64_t coo_tiles = 0;
     int32_t *coo_carry_row = nullptr; // one per COO tile
     void *coo_carry_val = nullptr;
@@ -120,7 +129,14 @@ mo_status spmv_csr(const mo_matrix &a, const void *x, void *y, bool accumulate, 
 mo_status spmv_coo(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s);
 mo_status spmv_dia(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 mo_status spmv_ell(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+mo_status spmv_hdc_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_elems, std::vector<int32_t> *xpos,
+                       std::vector<int32_t> *clusters, int64_t *total_elems);
+constexpr int64_t DIA_LDS_BYTES = 48 * 1024;  // LDS budget for staged x windows per block
+constexpr int64_t HDC_FUSED_MAX_ROW = 64;   // longest row for which HDC runs as one fused kernel
 mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s);
+int64_t csr_tile_count(int64_t nnz, int64_t max_row, int tile_size);
+mo_status csr_build_tiles(const int32_t *row_ptr, int64_t m, int64_t nnz, int64_t ntiles, int tile_size, int32_t *tile_rp, hipStream_t s);
 
 inline size_t dtype_size(mo_dtype d) { return d == MO_F32 ? 4 : 8; }
 

@@ -20,10 +20,10 @@ __global__ __launch_bounds__(ELL_B) void k_ell(const int32_t *__restrict__ col, 
     const T *v = val + row;
 #pragma unroll 4
     for (int64_t s = 0; s < K; ++s) {
-        const int32_t j = c[s * ld];
-        if (j >= 0) sum += v[s * ld] * x[j];
+        const int32_t j = ld_stream(c + s * ld);
+        if (j >= 0) sum += ld_stream(v + s * ld) * x[j];
     }
-    y[row] = sum;
+    st_stream(y + row, sum);
 }
 
 template <typename T>
