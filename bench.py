@@ -24,6 +24,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per SpMV launch from the committed rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scale
+# factors a plain 1 GiB copy gives; see profiles/spmv_all_formats_stencil27_128_f64.md).  Keyed by (config, dtype, format).
+MEASURED_TRAFFIC = {
+    (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 732.3e6, (2, "f64", "ELL"): 710.2e6,
+    (2, "f64", "COO"): 951.7e6,
+}
 REPS = 1000
 MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_tree.bin")
 
@@ -53,6 +59,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="2 = 27-point stencil 128^3 (default), 4 = banded+scatter, 3 = lognormal")
     ap.add_argument("--dtype", default="f64", choices=["f64", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB -> 1 GiB device copy five times, as the known-size reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md); run with --gpus 1", file=sys.stderr)
@@ -79,6 +87,15 @@ def main() -> int:
     y = torch.empty(m, dtype=x.dtype, device="cuda")
     stream = torch.cuda.current_stream()
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731  (events on the stream the kernels are launched on)
+
+    if args.calibrate:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     # ---- one-off rows of the path: features, conversions, per-format SpMV rate ------------------------------------
     t0 = time.perf_counter()
@@ -165,7 +182,7 @@ def main() -> int:
     achieved = alg / (spmv_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": {2: "k_dia_lds", 5: "k_dia_lds(HDC)", 1: "k_csr_tiled", 3: "k_ell", 0: "k_coo_tile", 4: "k_ell+k_coo_tile"}[chosen],
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes_per_launch": alg, "us_per_launch": round(spmv_ms * 1e3, 2)}
+                "traffic": MEASURED_TRAFFIC.get((args.config, args.dtype, mo.FORMAT_NAMES[chosen])), "algorithmic_bytes_per_launch": alg, "us_per_launch": round(spmv_ms * 1e3, 2)}
 
     # ---- run-first tuner (timed once; conversions included in its wall time) -------------------------------------------
     t0 = time.perf_counter()
