@@ -39,6 +39,45 @@ __device__ __forceinline__ void walk_rows(bool rv, int64_t row, int64_t lo, int6
     }
 }
 
+// Same traversal, but the entries of the wave's rows (one contiguous run of the CSR arrays) are first streamed into
+// the wave's own LDS region with coalesced loads, WCAP entries at a time, and the lanes then pick their rows' entries
+// out of LDS: f(row, p, s, col, val).  Lane-per-row reads straight from global memory touch one cache line per lane
+// and step; this way every line is read once.  Rows longer than SHORT_ROW are left to the cooperative loop, which
+// reads global memory with consecutive lanes anyway.  No block barrier: a wave's LDS accesses execute in order.
+constexpr int WCAP = 1024;
+
+template <typename T, class F>
+__device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo, int64_t hi, const int32_t *__restrict__ col_idx,
+                                              const T *__restrict__ val, int32_t *s_col, T *s_val, F f)
+{
+    const int lane = lane_id();
+    const int64_t len = hi - lo;
+    const bool is_short = rv && len <= SHORT_ROW;
+    const int64_t wb = wave_min(rv ? lo : (int64_t)0x7fffffffffffll);
+    const int64_t we = wave_max(rv ? hi : (int64_t)0);
+    for (int64_t c0 = wb; c0 < we; c0 += WCAP) {
+        const int64_t c1 = c0 + WCAP < we ? c0 + WCAP : we;
+        for (int i = lane; i < (int)(c1 - c0); i += WAVE) {
+            s_col[i] = ld_stream(col_idx + c0 + i);
+            s_val[i] = ld_stream(val + c0 + i);
+        }
+        const int64_t a = lo > c0 ? lo : c0, b = hi < c1 ? hi : c1;
+        const int cnt = (is_short && b > a) ? (int)(b - a) : 0;
+        const int wmax = wave_max(cnt);
+        for (int k = 0; k < wmax; ++k)
+            if (k < cnt) f(row, a + k, a + k - lo, s_col[a + k - c0], s_val[a + k - c0]);
+    }
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+    while (longmask) {
+        const int l = __ffsll((unsigned long long)longmask) - 1;
+        longmask &= longmask - 1;
+        const int64_t r = __shfl(row, l, WAVE);
+        const int64_t rlo = __shfl(lo, l, WAVE);
+        const int64_t rhi = __shfl(hi, l, WAVE);
+        for (int64_t q = rlo + lane; q < rhi; q += WAVE) f(r, q, q - rlo, col_idx[q], val[q]);
+    }
+}
+
 __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -55,19 +94,57 @@ __global__ void k_fill_val(T *p, int64_t n)
 }
 
 // ------------------------------------------------------------------ COO
+// Entry-parallel: a block copies a tile of COO_CT consecutive entries with coalesced loads and stores and attaches
+// the row index to each.  The rows that intersect the tile are found by two binary searches in row_ptr; their
+// row_ptr slice is staged in LDS and every entry searches that slice (global row_ptr when the slice is too long,
+// i.e. when the tile spans many empty rows).
+constexpr int COO_CT = 2048;
+
+__device__ __forceinline__ int64_t row_of_entry(const int32_t *__restrict__ row_ptr, int64_t lo, int64_t hi, int64_t p)
+{
+    // largest r in [lo, hi] with row_ptr[r] <= p  (row_ptr[lo] <= p is given)
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if ((int64_t)row_ptr[mid] <= p) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
 template <typename T>
 __global__ __launch_bounds__(CB) void k_csr_to_coo(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-                                                    const T *__restrict__ val, int64_t m, int32_t *__restrict__ orow,
+                                                    const T *__restrict__ val, int64_t m, int64_t nnz, int32_t *__restrict__ orow,
                                                     int32_t *__restrict__ ocol, T *__restrict__ oval)
 {
-    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
-    const bool rv = row < m;
-    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
-    walk_rows(rv, row, lo, hi, [&](int64_t r, int64_t p, int64_t) {
+    __shared__ int32_t rps[COO_CT + 2];
+    __shared__ int64_t s_r[2];
+    const int64_t t0 = (int64_t)blockIdx.x * COO_CT;
+    const int64_t t1 = t0 + COO_CT < nnz ? t0 + COO_CT : nnz;
+    if (threadIdx.x == 0) s_r[0] = row_of_entry(row_ptr, 0, m - 1, t0);
+    if (threadIdx.x == WAVE) s_r[1] = row_of_entry(row_ptr, 0, m - 1, t1 - 1);
+    __syncthreads();
+    const int64_t r0 = s_r[0], r1 = s_r[1];
+    const int64_t nr = r1 - r0 + 1;
+    const bool staged = nr <= COO_CT + 1;
+    if (staged) {
+        for (int i = threadIdx.x; i < (int)nr; i += CB) rps[i] = row_ptr[r0 + i];
+        __syncthreads();
+    }
+    for (int64_t p = t0 + threadIdx.x; p < t1; p += CB) {
+        int64_t r;
+        if (staged) {
+            int lo = 0, hi = (int)nr - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if ((int64_t)rps[mid] <= p) lo = mid; else hi = mid - 1;
+            }
+            r = r0 + lo;
+        } else {
+            r = row_of_entry(row_ptr, r0, r1, p);
+        }
         orow[p] = (int32_t)r;
-        ocol[p] = col_idx[p];
-        oval[p] = val[p];
-    });
+        ocol[p] = ld_stream(col_idx + p);
+        oval[p] = ld_stream(val + p);
+    }
 }
 
 // ------------------------------------------------------------------ diagonal selection
@@ -97,12 +174,15 @@ __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row
                                                   const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
                                                   int64_t ld, T *__restrict__ dval)
 {
+    __shared__ int32_t s_col[(CB / WAVE) * WCAP];
+    __shared__ T s_val[(CB / WAVE) * WCAP];
     const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
     const bool rv = row < m;
     const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
-    walk_rows(rv, row, lo, hi, [&](int64_t r, int64_t p, int64_t) {
-        const int k = slot[(int64_t)col_idx[p] - r + (m - 1)];
-        if (k >= 0) dval[(int64_t)k * ld + r] = val[p];
+    const int w = threadIdx.x / WAVE;
+    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP, [&](int64_t r, int64_t, int64_t, int32_t c, T v) {
+        const int k = slot[(int64_t)c - r + (m - 1)];
+        if (k >= 0) dval[(int64_t)k * ld + r] = v;
     });
 }
 
@@ -125,35 +205,56 @@ __global__ __launch_bounds__(CB) void k_fill_ell(const int32_t *__restrict__ row
             eval[s * ld + row] = (T)0;
         }
     }
-    walk_rows(rv, row, lo, hi, [&](int64_t r, int64_t p, int64_t s) {
+    __shared__ int32_t s_col[(CB / WAVE) * WCAP];
+    __shared__ T s_val[(CB / WAVE) * WCAP];
+    const int w = threadIdx.x / WAVE;
+    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP, [&](int64_t r, int64_t, int64_t s, int32_t c, T v) {
         if (s < K) {
-            ecol[s * ld + r] = col_idx[p];
-            eval[s * ld + r] = val[p];
+            ecol[s * ld + r] = c;
+            eval[s * ld + r] = v;
         } else {
             const int64_t q = (int64_t)coo_ptr[r] + (s - K);
             crow[q] = (int32_t)r;
-            ccol[q] = col_idx[p];
-            cval[q] = val[p];
+            ccol[q] = c;
+            cval[q] = v;
         }
     });
 }
 
-// Histogram of row lengths (equal lengths inside a wave are merged before the atomic) and, per row, the number of
-// entries beyond K that spill into the COO part when K >= 0.
-__global__ __launch_bounds__(CB) void k_len_hist(const int32_t *__restrict__ row_ptr, int64_t m, uint32_t *__restrict__ lhist)
+// Histogram of row lengths.  Regular matrices put every row on the same counter, and same-address atomics serialise
+// in L2, so counts are merged inside the wave (ballot), then inside the block (LDS histogram for lengths below
+// LEN_LDS, flushed once per block); a block owns a contiguous run of rows.
+constexpr int LEN_LDS = 2048;
+
+__global__ __launch_bounds__(CB) void k_len_hist(const int32_t *__restrict__ row_ptr, int64_t m, int64_t rows_per_block,
+                                                  uint32_t *__restrict__ lhist)
 {
-    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
-    const bool rv = row < m;
-    const int key = rv ? (row_ptr[row + 1] - row_ptr[row]) : -1;
+    __shared__ uint32_t sh[LEN_LDS];
+    for (int i = threadIdx.x; i < LEN_LDS; i += CB) sh[i] = 0u;
+    __syncthreads();
     const int lane = lane_id();
-    uint64_t todo = ballot64(rv);
-    while (todo) {
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const int lkey = __shfl(key, leader, WAVE);
-        const uint64_t same = ballot64(rv && key == lkey) & todo;
-        if (lane == leader) atomicAdd(&lhist[lkey], (uint32_t)__popcll(same));
-        todo &= ~same;
+    const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
+    int64_t row_end = row_begin + rows_per_block;
+    row_end = row_end < m ? row_end : m;
+    for (int64_t base = row_begin; base < row_end; base += CB) {
+        const int64_t row = base + threadIdx.x;
+        const bool rv = row < row_end;
+        const int key = rv ? (row_ptr[row + 1] - row_ptr[row]) : -1;
+        uint64_t todo = ballot64(rv);
+        while (todo) {
+            const int leader = __ffsll((unsigned long long)todo) - 1;
+            const int lkey = __shfl(key, leader, WAVE);
+            const uint64_t same = ballot64(rv && key == lkey) & todo;
+            if (lane == leader) {
+                if (lkey < LEN_LDS) atomicAdd(&sh[lkey], (uint32_t)__popcll(same));
+                else atomicAdd(&lhist[lkey], (uint32_t)__popcll(same));
+            }
+            todo &= ~same;
+        }
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < LEN_LDS; i += CB)
+        if (sh[i]) atomicAdd(&lhist[i], sh[i]);
 }
 
 __global__ __launch_bounds__(CB) void k_surplus(const int32_t *__restrict__ row_ptr, int64_t m, int64_t K, int32_t *__restrict__ cnt)
@@ -398,9 +499,11 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         h->coo_val = b.own(e * sizeof(T));
         setup_coo_tiles(b, sizeof(T));
         if (b.failed) return MO_E_ALLOC;
-        hipLaunchKernelGGL(k_csr_to_coo<T>, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, h->coo_row,
-                           h->coo_col, (T *)h->coo_val);
-        MO_LAUNCH_CHECK();
+        if (a.nnz > 0) {
+            hipLaunchKernelGGL(k_csr_to_coo<T>, dim3((unsigned)((a.nnz + COO_CT - 1) / COO_CT)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval,
+                               a.m, a.nnz, h->coo_row, h->coo_col, (T *)h->coo_val);
+            MO_LAUNCH_CHECK();
+        }
         break;
     }
     case MO_DIA: {
@@ -422,7 +525,9 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
             if (!lhist) return MO_E_ALLOC;
             hipLaunchKernelGGL(k_fill_i32, dim3(fill_grid(nh)), dim3(CB), 0, s, (int32_t *)lhist, nh, 0);
             MO_LAUNCH_CHECK();
-            hipLaunchKernelGGL(k_len_hist, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.m, lhist);
+            int64_t rpb = (a.m + 1023) / 1024;                 // at most 1024 blocks, each a multiple of the block size
+            rpb = ((rpb + CB - 1) / CB) * CB;
+            hipLaunchKernelGGL(k_len_hist, dim3((unsigned)((a.m + rpb - 1) / rpb)), dim3(CB), 0, s, a.row_ptr, a.m, rpb, lhist);
             MO_LAUNCH_CHECK();
             std::vector<uint32_t> hh((size_t)nh);
             MO_HIP(hipMemcpyAsync(hh.data(), lhist, (size_t)nh * 4, hipMemcpyDeviceToHost, s));

@@ -69,65 +69,122 @@ __global__ __launch_bounds__(FB) void k_row_stats(const int32_t *__restrict__ ro
     }
 }
 
-// F2: one pass over col_idx.  Lane l of a wave owns row r0 + l and walks its first SHORT_ROW entries, so for banded
-// and stencil matrices all lanes meet the same diagonal in the same step; equal keys are merged inside the wave
-// (ballot + one atomic per distinct key, at most two merge rounds, then plain atomics) before they reach memory.
-// The tail of a longer row is walked by the whole wave with coalesced loads; entries of one row lie on distinct
-// diagonals, so nothing is there to merge.
+// F2: one pass over col_idx.  Lane l of a wave owns row r0 + l and walks its entries (rows of at most SHORT_ROW
+// entries; the columns reach the lanes through LDS so that global loads stay coalesced), so for banded and stencil
+// matrices all lanes meet the same diagonal in the same step.  Counts are merged twice before they reach
+// memory: equal keys inside a wave by ballot (one update per distinct key, at most MERGE_ROUNDS rounds, then one
+// update per lane), and across the whole block in a small LDS hash table that is flushed once at the end.  A block
+// owns a contiguous run of rows, so a stencil's 27 diagonals cost 27 global atomics per block instead of one per
+// wave and step (same-address atomics serialise in L2: that was 1.6 ms on the 128^3 stencil).  Keys that find no
+// free slot within a few probes (matrices with many distinct diagonals) go straight to global memory.
+// A row longer than SHORT_ROW is walked by the whole wave with coalesced loads; entries of one row lie on distinct
+// diagonals, so they are counted directly.
+constexpr int HT_SIZE = 2048;     // LDS table slots (power of two)
+constexpr int HT_PROBES = 4;
+constexpr int MERGE_ROUNDS = 4;
+constexpr int FCAP = 1024;        // entries a wave stages in LDS at a time
+
+__device__ __forceinline__ void count_key(int key, uint32_t n, int *ht_key, uint32_t *ht_cnt, int *ht_full, uint32_t *__restrict__ hist)
+{
+    // once the table has overflowed, single counts skip it: they are almost surely keys that do not repeat
+    if (n == 1u && *ht_full) { atomicAdd(&hist[key], 1u); return; }
+    uint32_t h = ((uint32_t)key * 2654435761u) >> 21;   // 11 bits
+    for (int p = 0; p < HT_PROBES; ++p) {
+        const int s = (int)((h + p) & (HT_SIZE - 1));
+        const int old = atomicCAS(&ht_key[s], -1, key);
+        if (old == -1 || old == key) { atomicAdd(&ht_cnt[s], n); return; }
+    }
+    *ht_full = 1;
+    atomicAdd(&hist[key], n);
+}
+
 template <bool DO_HIST>
 __global__ __launch_bounds__(FB) void k_diag_hist(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-                                                   int64_t m, int64_t n, int64_t nnz, uint32_t *__restrict__ hist, Counters *ctr)
+                                                   int64_t m, int64_t n, int64_t nnz, int64_t rows_per_block,
+                                                   uint32_t *__restrict__ hist, Counters *ctr)
 {
-    const int64_t row = (int64_t)blockIdx.x * FB + threadIdx.x;
-    const bool rv = row < m;
-    int64_t lo = 0, hi = 0;
-    if (rv) {
-        lo = row_ptr[row]; hi = row_ptr[row + 1];
-        lo = lo < 0 ? 0 : (lo > nnz ? nnz : lo);
-        hi = hi < lo ? lo : (hi > nnz ? nnz : hi);
+    __shared__ int ht_key[DO_HIST ? HT_SIZE : 1];
+    __shared__ uint32_t ht_cnt[DO_HIST ? HT_SIZE : 1];
+    __shared__ int ht_full;
+    __shared__ int32_t s_col_all[(FB / WAVE) * FCAP];
+    int32_t *s_col = s_col_all + (threadIdx.x / WAVE) * FCAP;
+    if (threadIdx.x == 0) ht_full = 0;
+    if (DO_HIST) {
+        for (int i = threadIdx.x; i < HT_SIZE; i += FB) { ht_key[i] = -1; ht_cnt[i] = 0u; }
+        __syncthreads();
     }
-    const int64_t len = hi - lo;
-    const int short_len = (int)(len < SHORT_ROW ? len : SHORT_ROW);
-    const int wmax = wave_max(short_len);
     const int lane = lane_id();
     bool err = false;
-    int64_t prev = -1;
-    for (int k = 0; k < wmax; ++k) {
-        const bool act = k < short_len;
-        const int64_t c = act ? (int64_t)col_idx[lo + k] : 0;
-        const bool ok = act && c >= 0 && c < n && c > prev;
-        if (act && !ok) err = true;
-        if (act) prev = c;
-        if (DO_HIST) {
-            const int key = ok ? (int)(c - row + (m - 1)) : -1;
-            uint64_t todo = ballot64(ok);
-            int rounds = 0;
-            while (todo) {
-                if (rounds == 2) {
-                    if ((todo >> lane) & 1ull) atomicAdd(&hist[key], 1u);
-                    break;
+    const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
+    int64_t row_end = row_begin + rows_per_block;
+    row_end = row_end < m ? row_end : m;
+    for (int64_t base = row_begin; base < row_end; base += FB) {   // uniform trip count across the block
+        const int64_t row = base + threadIdx.x;
+        const bool rv = row < row_end;
+        int64_t lo = 0, hi = 0;
+        if (rv) {
+            lo = row_ptr[row]; hi = row_ptr[row + 1];
+            lo = lo < 0 ? 0 : (lo > nnz ? nnz : lo);
+            hi = hi < lo ? lo : (hi > nnz ? nnz : hi);
+        }
+        const int64_t len = hi - lo;
+        // The entries of the wave's 64 rows are one contiguous run: stream it through the wave's LDS region with
+        // coalesced loads (FCAP entries at a time) and let every lane pick the entries of its own row out of LDS.
+        const bool is_short = rv && len <= SHORT_ROW;
+        const int64_t wb = wave_min(rv ? lo : (int64_t)0x7fffffffffffll);
+        const int64_t we = wave_max(rv ? hi : (int64_t)0);
+        int64_t prev = -1;
+        for (int64_t c0 = wb; c0 < we; c0 += FCAP) {
+            const int64_t c1 = c0 + FCAP < we ? c0 + FCAP : we;
+            for (int i = lane; i < (int)(c1 - c0); i += WAVE) s_col[i] = ld_stream(col_idx + c0 + i);
+            const int64_t ea = lo > c0 ? lo : c0, eb = hi < c1 ? hi : c1;
+            const int cnt = (is_short && eb > ea) ? (int)(eb - ea) : 0;
+            const int wmax = wave_max(cnt);
+            for (int k = 0; k < wmax; ++k) {
+                const bool act = k < cnt;
+                const int64_t c = act ? (int64_t)s_col[ea + k - c0] : 0;
+                const bool ok = act && c >= 0 && c < n && c > prev;
+                if (act && !ok) err = true;
+                if (act) prev = c;
+                if (DO_HIST) {
+                    const int key = ok ? (int)(c - row + (m - 1)) : -1;
+                    uint64_t todo = ballot64(ok);
+                    int rounds = 0;
+                    while (todo) {
+                        if (rounds == MERGE_ROUNDS) {
+                            if ((todo >> lane) & 1ull) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
+                            break;
+                        }
+                        const int leader = __ffsll((unsigned long long)todo) - 1;
+                        const int lkey = __shfl(key, leader, WAVE);
+                        const uint64_t same = ballot64(ok && key == lkey) & todo;
+                        if (lane == leader) count_key(lkey, (uint32_t)__popcll(same), ht_key, ht_cnt, &ht_full, hist);
+                        todo &= ~same;
+                        ++rounds;
+                    }
                 }
-                const int leader = __ffsll((unsigned long long)todo) - 1;
-                const int lkey = __shfl(key, leader, WAVE);
-                const uint64_t same = ballot64(ok && key == lkey) & todo;
-                if (lane == leader) atomicAdd(&hist[lkey], (uint32_t)__popcll(same));
-                todo &= ~same;
-                ++rounds;
+            }
+        }
+        uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+        while (longmask) {
+            const int l = __ffsll((unsigned long long)longmask) - 1;
+            longmask &= longmask - 1;
+            const int64_t r = __shfl(row, l, WAVE);
+            const int64_t rlo = __shfl(lo, l, WAVE);
+            const int64_t rhi = __shfl(hi, l, WAVE);
+            for (int64_t q = rlo + lane; q < rhi; q += WAVE) {
+                const int64_t c = col_idx[q], cp = q > rlo ? (int64_t)col_idx[q - 1] : (int64_t)-1;
+                const bool ok = c >= 0 && c < n && c > cp;
+                if (!ok) err = true;
+                else if (DO_HIST) atomicAdd(&hist[c - r + (m - 1)], 1u);
             }
         }
     }
-    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
-    while (longmask) {
-        const int l = __ffsll((unsigned long long)longmask) - 1;
-        longmask &= longmask - 1;
-        const int64_t r = __shfl(row, l, WAVE);
-        const int64_t rlo = __shfl(lo, l, WAVE) + SHORT_ROW;
-        const int64_t rhi = __shfl(hi, l, WAVE);
-        for (int64_t q = rlo + lane; q < rhi; q += WAVE) {
-            const int64_t c = col_idx[q], cp = col_idx[q - 1];
-            const bool ok = c >= 0 && c < n && c > cp;
-            if (!ok) err = true;
-            else if (DO_HIST) atomicAdd(&hist[c - r + (m - 1)], 1u);
+    if (DO_HIST) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < HT_SIZE; i += FB) {
+            const uint32_t c = ht_cnt[i];
+            if (c) atomicAdd(&hist[ht_key[i]], c);
         }
     }
     if (err) atomicOr(&ctr->err, 2u);
@@ -147,9 +204,13 @@ __global__ __launch_bounds__(FB) void k_diag_count(const uint32_t *__restrict__ 
         }
     }
     c_nd = wave_sum(c_nd); c_td = wave_sum(c_td);
-    if (lane_id() == 0 && (c_nd | c_td)) {
-        atomicAdd(&ctr->n_diag, c_nd);
-        atomicAdd(&ctr->n_true, c_td);
+    __shared__ unsigned long long s_nd[FB / WAVE], s_td[FB / WAVE];
+    if (lane_id() == 0) { s_nd[threadIdx.x / WAVE] = c_nd; s_td[threadIdx.x / WAVE] = c_td; }
+    __syncthreads();
+    if (threadIdx.x == 0) {   // one pair of atomics per block: same-address atomics serialise
+        for (int w = 1; w < FB / WAVE; ++w) { c_nd += s_nd[w]; c_td += s_td[w]; }
+        if (c_nd) atomicAdd(&ctr->n_diag, c_nd);
+        if (c_td) atomicAdd(&ctr->n_true, c_td);
     }
 }
 
@@ -177,17 +238,23 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
         hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, 0u);
         MO_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(k_row_stats, dim3(grid_for(a.m, FB * 4, 2048)), dim3(FB), 0, s, a.row_ptr, a.m, a.nnz, ctr);
+    hipLaunchKernelGGL(k_row_stats, dim3(grid_for(a.m, FB * 4, 512)), dim3(FB), 0, s, a.row_ptr, a.m, a.nnz, ctr);
     MO_LAUNCH_CHECK();
-    const int64_t row_blocks = (a.m + FB - 1) / FB;   // m <= 2^31 - 1, so this fits a grid dimension
+    // at most HIST_BLOCKS blocks, each owning a contiguous run of rows (a multiple of the block size)
+    constexpr int64_t HIST_BLOCKS = 2048;
+    int64_t rows_per_block = (a.m + HIST_BLOCKS - 1) / HIST_BLOCKS;
+    rows_per_block = ((rows_per_block + FB - 1) / FB) * FB;
+    const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;
     if (want_hist)
-        hipLaunchKernelGGL(k_diag_hist<true>, dim3((unsigned)row_blocks), dim3(FB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, ctr);
+        hipLaunchKernelGGL(k_diag_hist<true>, dim3((unsigned)row_blocks), dim3(FB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
+                           rows_per_block, hist, ctr);
     else
-        hipLaunchKernelGGL(k_diag_hist<false>, dim3((unsigned)row_blocks), dim3(FB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, ctr);
+        hipLaunchKernelGGL(k_diag_hist<false>, dim3((unsigned)row_blocks), dim3(FB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
+                           rows_per_block, hist, ctr);
     MO_LAUNCH_CHECK();
     if (want_hist) {
         const int64_t mn = a.m < a.n ? a.m : a.n;
-        hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 2048)), dim3(FB), 0, s, hist, ndiag,
+        hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
                            (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
         MO_LAUNCH_CHECK();
     }
