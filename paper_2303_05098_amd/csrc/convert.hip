@@ -442,13 +442,12 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         std::vector<int32_t> hoff((size_t)nd);
         MO_HIP(hipMemcpyAsync(hoff.data(), h->dia_off, (size_t)nd * 4, hipMemcpyDeviceToHost, s));
         MO_HIP(hipStreamSynchronize(s));
-        int block = 512, rows = sizeof(T) == 4 ? 2 : 1;
-        if (const char *e = getenv("MO_DIA_BLOCK")) block = atoi(e);
-        if (const char *e = getenv("MO_DIA_ROWS")) rows = atoi(e) == 2 ? 2 : 1;
+        // 512 threads per block, one row per lane in fp64 and two in fp32 (8 bytes per lane and load either way):
+        // measured best of {256, 512} x {1, 2} on the stencil and band configurations.
+        const int block = 512, rows = sizeof(T) == 4 ? 2 : 1;
         std::vector<int32_t> xpos, cl;
         int64_t elems = 0;
-        if ((block == 256 || block == 512) &&
-            plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems)) {
+        if (plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems)) {
             h->dia_xpos = (int32_t *)b.own(xpos.size() * 4);
             h->dia_clusters = (int32_t *)b.own(cl.size() * 4);
             if (b.failed) return MO_E_ALLOC;
@@ -467,7 +466,11 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
 void setup_coo_tiles(Builder &b, size_t sv)
 {
     mo_matrix *h = b.h;
-    h->coo_tiles = (h->nnz_coo + COO_TILE - 1) / COO_TILE;
+    // Short strips only pay off for the scattered COO part of a HYB matrix, whose SpMV read-modify-writes y: measured
+    // 148 vs 165 us on the banded+scatter matrix; a plain COO matrix is faster with 8 entries per thread at any size.
+    h->coo_strip = (h->fmt == MO_HYB && h->nnz_coo < COO_SMALL_NNZ) ? 2 : 8;
+    const int64_t tile = (int64_t)COO_B_THREADS * h->coo_strip;
+    h->coo_tiles = (h->nnz_coo + tile - 1) / tile;
     const int64_t t = h->coo_tiles > 0 ? h->coo_tiles : 1;
     h->coo_carry_row = (int32_t *)b.own((size_t)t * 4);
     h->coo_carry_val = b.own((size_t)t * sv);

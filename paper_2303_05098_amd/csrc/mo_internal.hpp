@@ -53,7 +53,8 @@ struct Scratch {
 // ---------------------------------------------------------------- handle
 constexpr int CSR_TILE = 2048;        // entries per CSR work tile
 constexpr int CSR_TILE_SLACK = 256;   // longest row the tiled CSR kernel accepts (LDS holds CSR_TILE + slack entries)
-constexpr int COO_TILE = 2048;        // entries per COO work tile
+constexpr int COO_B_THREADS = 256;    // threads per COO block; a tile is COO_B_THREADS * coo_strip entries
+constexpr int64_t COO_SMALL_NNZ = 4 * 1024 * 1024;   // below this many entries the COO part of HYB uses 2-entry strips
 
 
 }  // namespace mo
@@ -91,6 +92,7 @@ struct mo_matrix {
     int32_t csr_group = 1;
     int32_t *csr_tile_rp = nullptr;   // (first row, its row_ptr) per tile, tiles + 1 pairs
     int64_t coo_tiles = 0;
+    int32_t coo_strip = 8;            // entries per thread of the COO kernel (8 or 2)
     int32_t *coo_carry_row = nullptr; // one per COO tile
     void *coo_carry_val = nullptr;
     // everything this handle owns

@@ -12,8 +12,9 @@
 namespace mo {
 
 constexpr int COO_B = 256;
-constexpr int COO_STRIP = COO_TILE / COO_B;   // 8 entries per thread
-static_assert(COO_STRIP == 8, "strip loads below are written for 8 entries per thread");
+// Entries per thread: 8 for large COO parts (more bytes in flight per lane), 2 for small ones (the COO part of a HYB
+// matrix is often a few hundred thousand scattered entries: shorter strips mean four times as many threads to hide
+// the latency of the x gathers and of the y read-modify-writes behind).
 
 template <typename T>
 __global__ void k_zero(T *__restrict__ p, int64_t n)
@@ -27,7 +28,7 @@ template <typename T> struct Vec2;
 template <> struct Vec2<double> { using type = double2; };
 template <> struct Vec2<float> { using type = float2; };
 
-template <typename T, bool ACC>
+template <typename T, int COO_STRIP, bool ACC>
 __global__ __launch_bounds__(COO_B) void k_coo_tile(const int32_t *__restrict__ row, const int32_t *__restrict__ col,
                                                      const T *__restrict__ val, int64_t nnz, const T *__restrict__ x,
                                                      T *__restrict__ y, int32_t *__restrict__ carry_row, T *__restrict__ carry_val)
@@ -37,22 +38,32 @@ __global__ __launch_bounds__(COO_B) void k_coo_tile(const int32_t *__restrict__ 
     __shared__ int s_closed[COO_B];
     __shared__ T s_lead[COO_B];
 
+    constexpr int TILE = COO_B * COO_STRIP;
     const int64_t tile = xcd_block(blockIdx.x, gridDim.x);
-    const int64_t base = tile * COO_TILE;
+    const int64_t base = tile * TILE;
     const int t = threadIdx.x;
     const int64_t p0 = base + (int64_t)t * COO_STRIP;
 
     int r[COO_STRIP];
     T pr[COO_STRIP];
     if (p0 + COO_STRIP <= nnz) {
-        const int4 ra = *reinterpret_cast<const int4 *>(row + p0), rb = *reinterpret_cast<const int4 *>(row + p0 + 4);
-        const int4 ca = *reinterpret_cast<const int4 *>(col + p0), cb = *reinterpret_cast<const int4 *>(col + p0 + 4);
         using V2 = typename Vec2<T>::type;
+        int c[COO_STRIP];
         V2 v[COO_STRIP / 2];
+        if constexpr (COO_STRIP == 8) {
+            const int4 ra = *reinterpret_cast<const int4 *>(row + p0), rb = *reinterpret_cast<const int4 *>(row + p0 + 4);
+            const int4 ca = *reinterpret_cast<const int4 *>(col + p0), cb = *reinterpret_cast<const int4 *>(col + p0 + 4);
+            r[0] = ra.x; r[1] = ra.y; r[2] = ra.z; r[3] = ra.w; r[4] = rb.x; r[5] = rb.y; r[6] = rb.z; r[7] = rb.w;
+            c[0] = ca.x; c[1] = ca.y; c[2] = ca.z; c[3] = ca.w; c[4] = cb.x; c[5] = cb.y; c[6] = cb.z; c[7] = cb.w;
+        } else {
+            static_assert(COO_STRIP == 2, "strip loads are written for 8 or 2 entries per thread");
+            const int2 ra = *reinterpret_cast<const int2 *>(row + p0);
+            const int2 ca = *reinterpret_cast<const int2 *>(col + p0);
+            r[0] = ra.x; r[1] = ra.y;
+            c[0] = ca.x; c[1] = ca.y;
+        }
 #pragma unroll
         for (int q = 0; q < COO_STRIP / 2; ++q) v[q] = *reinterpret_cast<const V2 *>(val + p0 + 2 * q);
-        r[0] = ra.x; r[1] = ra.y; r[2] = ra.z; r[3] = ra.w; r[4] = rb.x; r[5] = rb.y; r[6] = rb.z; r[7] = rb.w;
-        const int c[COO_STRIP] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
         T xv[COO_STRIP];
 #pragma unroll
         for (int q = 0; q < COO_STRIP; ++q) xv[q] = x[c[q]];
@@ -151,25 +162,32 @@ mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s)
     return dt == MO_F32 ? zero_typed<float>(p, n_elems, s) : zero_typed<double>(p, n_elems, s);
 }
 
+template <typename T, int STRIP>
+static mo_status coo_launch(const mo_matrix &a, const T *x, T *y, bool accumulate, hipStream_t s)
+{
+    const unsigned tiles = (unsigned)a.coo_tiles;
+    if (accumulate)
+        hipLaunchKernelGGL((k_coo_tile<T, STRIP, true>), dim3(tiles), dim3(COO_B), 0, s, a.coo_row, a.coo_col, (const T *)a.coo_val,
+                           a.nnz_coo, x, y, a.coo_carry_row, (T *)a.coo_carry_val);
+    else
+        hipLaunchKernelGGL((k_coo_tile<T, STRIP, false>), dim3(tiles), dim3(COO_B), 0, s, a.coo_row, a.coo_col, (const T *)a.coo_val,
+                           a.nnz_coo, x, y, a.coo_carry_row, (T *)a.coo_carry_val);
+    MO_LAUNCH_CHECK();
+    if (tiles > 1) {
+        hipLaunchKernelGGL(k_coo_fixup<T>, dim3((tiles + 255) / 256), dim3(256), 0, s, a.coo_carry_row, (const T *)a.coo_carry_val,
+                           (int64_t)tiles, y);
+        MO_LAUNCH_CHECK();
+    }
+    return MO_OK;
+}
+
 template <typename T>
 static mo_status coo_typed(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s)
 {
     if (!accumulate) MO_TRY(zero_typed<T>(y, a.m, s));
     if (a.nnz_coo <= 0) return MO_OK;
-    const unsigned tiles = (unsigned)a.coo_tiles;
-    if (accumulate)
-        hipLaunchKernelGGL((k_coo_tile<T, true>), dim3(tiles), dim3(COO_B), 0, s, a.coo_row, a.coo_col, (const T *)a.coo_val,
-                           a.nnz_coo, (const T *)x, (T *)y, a.coo_carry_row, (T *)a.coo_carry_val);
-    else
-        hipLaunchKernelGGL((k_coo_tile<T, false>), dim3(tiles), dim3(COO_B), 0, s, a.coo_row, a.coo_col, (const T *)a.coo_val,
-                           a.nnz_coo, (const T *)x, (T *)y, a.coo_carry_row, (T *)a.coo_carry_val);
-    MO_LAUNCH_CHECK();
-    if (tiles > 1) {
-        hipLaunchKernelGGL(k_coo_fixup<T>, dim3((tiles + 255) / 256), dim3(256), 0, s, a.coo_carry_row, (const T *)a.coo_carry_val,
-                           (int64_t)tiles, (T *)y);
-        MO_LAUNCH_CHECK();
-    }
-    return MO_OK;
+    if (a.coo_strip == 2) return coo_launch<T, 2>(a, (const T *)x, (T *)y, accumulate, s);
+    return coo_launch<T, 8>(a, (const T *)x, (T *)y, accumulate, s);
 }
 
 mo_status spmv_coo(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s)
