@@ -29,6 +29,10 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC = {
     (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 732.3e6, (2, "f64", "ELL"): 710.2e6,
     (2, "f64", "COO"): 951.7e6,
+    # profiles/spmv_all_formats_banded_scatter_f64.md: the 1.17 M scattered entries gather one 128-byte line of x each
+    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 700.8e6, (4, "f64", "ELL"): 683.0e6, (4, "f64", "COO"): 836.4e6 + 33.6e6,
+    # profiles/spmv_all_formats_lognormal_f64.md: 16.8 M random gathers of x miss L2; bytes counted at the L2 boundary
+    (3, "f64", "HYB"): 642.0e6 + 750.1e6, (3, "f64", "CSR"): 1522.5e6, (3, "f64", "COO"): 1585.9e6 + 8.4e6,
 }
 REPS = 1000
 MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_tree.bin")
