@@ -390,16 +390,18 @@ mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, i
     mo_matrix *h = b.h;
     h->csr_max_row = max_row;
     const double avg = m > 0 ? (double)nnz / (double)m : 0.0;
-    int lanes = 2;
-    while (lanes < 64 && (double)lanes < avg) lanes <<= 1;
-    h->csr_lanes = lanes;
     // lanes per row: the rows of one tile (about CSR_TILE / avg) should fit one pass of 256 / g rows
     int g = 1;
     while (g < 16 && avg > 10.0 * g) g <<= 1;
     h->csr_group = g;
-    h->csr_tiles = csr_tile_count(nnz, max_row, CSR_TILE);
-    if (h->csr_tiles > 0) {
+    h->csr_tiles = csr_tile_count(nnz, CSR_TILE);
+    h->csr_split = max_row > CSR_TILE_SLACK ? 1 : 0;
+    {
         h->csr_tile_rp = (int32_t *)b.own((size_t)(h->csr_tiles + 1) * 8);
+        if (h->csr_split) {
+            h->csr_carry_row = (int32_t *)b.own((size_t)h->csr_tiles * 4);
+            h->csr_carry_val = b.own((size_t)h->csr_tiles * dtype_size(h->dtype));
+        }
         if (b.failed) return MO_E_ALLOC;
         MO_TRY(csr_build_tiles(row_ptr, m, nnz, h->csr_tiles, CSR_TILE, h->csr_tile_rp, b.s));
     }
@@ -467,8 +469,8 @@ void setup_coo_tiles(Builder &b, size_t sv)
 {
     mo_matrix *h = b.h;
     // Short strips only pay off for the scattered COO part of a HYB matrix, whose SpMV read-modify-writes y: measured
-    // 148 vs 165 us on the banded+scatter matrix; a plain COO matrix is faster with 8 entries per thread at any size.
-    h->coo_strip = (h->fmt == MO_HYB && h->nnz_coo < COO_SMALL_NNZ) ? 2 : 8;
+    // 148 vs 165 us on the banded+scatter matrix; a plain COO matrix is faster with longer strips at any size.
+    h->coo_strip = (h->fmt == MO_HYB && h->nnz_coo < COO_SMALL_NNZ) ? 2 : 4;
     const int64_t tile = (int64_t)COO_B_THREADS * h->coo_strip;
     h->coo_tiles = (h->nnz_coo + tile - 1) / tile;
     const int64_t t = h->coo_tiles > 0 ? h->coo_tiles : 1;

@@ -86,13 +86,15 @@ struct mo_matrix {
     const int32_t *csr_row_ptr = nullptr, *csr_col = nullptr;
     const void *csr_val = nullptr;
     // launch data derived at conversion time (not part of the format)
-    int32_t csr_lanes = 1;            // lanes per row of the vector CSR kernel
     int64_t csr_max_row = 0;
-    int64_t csr_tiles = 0;            // > 0: tiled CSR kernel with csr_group lanes per row
+    int64_t csr_tiles = 0;            // tiles of CSR_TILE entries; csr_group lanes per row in the LDS reduction
     int32_t csr_group = 1;
+    int32_t csr_split = 0;            // 1: tiles cut rows (any row length), carries in csr_carry_*
+    int32_t *csr_carry_row = nullptr;
+    void *csr_carry_val = nullptr;
     int32_t *csr_tile_rp = nullptr;   // (first row, its row_ptr) per tile, tiles + 1 pairs
     int64_t coo_tiles = 0;
-    int32_t coo_strip = 8;            // entries per thread of the COO kernel (8 or 2)
+    int32_t coo_strip = 4;            // entries per thread of the COO kernel (4 or 2)
     int32_t *coo_carry_row = nullptr; // one per COO tile
     void *coo_carry_val = nullptr;
     // everything this handle owns
@@ -137,7 +139,9 @@ bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_e
 constexpr int64_t DIA_LDS_BYTES = 48 * 1024;  // LDS budget for staged x windows per block
 constexpr int64_t HDC_FUSED_MAX_ROW = 64;   // longest row for which HDC runs as one fused kernel
 mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s);
-int64_t csr_tile_count(int64_t nnz, int64_t max_row, int tile_size);
+int64_t csr_tile_count(int64_t nnz, int tile_size);
+// y[row] += carries of every chain of consecutive tiles with the same carry row (shared by the COO and CSR kernels)
+mo_status carry_fixup(const int32_t *carry_row, const void *carry_val, int64_t tiles, void *y, mo_dtype dt, hipStream_t s);
 mo_status csr_build_tiles(const int32_t *row_ptr, int64_t m, int64_t nnz, int64_t ntiles, int tile_size, int32_t *tile_rp, hipStream_t s);
 
 inline size_t dtype_size(mo_dtype d) { return d == MO_F32 ? 4 : 8; }
