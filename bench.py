@@ -28,6 +28,37 @@ HBM_PEAK_GBS = 8000.0
 # factors a plain 1 GiB copy gives; see profiles/spmv_all_formats_stencil27_128_f64.md).  Keyed by (config, dtype, format).
 MEASURED_TRAFFIC = {
     (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 732.3e6, (2, "f64", "ELL"): 710.2e6,
+    (2, "f64", "COO"): 959.4e6 + 16.8e6 + 9.1e6,
+    # profiles/spmv_all_formats_banded_scatter_f64.md: the 1.17 M scattered entries gather one 128-byte line of x each
+    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 700.9e6, (4, "f64", "ELL"): 650.9e6, (4, "f64", "COO"): 835.6e6 + 33.6e6 + 2.1e6,
+    # profiles/spmv_all_formats_lognormal_f64.md: 16.8 M random gathers of x miss L2; bytes counted at the L2 boundary
+    (3, "f64", "CSR"): 1334.0e6, (3, "f64", "HYB"): 642.2e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
+}
+REPS = 1000 SpMVs in that format.  The headline value is
+2 * nnz * REPS / t_step.  The one-off rows of the path (conversions, run-first tuning) and the SpMV rate of every
+format are measured in the same run and printed in the same JSON line.
+
+Workload: benchmark configs[1], the 3-D 27-point stencil on a 128^3 grid in fp64 (synthetic, seeded), with
+all inputs resident in HBM before the timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per SpMV launch from the committed rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scale
+# factors a plain 1 GiB copy gives; see profiles/spmv_all_formats_stencil27_128_f64.md).  Keyed by (config, dtype, format).
+MEASURED_TRAFFIC = {
+    (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 732.3e6, (2, "f64", "ELL"): 710.2e6,
     (2, "f64", "COO"): 951.7e6,
     # profiles/spmv_all_formats_banded_scatter_f64.md: the 1.17 M scattered entries gather one 128-byte line of x each
     (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 700.8e6, (4, "f64", "ELL"): 683.0e6, (4, "f64", "COO"): 836.4e6 + 33.6e6,
@@ -184,7 +215,7 @@ def main() -> int:
 
     alg = algorithmic_bytes(chosen, h.view(), sv)
     achieved = alg / (spmv_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": {2: "k_dia_lds", 5: "k_dia_lds(HDC)", 1: "k_csr_tiled", 3: "k_ell", 0: "k_coo_tile", 4: "k_ell+k_coo_tile"}[chosen],
+    roofline = {"bound": "hbm", "kernel": {2: "k_dia_lds", 5: "k_dia_lds(HDC)", 1: "k_csr_tiled / k_csr_split", 3: "k_ell", 0: "k_coo_tile", 4: "k_ell+k_coo_tile"}[chosen],
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC.get((args.config, args.dtype, mo.FORMAT_NAMES[chosen])), "algorithmic_bytes_per_launch": alg, "us_per_launch": round(spmv_ms * 1e3, 2)}
 
