@@ -34,37 +34,6 @@ MEASURED_TRAFFIC = {
     # profiles/spmv_all_formats_lognormal_f64.md: 16.8 M random gathers of x miss L2; bytes counted at the L2 boundary
     (3, "f64", "CSR"): 1334.0e6, (3, "f64", "HYB"): 642.2e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
 }
-REPS = 1000 SpMVs in that format.  The headline value is
-2 * nnz * REPS / t_step.  The one-off rows of the path (conversions, run-first tuning) and the SpMV rate of every
-format are measured in the same run and printed in the same JSON line.
-
-Workload: benchmark configs[1], the 3-D 27-point stencil on a 128^3 grid in fp64 (synthetic, seeded), with
-all inputs resident in HBM before the timed region starts.
-"""
-from __future__ import annotations
-
-import argparse
-import json
-import math
-import os
-import sys
-import time
-
-ROOT = os.path.dirname(os.path.abspath(__file__))
-if ROOT not in sys.path:
-    sys.path.insert(0, ROOT)
-
-HBM_PEAK_GBS = 8000.0
-# HBM bytes per SpMV launch from the committed rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scale
-# factors a plain 1 GiB copy gives; see profiles/spmv_all_formats_stencil27_128_f64.md).  Keyed by (config, dtype, format).
-MEASURED_TRAFFIC = {
-    (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 732.3e6, (2, "f64", "ELL"): 710.2e6,
-    (2, "f64", "COO"): 951.7e6,
-    # profiles/spmv_all_formats_banded_scatter_f64.md: the 1.17 M scattered entries gather one 128-byte line of x each
-    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 700.8e6, (4, "f64", "ELL"): 683.0e6, (4, "f64", "COO"): 836.4e6 + 33.6e6,
-    # profiles/spmv_all_formats_lognormal_f64.md: 16.8 M random gathers of x miss L2; bytes counted at the L2 boundary
-    (3, "f64", "HYB"): 642.0e6 + 750.1e6, (3, "f64", "CSR"): 1522.5e6, (3, "f64", "COO"): 1585.9e6 + 8.4e6,
-}
 REPS = 1000
 MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_tree.bin")
 
