@@ -88,6 +88,14 @@ def analyse(recs, max_depth: int, min_samples_leaf: int, reps_eq2: int = 1000, t
     eq2 = (t_csr * reps_eq2) / (t_fe + t_pred_ms + t_pred * reps_eq2)
     cost = (t_fe + t_pred_ms) / t_csr
     q = np.percentile(cost, [0, 25, 50, 75, 100])
+    # SpMVs after which tuning has paid for itself, conversion included (the paper leaves conversion out of Eq. 2):
+    # smallest n with t_fe + t_pred + t_conv + n * t_pred_fmt < n * t_csr; only where the predicted format is faster
+    conv = np.array([[np.nan if t is None else t for t in r["convert_ms"]] for r in recs], dtype=np.float64)
+    t_conv = conv[np.arange(len(recs)), pred]
+    gain = t_csr - t_pred
+    pays = (gain > 0) & (pred != 1) & ~np.isnan(t_conv)
+    breakeven = np.ceil((t_fe + t_pred_ms + t_conv)[pays] / gain[pays])
+    bq = np.percentile(breakeven, [25, 50, 75]) if breakeven.size else [float("nan")] * 3
     return dict(
         n=len(recs), class_histogram={FORMATS[c]: int((y == c).sum()) for c in range(6)},
         predicted_histogram={FORMATS[c]: int((pred == c).sum()) for c in range(6)},
@@ -99,6 +107,7 @@ def analyse(recs, max_depth: int, min_samples_leaf: int, reps_eq2: int = 1000, t
         mean_speedup_best_vs_csr_where_not_csr=float(np.mean((t_csr / t_best)[y != 1])) if (y != 1).any() else None,
         tuner_cost_in_csr_spmv=dict(mean=float(cost.mean()), std=float(cost.std()), min=float(q[0]), q1=float(q[1]),
                                     q2=float(q[2]), q3=float(q[3]), max=float(q[4])),
+        breakeven_spmvs_incl_conversion=dict(n_matrices=int(pays.sum()), q1=float(bq[0]), q2=float(bq[1]), q3=float(bq[2])),
         max_depth=max_depth, min_samples_leaf=min_samples_leaf,
     ), X, y
 
