@@ -396,3 +396,65 @@ int orc_pick(int32_t n, const double *ms)
     }
     return best;
 }
+
+/* ------------------------------------------------- back from a format to triplets */
+
+/* Section II-C: the formats can be switched at run time in any direction.  Going back to triplets is the
+ * definition of each format read backwards.  Each function returns the number of triplets and fills ti/tj/ta
+ * (sized by the caller for the worst case) unless they are NULL (count only).
+ *
+ * DIA cannot tell a stored zero from padding, so exactly-zero positions are not entries; positions whose column
+ * falls outside [0, n) are never entries. */
+int64_t orc_from_dia(int64_t m, int64_t n, int64_t nd, const int32_t *off, const double *val,
+                     int32_t *ti, int32_t *tj, double *ta)
+{
+    int64_t c = 0;
+    for (int64_t k = 0; k < nd; ++k)
+        for (int64_t i = 0; i < m; ++i) {
+            int64_t j = i + off[k];
+            if (j < 0 || j >= n) continue;
+            if (val[k * m + i] == 0.0) continue;
+            if (ti) { ti[c] = (int32_t)i; tj[c] = (int32_t)j; ta[c] = val[k * m + i]; }
+            c++;
+        }
+    return c;
+}
+
+/* ELL: every slot whose column is not the padding marker is an entry (stored zeros included). */
+int64_t orc_from_ell(int64_t m, int64_t k, const int32_t *col, const double *val, int32_t *ti, int32_t *tj, double *ta)
+{
+    int64_t c = 0;
+    for (int64_t s = 0; s < k; ++s)
+        for (int64_t i = 0; i < m; ++i) {
+            if (col[s * m + i] < 0) continue;
+            if (ti) { ti[c] = (int32_t)i; tj[c] = col[s * m + i]; ta[c] = val[s * m + i]; }
+            c++;
+        }
+    return c;
+}
+
+/* CSR: expand the row pointer. */
+int64_t orc_from_csr(int64_t m, const int32_t *row_ptr, const int32_t *col, const double *val, int32_t *ti, int32_t *tj, double *ta)
+{
+    int64_t c = 0;
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {
+            if (ti) { ti[c] = (int32_t)i; tj[c] = col[p]; ta[c] = val[p]; }
+            c++;
+        }
+    return c;
+}
+
+/* Triplets -> CSR with ascending columns (the inverse conversions all end here). */
+int orc_to_csr(int64_t m, int64_t nnz, const int32_t *ti, const int32_t *tj, const double *ta,
+               int32_t *row_ptr, int32_t *col, double *val)
+{
+    orc_trip *s = orc_sorted(nnz, ti, tj, ta);
+    if (!s) return ORC_E_MEM;
+    for (int64_t i = 0; i <= m; ++i) row_ptr[i] = 0;
+    for (int64_t t = 0; t < nnz; ++t) row_ptr[s[t].i + 1]++;
+    for (int64_t i = 0; i < m; ++i) row_ptr[i + 1] += row_ptr[i];
+    for (int64_t t = 0; t < nnz; ++t) { col[t] = s[t].j; val[t] = s[t].a; }
+    free(s);
+    return ORC_OK;
+}

@@ -29,6 +29,8 @@ def lib():
         _lib.orc_dia_offsets.restype = C.c_int64
         _lib.orc_max_row.restype = C.c_int64
         _lib.orc_hyb_k.restype = C.c_int64
+        for name in ("orc_from_dia", "orc_from_ell", "orc_from_csr"):
+            getattr(_lib, name).restype = C.c_int64
     return _lib
 
 
@@ -179,6 +181,68 @@ def to_hdc(m, n, ti, tj, ta, td=(1, 2)):
                                _p(row_ptr, I32P), _p(col, I32P), _p(val, F64P))
     assert rc == 0
     return dict(dia_off=off, dia_val=dval, csr_row_ptr=row_ptr, csr_col=col[:nrest], csr_val=val[:nrest])
+
+
+def _trip_buffers(cnt):
+    c = max(int(cnt), 1)
+    return np.zeros(c, np.int32), np.zeros(c, np.int32), np.zeros(c, np.float64)
+
+
+def from_dia(m, n, off, val):
+    """DIA arrays (off[nd], val[nd, m]) -> triplets; exactly-zero and out-of-matrix positions are not entries."""
+    off, val = _i32(off), _f64(val).reshape(-1)
+    nd = off.shape[0]
+    args = (_i64(m), _i64(n), _i64(nd), _p(off, I32P) if nd else None, _p(val, F64P) if val.size else None)
+    cnt = int(lib().orc_from_dia(*args, None, None, None))
+    ti, tj, ta = _trip_buffers(cnt)
+    lib().orc_from_dia(*args, _p(ti, I32P), _p(tj, I32P), _p(ta, F64P))
+    return ti[:cnt], tj[:cnt], ta[:cnt]
+
+
+def from_ell(m, col, val):
+    """ELL arrays (col[k, m], val[k, m]) -> triplets; slots with col >= 0 are entries."""
+    k = col.shape[0]
+    col, val = _i32(col).reshape(-1), _f64(val).reshape(-1)
+    args = (_i64(m), _i64(k), _p(col, I32P) if col.size else None, _p(val, F64P) if val.size else None)
+    cnt = int(lib().orc_from_ell(*args, None, None, None))
+    ti, tj, ta = _trip_buffers(cnt)
+    lib().orc_from_ell(*args, _p(ti, I32P), _p(tj, I32P), _p(ta, F64P))
+    return ti[:cnt], tj[:cnt], ta[:cnt]
+
+
+def from_csr(m, row_ptr, col, val):
+    row_ptr, col, val = _i32(row_ptr), _i32(col), _f64(val)
+    cnt = int(row_ptr[m])
+    ti, tj, ta = _trip_buffers(cnt)
+    got = int(lib().orc_from_csr(_i64(m), _p(row_ptr, I32P), _p(col, I32P) if cnt else None, _p(val, F64P) if cnt else None,
+                                 _p(ti, I32P), _p(tj, I32P), _p(ta, F64P)))
+    assert got == cnt
+    return ti[:cnt], tj[:cnt], ta[:cnt]
+
+
+def to_csr(m, ti, tj, ta):
+    """-> (row_ptr int32[m+1], col int32[nnz], val float64[nnz]), columns ascending inside a row."""
+    ti, tj, ta = _i32(ti), _i32(tj), _f64(ta)
+    nnz = ti.shape[0]
+    row_ptr = np.zeros(m + 1, np.int32)
+    col, _, val = _trip_buffers(nnz)
+    rc = lib().orc_to_csr(_i64(m), _i64(nnz), _p(ti, I32P), _p(tj, I32P), _p(ta, F64P), _p(row_ptr, I32P), _p(col, I32P), _p(val, F64P))
+    assert rc == 0
+    return row_ptr, col[:nnz], val[:nnz]
+
+
+def format_to_triplets(fmt, m, n, arrays):
+    """Triplets held by a matrix in format ``fmt`` given the oracle-layout arrays of that format (dict)."""
+    parts = []
+    if fmt in (FMT_DIA, FMT_HDC):
+        parts.append(from_dia(m, n, arrays["dia_off"], arrays["dia_val"]))
+    if fmt in (FMT_ELL, FMT_HYB):
+        parts.append(from_ell(m, arrays["ell_col"], arrays["ell_val"]))
+    if fmt in (FMT_COO, FMT_HYB):
+        parts.append((_i32(arrays["coo_row"]), _i32(arrays["coo_col"]), _f64(arrays["coo_val"])))
+    if fmt in (FMT_CSR, FMT_HDC):
+        parts.append(from_csr(m, arrays["csr_row_ptr"], arrays["csr_col"], arrays["csr_val"]))
+    return (np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts]), np.concatenate([p[2] for p in parts]))
 
 
 def feasible(slots, nnz, max_fill=16, max_slots=(1 << 62)):

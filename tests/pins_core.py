@@ -51,6 +51,22 @@ def check_all():
             woff, wval, wrp, wcol, wv = dense_pins.hdc(a, mask, td)
             assert np.array_equal(d["dia_off"], woff) and np.array_equal(d["dia_val"], wval)
             assert np.array_equal(d["csr_row_ptr"], wrp) and np.array_equal(d["csr_col"], wcol) and np.array_equal(d["csr_val"], wv)
+    # --- back from every format: hand cases and round trips
+    off = np.array([-1, 2], np.int32)
+    dval = np.array([[9.0, 1.0, 2.0], [3.0, 0.0, 7.0]])
+    got = sorted(zip(*[list(map(float, q)) for q in ref.from_dia(3, 4, off, dval)]))
+    assert got == [(0.0, 2.0, 3.0), (1.0, 0.0, 1.0), (2.0, 1.0, 2.0)]
+    ecol = np.array([[0, 2, -1], [3, -1, -1]], np.int32)
+    ev = np.array([[5.0, 0.0, 0.0], [6.0, 0.0, 0.0]])
+    got = sorted(zip(*[list(map(float, q)) for q in ref.from_ell(3, ecol, ev)]))
+    assert got == [(0.0, 0.0, 5.0), (0.0, 3.0, 6.0), (1.0, 2.0, 0.0)]
+    m, n, rp, ci, v = synth.random_csr(12, 7, 0.3, 2, 0.3)
+    ti, tj, ta = ref.csr_to_triplets(rp, ci, v)
+    g = ref.from_csr(m, rp, ci, v)
+    assert np.array_equal(g[0], ti) and np.array_equal(g[1], tj) and np.array_equal(g[2], ta)
+    perm = np.argsort(synth.uniform01(5, 98, np.arange(ti.shape[0])))
+    rp2, c2, v2 = ref.to_csr(m, ti[perm], tj[perm], ta[perm])
+    assert np.array_equal(rp2, rp) and np.array_equal(c2, ci) and np.array_equal(v2, v)
     # --- closed forms: 5-point Laplacian 64 x 64
     m, n, rp, ci, v = synth.config(1)
     ti, tj, ta = ref.csr_to_triplets(rp, ci, v)

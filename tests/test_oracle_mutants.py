@@ -31,7 +31,13 @@ MUTANTS = [
     ("coo_column_major", "if (a->i != b->i) return a->i < b->i ? -1 : 1;\n    if (a->j != b->j) return a->j < b->j ? -1 : 1;", "if (a->j != b->j) return a->j < b->j ? -1 : 1;\n    if (a->i != b->i) return a->i < b->i ? -1 : 1;"),
     ("hyb_k_strict", "if ((__int128)rows * hyb_den >= (__int128)m * hyb_num) best = k;", "if ((__int128)rows * hyb_den > (__int128)m * hyb_num) best = k;"),
     ("hyb_k_counts_longer_only", "if (len[i] >= k) rows++;", "if (len[i] > k) rows++;"),
-    ("hdc_row_ptr_shifted", "row_ptr[s[t].i + 1]++;", "row_ptr[s[t].i]++;"),
+    ("hdc_row_ptr_shifted", "for (int64_t t = 0; t < keep; ++t) row_ptr[s[t].i + 1]++;", "for (int64_t t = 0; t < keep; ++t) row_ptr[s[t].i]++;"),
+    ("to_csr_row_ptr_shifted", "for (int64_t t = 0; t < nnz; ++t) row_ptr[s[t].i + 1]++;", "for (int64_t t = 0; t < nnz; ++t) row_ptr[s[t].i]++;"),
+    ("from_dia_keeps_zeros", "if (val[k * m + i] == 0.0) continue;", ""),
+    ("from_dia_keeps_columns_beyond_n", "if (j < 0 || j >= n) continue;", "if (j < 0) continue;"),
+    ("from_dia_column_indexed", "if (ti) { ti[c] = (int32_t)i; tj[c] = (int32_t)j; ta[c] = val[k * m + i]; }", "if (ti) { ti[c] = (int32_t)j; tj[c] = (int32_t)i; ta[c] = val[k * m + i]; }"),
+    ("from_ell_drops_column_zero", "if (col[s * m + i] < 0) continue;", "if (col[s * m + i] <= 0) continue;"),
+    ("from_csr_skips_last_entry_of_row", "for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) {", "for (int64_t p = row_ptr[i]; p + 1 < row_ptr[i + 1]; ++p) {"),
     ("feasible_non_strict", "if ((__int128)slots > (__int128)max_fill * nnz) return 0;", "if ((__int128)slots >= (__int128)max_fill * nnz) return 0;"),
     ("feasible_ignores_max_slots", "if (slots > max_slots) return 0;", ""),
     ("tree_strict_compare", "(x[f] <= threshold[base + node])", "(x[f] < threshold[base + node])"),
@@ -47,6 +53,8 @@ def load(path):
     lib.orc_dia_offsets.restype = C.c_int64
     lib.orc_max_row.restype = C.c_int64
     lib.orc_hyb_k.restype = C.c_int64
+    for name in ("orc_from_dia", "orc_from_ell", "orc_from_csr"):
+        getattr(lib, name).restype = C.c_int64
     return lib
 
 
