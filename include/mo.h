@@ -158,6 +158,20 @@ mo_status mo_model_info(const mo_model *model, int32_t *n_trees, int32_t *n_node
  * tree is a forest of one. */
 mo_status mo_select(const mo_model *model, const double features[MO_NUM_FEATURES], mo_format *out);
 
+/* Run-time switching between any two formats (Section II-C): rebuilds CSR from whatever `a` holds (row lengths ->
+ * exclusive scan -> rows written in ascending column order) and converts that to `fmt`.  A handle produced with
+ * fmt = MO_CSR OWNS its arrays.  A DIA slab cannot tell a stored zero from padding, so positions holding exactly 0
+ * are not entries on the way back; every other format keeps stored zeros.  Same errors and synchronisation as
+ * mo_convert.  `a` is not modified and may be freed afterwards. */
+mo_status mo_switch(const mo_matrix *a, mo_format fmt, const mo_params *params, mo_matrix **out, void *stream);
+
+/* The ten features of Table I for a matrix in whatever format it is held, gathered from that format's own arrays
+ * without converting back (Section VI-C).  Equal, bit for bit, to mo_features of the CSR the handle was built from
+ * (for DIA / HDC: as long as no stored entry of a kept diagonal is exactly 0).  Synchronises `stream`; allocates
+ * and frees 4*(2m + n) bytes of scratch. */
+mo_status mo_matrix_features(const mo_matrix *a, const mo_params *params, double out[MO_NUM_FEATURES],
+                             mo_feature_ints *ints_opt, void *stream);
+
 mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out);
 void mo_matrix_free(mo_matrix *a);
 

@@ -1,0 +1,372 @@
+// Switching away from any format, and features of a matrix in whatever format it is held.
+//
+// The paper's tuner inspects the active format of the matrix without converting it back (Section VI-C: statistics
+// per format, no transfers between memory spaces), and the container can switch between any two formats at run time
+// (Section II-C).  Here:
+//   * row lengths and diagonal counts are gathered straight from the arrays of each format (DIA slabs, ELL slabs,
+//     COO triples, CSR remainder), with the same two-level merging of diagonal counts as the CSR kernels;
+//   * any -> CSR rebuilds row_ptr from the row lengths (exclusive scan) and writes each row's entries in ascending
+//     column order (DIA and CSR parts of HDC are merged by column; the COO part of HYB follows its ELL part);
+//   * any -> any is any -> CSR followed by the CSR -> format conversion.
+// A DIA slab cannot tell a stored zero from padding: positions holding exactly 0 are not entries on the way back.
+#include "dev_common.hpp"
+#include "feat_common.hpp"
+#include "mo_internal.hpp"
+
+#include <cmath>
+
+namespace mo {
+
+// Everything a kernel needs to walk a handle, by value.
+template <typename T>
+struct View {
+    int64_t m, n, ld, nd, k, nnz_coo;
+    const int32_t *dia_off;
+    const T *dia_val;
+    const int32_t *ell_col;
+    const T *ell_val;
+    const int32_t *coo_row, *coo_col;
+    const T *coo_val;
+    const int32_t *csr_row_ptr, *csr_col;
+    const T *csr_val;
+};
+
+template <typename T>
+static View<T> make_view(const mo_matrix &a)
+{
+    View<T> v{};
+    v.m = a.m; v.n = a.n; v.ld = a.ld;
+    const bool dia = a.fmt == MO_DIA || a.fmt == MO_HDC, ell = a.fmt == MO_ELL || a.fmt == MO_HYB;
+    const bool coo = a.fmt == MO_COO || a.fmt == MO_HYB, csr = a.fmt == MO_CSR || a.fmt == MO_HDC;
+    v.nd = dia ? a.nd : 0; v.dia_off = a.dia_off; v.dia_val = (const T *)a.dia_val;
+    v.k = ell ? a.k : 0; v.ell_col = a.ell_col; v.ell_val = (const T *)a.ell_val;
+    v.nnz_coo = coo ? a.nnz_coo : 0; v.coo_row = a.coo_row; v.coo_col = a.coo_col; v.coo_val = (const T *)a.coo_val;
+    v.csr_row_ptr = csr ? a.csr_row_ptr : nullptr; v.csr_col = a.csr_col; v.csr_val = (const T *)a.csr_val;
+    return v;
+}
+
+// First position p in the sorted COO row array with coo_row[p] >= r.
+__device__ __forceinline__ int64_t coo_lower_bound(const int32_t *__restrict__ coo_row, int64_t nnz, int64_t r)
+{
+    int64_t lo = 0, hi = nnz;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)coo_row[mid] < r) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// ------------------------------------------------------------------ row lengths of any format
+template <typename T>
+__global__ __launch_bounds__(FB) void k_len_any(View<T> v, int32_t *__restrict__ len)
+{
+    const int64_t row = (int64_t)blockIdx.x * FB + threadIdx.x;
+    if (row >= v.m) return;
+    int c = 0;
+    for (int64_t k = 0; k < v.nd; ++k) {
+        const int64_t j = row + v.dia_off[k];
+        if (j >= 0 && j < v.n && v.dia_val[k * v.ld + row] != (T)0) ++c;
+    }
+    for (int64_t s = 0; s < v.k; ++s)
+        if (v.ell_col[s * v.ld + row] >= 0) ++c;
+    if (v.nnz_coo > 0) c += (int)(coo_lower_bound(v.coo_row, v.nnz_coo, row + 1) - coo_lower_bound(v.coo_row, v.nnz_coo, row));
+    if (v.csr_row_ptr) c += v.csr_row_ptr[row + 1] - v.csr_row_ptr[row];
+    len[row] = c;
+}
+
+// max, min, sum, sum of squares of the row lengths (one set of atomics per block).
+__global__ __launch_bounds__(FB) void k_len_stats(const int32_t *__restrict__ len, int64_t m, Counters *ctr, unsigned long long *total)
+{
+    unsigned long long mx = 0ull, mn = ~0ull, sq = 0ull, sm = 0ull;
+    const int64_t stride = (int64_t)gridDim.x * FB;
+    for (int64_t i = (int64_t)blockIdx.x * FB + threadIdx.x; i < m; i += stride) {
+        const unsigned long long l = (unsigned long long)len[i];
+        mx = l > mx ? l : mx; mn = l < mn ? l : mn; sq += l * l; sm += l;
+    }
+    mx = wave_max(mx); mn = wave_min(mn); sq = wave_sum(sq); sm = wave_sum(sm);
+    __shared__ unsigned long long s_mx[FB / WAVE], s_mn[FB / WAVE], s_sq[FB / WAVE], s_sm[FB / WAVE];
+    if (lane_id() == 0) { const int w = threadIdx.x / WAVE; s_mx[w] = mx; s_mn[w] = mn; s_sq[w] = sq; s_sm[w] = sm; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < FB / WAVE; ++w) {
+            mx = s_mx[w] > mx ? s_mx[w] : mx; mn = s_mn[w] < mn ? s_mn[w] : mn; sq += s_sq[w]; sm += s_sm[w];
+        }
+        atomicMax(&ctr->max_row, mx); atomicMin(&ctr->min_row, mn); atomicAdd(&ctr->sum_sq, sq); atomicAdd(total, sm);
+    }
+}
+
+// ------------------------------------------------------------------ diagonal counts of any format
+// DIA part: the count of diagonal off_k is the number of in-matrix, non-zero positions of slab k.
+// blockIdx.x = diagonal, blockIdx.y = chunk of rows; one atomic per block.
+template <typename T>
+__global__ __launch_bounds__(FB) void k_hist_dia(View<T> v, uint32_t *__restrict__ hist)
+{
+    const int64_t k = blockIdx.x;
+    const int64_t off = v.dia_off[k];
+    unsigned int c = 0;
+    const int64_t stride = (int64_t)gridDim.y * FB;
+    for (int64_t row = (int64_t)blockIdx.y * FB + threadIdx.x; row < v.m; row += stride) {
+        const int64_t j = row + off;
+        if (j >= 0 && j < v.n && v.dia_val[k * v.ld + row] != (T)0) ++c;
+    }
+    c = wave_sum(c);
+    __shared__ unsigned int s_c[FB / WAVE];
+    if (lane_id() == 0) s_c[threadIdx.x / WAVE] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < FB / WAVE; ++w) c += s_c[w];
+        if (c) atomicAdd(&hist[off + (v.m - 1)], c);
+    }
+}
+
+// ELL, COO and CSR parts: one row per lane for the slabs and the CSR remainder (equal diagonals meet in the same
+// step and are merged by ballot), one entry per lane for COO; everything goes through the block's LDS hash table.
+template <typename T>
+__global__ __launch_bounds__(FB) void k_hist_parts(View<T> v, int64_t rows_per_block, int64_t coo_per_block, uint32_t *__restrict__ hist)
+{
+    __shared__ int ht_key[HT_SIZE];
+    __shared__ uint32_t ht_cnt[HT_SIZE];
+    __shared__ int ht_full;
+    if (threadIdx.x == 0) ht_full = 0;
+    for (int i = threadIdx.x; i < HT_SIZE; i += FB) { ht_key[i] = -1; ht_cnt[i] = 0u; }
+    __syncthreads();
+    const int lane = lane_id();
+    auto merged = [&](bool ok, int key) {   // called by whole waves
+        uint64_t todo = ballot64(ok);
+        int rounds = 0;
+        while (todo) {
+            if (rounds == MERGE_ROUNDS) {
+                if ((todo >> lane) & 1ull) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
+                break;
+            }
+            const int leader = __ffsll((unsigned long long)todo) - 1;
+            const int lkey = __shfl(key, leader, WAVE);
+            const uint64_t same = ballot64(ok && key == lkey) & todo;
+            if (lane == leader) count_key(lkey, (uint32_t)__popcll(same), ht_key, ht_cnt, &ht_full, hist);
+            todo &= ~same;
+            ++rounds;
+        }
+    };
+    const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
+    int64_t row_end = row_begin + rows_per_block;
+    row_end = row_end < v.m ? row_end : v.m;
+    for (int64_t base = row_begin; base < row_end; base += FB) {   // uniform trip count across the block
+        const int64_t row = base + threadIdx.x;
+        const bool rv = row < row_end;
+        for (int64_t s = 0; s < v.k; ++s) {
+            const int c = rv ? v.ell_col[s * v.ld + row] : -1;
+            merged(c >= 0, (int)((int64_t)c - row + (v.m - 1)));
+        }
+        if (v.csr_row_ptr) {
+            const int lo = rv ? v.csr_row_ptr[row] : 0, hi = rv ? v.csr_row_ptr[row + 1] : 0;
+            const int wmax = wave_max(hi - lo);
+            for (int q = 0; q < wmax; ++q) {
+                const bool act = q < hi - lo;
+                const int c = act ? v.csr_col[lo + q] : 0;
+                merged(act, (int)((int64_t)c - row + (v.m - 1)));
+            }
+        }
+    }
+    const int64_t p_begin = (int64_t)blockIdx.x * coo_per_block;
+    int64_t p_end = p_begin + coo_per_block;
+    p_end = p_end < v.nnz_coo ? p_end : v.nnz_coo;
+    for (int64_t p = p_begin + threadIdx.x; p < p_end; p += FB)
+        count_key((int)((int64_t)v.coo_col[p] - v.coo_row[p] + (v.m - 1)), 1u, ht_key, ht_cnt, &ht_full, hist);
+    __syncthreads();
+    for (int i = threadIdx.x; i < HT_SIZE; i += FB) {
+        const uint32_t c = ht_cnt[i];
+        if (c) atomicAdd(&hist[ht_key[i]], c);
+    }
+}
+
+// ------------------------------------------------------------------ any -> CSR
+// One row per lane; the row's entries leave in ascending column order.
+template <typename T>
+__global__ __launch_bounds__(FB) void k_fill_csr_any(View<T> v, const int32_t *__restrict__ out_ptr, int32_t *__restrict__ ocol,
+                                                      T *__restrict__ oval)
+{
+    const int64_t row = (int64_t)blockIdx.x * FB + threadIdx.x;
+    if (row >= v.m) return;
+    int64_t pos = out_ptr[row];
+    // DIA part and CSR part (HDC holds both): two ascending column sequences, merged
+    int64_t kd = 0;
+    int p = v.csr_row_ptr ? v.csr_row_ptr[row] : 0;
+    const int pe = v.csr_row_ptr ? v.csr_row_ptr[row + 1] : 0;
+    while (true) {
+        int64_t jd = -1;
+        T ad = (T)0;
+        while (kd < v.nd) {   // next entry of the DIA part
+            const int64_t j = row + v.dia_off[kd];
+            const T a = (j >= 0 && j < v.n) ? v.dia_val[kd * v.ld + row] : (T)0;
+            if (a != (T)0) { jd = j; ad = a; break; }
+            ++kd;
+        }
+        const bool has_d = jd >= 0, has_c = p < pe;
+        if (!has_d && !has_c) break;
+        if (has_d && (!has_c || jd < (int64_t)v.csr_col[p])) { ocol[pos] = (int32_t)jd; oval[pos] = ad; ++kd; }
+        else { ocol[pos] = v.csr_col[p]; oval[pos] = v.csr_val[p]; ++p; }
+        ++pos;
+    }
+    // ELL part, then the COO part (HYB: the COO entries of a row come after its ELL entries)
+    for (int64_t s = 0; s < v.k; ++s) {
+        const int c = v.ell_col[s * v.ld + row];
+        if (c >= 0) { ocol[pos] = c; oval[pos] = v.ell_val[s * v.ld + row]; ++pos; }
+    }
+    if (v.nnz_coo > 0) {
+        for (int64_t q = coo_lower_bound(v.coo_row, v.nnz_coo, row); q < v.nnz_coo && v.coo_row[q] == row; ++q) {
+            ocol[pos] = v.coo_col[q]; oval[pos] = v.coo_val[q]; ++pos;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host side
+struct TempCsr {   // device arrays of a rebuilt CSR; freed unless handed over
+    hipStream_t s;
+    int32_t *row_ptr = nullptr, *col = nullptr;
+    void *val = nullptr;
+    int64_t nnz = 0;
+    explicit TempCsr(hipStream_t st) : s(st) {}
+    ~TempCsr() { dev_free(row_ptr, s); dev_free(col, s); dev_free(val, s); }
+    void release() { row_ptr = nullptr; col = nullptr; val = nullptr; }
+};
+
+template <typename T>
+static mo_status rebuild_csr(const mo_matrix &a, TempCsr &out, hipStream_t s)
+{
+    const View<T> v = make_view<T>(a);
+    Scratch scr(s);
+    int32_t *len = (int32_t *)scr.get((size_t)a.m * 4);
+    void *tmp = scr.get(scan_tmp_bytes(a.m));
+    out.row_ptr = (int32_t *)dev_alloc((size_t)(a.m + 1) * 4, s);
+    if (!len || !tmp || !out.row_ptr) return MO_E_ALLOC;
+    const unsigned rb = (unsigned)((a.m + FB - 1) / FB);
+    hipLaunchKernelGGL(k_len_any<T>, dim3(rb), dim3(FB), 0, s, v, len);
+    MO_LAUNCH_CHECK();
+    MO_TRY(exclusive_scan_i32(len, out.row_ptr, a.m, tmp, s));
+    int32_t total = 0;
+    MO_HIP(hipMemcpyAsync(&total, out.row_ptr + a.m, 4, hipMemcpyDeviceToHost, s));
+    MO_HIP(hipStreamSynchronize(s));
+    out.nnz = total;
+    out.col = (int32_t *)dev_alloc((size_t)(total > 0 ? total : 1) * 4, s);
+    out.val = dev_alloc((size_t)(total > 0 ? total : 1) * sizeof(T), s);
+    if (!out.col || !out.val) return MO_E_ALLOC;
+    hipLaunchKernelGGL(k_fill_csr_any<T>, dim3(rb), dim3(FB), 0, s, v, out.row_ptr, out.col, (T *)out.val);
+    MO_LAUNCH_CHECK();
+    MO_HIP(hipStreamSynchronize(s));   // scratch is released on return
+    return MO_OK;
+}
+
+static mo_status switch_impl(const mo_matrix &a, mo_format fmt, const mo_params &p, mo_matrix **out, hipStream_t s)
+{
+    TempCsr t(s);
+    MO_TRY(a.dtype == MO_F32 ? rebuild_csr<float>(a, t, s) : rebuild_csr<double>(a, t, s));
+    mo_csr view{a.m, a.n, t.nnz, t.row_ptr, t.col, t.val, a.dtype};
+    Scratch scr(s);
+    Analysis an;
+    MO_TRY(analyse(view, p, fmt == MO_DIA || fmt == MO_HDC, &an, scr, s));
+    mo_matrix *h = nullptr;
+    MO_TRY(convert_impl(view, fmt, p, an, &h, s));
+    if (fmt == MO_CSR) {   // the CSR handle borrows these arrays: hand them over
+        h->owned.push_back(t.row_ptr); h->owned.push_back(t.col); h->owned.push_back(t.val);
+        t.release();
+    }
+    *out = h;
+    return MO_OK;
+}
+
+template <typename T>
+static mo_status features_any(const mo_matrix &a, const mo_params &p, Counters *h_out, unsigned long long *nnz_out, hipStream_t s)
+{
+    const View<T> v = make_view<T>(a);
+    Scratch scr(s);
+    const int64_t ndiag = a.m + a.n - 1;
+    int32_t *len = (int32_t *)scr.get((size_t)a.m * 4);
+    uint32_t *hist = (uint32_t *)scr.get((size_t)ndiag * 4);
+    Counters *ctr = (Counters *)scr.get(sizeof(Counters) + 8);
+    if (!len || !hist || !ctr) return MO_E_ALLOC;
+    unsigned long long *total = (unsigned long long *)(ctr + 1);
+    hipLaunchKernelGGL(k_init_counters, dim3(1), dim3(64), 0, s, ctr);
+    MO_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(ndiag + 2, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, 0u);
+    MO_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, (uint32_t *)total, (int64_t)2, 0u);
+    MO_LAUNCH_CHECK();
+    const unsigned rb = (unsigned)((a.m + FB - 1) / FB);
+    hipLaunchKernelGGL(k_len_any<T>, dim3(rb), dim3(FB), 0, s, v, len);
+    MO_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_len_stats, dim3(grid_for(a.m, FB * 4, 512)), dim3(FB), 0, s, len, a.m, ctr, total);
+    MO_LAUNCH_CHECK();
+    if (v.nd > 0) {
+        hipLaunchKernelGGL(k_hist_dia<T>, dim3((unsigned)v.nd, grid_for(a.m, FB * 8, 256)), dim3(FB), 0, s, v, hist);
+        MO_LAUNCH_CHECK();
+    }
+    if (v.k > 0 || v.nnz_coo > 0 || v.csr_row_ptr) {
+        constexpr int64_t BLOCKS = 2048;
+        int64_t rpb = (a.m + BLOCKS - 1) / BLOCKS;
+        rpb = ((rpb + FB - 1) / FB) * FB;
+        const int64_t nblk = (a.m + rpb - 1) / rpb;
+        const int64_t cpb = (v.nnz_coo + nblk - 1) / nblk;
+        hipLaunchKernelGGL(k_hist_parts<T>, dim3((unsigned)nblk), dim3(FB), 0, s, v, rpb, cpb, hist);
+        MO_LAUNCH_CHECK();
+    }
+    const int64_t mn = a.m < a.n ? a.m : a.n;
+    hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
+    MO_LAUNCH_CHECK();
+    struct { Counters c; unsigned long long total; } host;
+    MO_HIP(hipMemcpyAsync(&host, ctr, sizeof(Counters) + 8, hipMemcpyDeviceToHost, s));
+    MO_HIP(hipStreamSynchronize(s));
+    *h_out = host.c;
+    *nnz_out = host.total;
+    return MO_OK;
+}
+
+}  // namespace mo
+
+using namespace mo;
+
+extern "C" {
+
+mo_status mo_switch(const mo_matrix *a, mo_format fmt, const mo_params *params, mo_matrix **out, void *stream)
+{
+    if (!out) return MO_E_NULL;
+    *out = nullptr;
+    if (!a) return MO_E_NULL;
+    if ((int)fmt < 0 || (int)fmt >= MO_NUM_FORMATS) return MO_E_FORMAT;
+    mo_params p;
+    MO_TRY(check_params(params, &p));
+    return switch_impl(*a, fmt, p, out, (hipStream_t)stream);
+}
+
+mo_status mo_matrix_features(const mo_matrix *a, const mo_params *params, double out[MO_NUM_FEATURES], mo_feature_ints *ints_opt,
+                             void *stream)
+{
+    if (!a || !out) return MO_E_NULL;
+    mo_params p;
+    MO_TRY(check_params(params, &p));
+    Counters c;
+    unsigned long long nnz = 0;
+    MO_TRY(a->dtype == MO_F32 ? features_any<float>(*a, p, &c, &nnz, (hipStream_t)stream)
+                              : features_any<double>(*a, p, &c, &nnz, (hipStream_t)stream));
+    // same finalisation as mo_features (Table I), from exact integers
+    const unsigned __int128 num = (unsigned __int128)a->m * (unsigned __int128)c.sum_sq - (unsigned __int128)nnz * (unsigned __int128)nnz;
+    const double md = (double)a->m, nd = (double)a->n, zd = (double)nnz;
+    const double mm = md * md;
+    const double var = (double)num / mm;
+    out[0] = md; out[1] = nd; out[2] = zd;
+    out[3] = zd / md;
+    const double mn = md * nd;
+    out[4] = zd / mn;
+    out[5] = (double)c.max_row; out[6] = (double)c.min_row;
+    out[7] = std::sqrt(var);
+    out[8] = (double)c.n_diag; out[9] = (double)c.n_true;
+    if (ints_opt) {
+        ints_opt->m = a->m; ints_opt->n = a->n; ints_opt->nnz = (int64_t)nnz;
+        ints_opt->max_row = (int64_t)c.max_row; ints_opt->min_row = (int64_t)c.min_row;
+        ints_opt->n_diag = (int64_t)c.n_diag; ints_opt->n_true_diag = (int64_t)c.n_true;
+        ints_opt->sum_sq_row = c.sum_sq;
+    }
+    return MO_OK;
+}
+
+}  // extern "C"

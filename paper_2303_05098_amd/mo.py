@@ -31,7 +31,7 @@ MO_F32, MO_F64 = 0, 1
  MO_E_MODEL, MO_E_PARAM) = range(11)
 
 EXPORTS = ("mo_default_params", "mo_features", "mo_convert", "mo_spmv", "mo_tune", "mo_pick", "mo_model_load",
-           "mo_model_free", "mo_model_info", "mo_select", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
+           "mo_model_free", "mo_model_info", "mo_select", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
            "mo_strerror", "mo_last_hip_error")
 
 
@@ -80,6 +80,8 @@ lib.mo_default_params.restype = None
 lib.mo_default_params.argtypes = [C.POINTER(mo_params)]
 lib.mo_features.argtypes = [C.POINTER(mo_csr), C.POINTER(mo_params), C.POINTER(C.c_double), C.POINTER(mo_feature_ints), C.c_void_p]
 lib.mo_convert.argtypes = [C.POINTER(mo_csr), C.c_int, C.POINTER(mo_params), C.POINTER(C.c_void_p), C.c_void_p]
+lib.mo_switch.argtypes = [C.c_void_p, C.c_int, C.POINTER(mo_params), C.POINTER(C.c_void_p), C.c_void_p]
+lib.mo_matrix_features.argtypes = [C.c_void_p, C.POINTER(mo_params), C.POINTER(C.c_double), C.POINTER(mo_feature_ints), C.c_void_p]
 lib.mo_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
 lib.mo_tune.argtypes = [C.POINTER(mo_csr), C.POINTER(mo_params), C.POINTER(mo_tune_opts), C.POINTER(C.c_int),
                         C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
@@ -234,6 +236,20 @@ def mo_convert(a: Csr, fmt: int, params=None, stream=None) -> Matrix:
     st = a.struct()
     _check(lib.mo_convert(C.byref(st), int(fmt), _params(params), C.byref(h), _stream_ptr(stream)), "mo_convert")
     return Matrix(h, keep=a if fmt == MO_CSR else None)
+
+
+def mo_switch(a: Matrix, fmt: int, params=None, stream=None) -> Matrix:
+    h = C.c_void_p()
+    _check(lib.mo_switch(a.handle, int(fmt), _params(params), C.byref(h), _stream_ptr(stream)), "mo_switch")
+    return Matrix(h)
+
+
+def mo_matrix_features(a: Matrix, params=None, stream=None):
+    """-> (features float64[10], ints dict) of a matrix in whatever format the handle holds"""
+    out = (C.c_double * 10)()
+    ints = mo_feature_ints()
+    _check(lib.mo_matrix_features(a.handle, _params(params), out, C.byref(ints), _stream_ptr(stream)), "mo_matrix_features")
+    return np.array(list(out), dtype=np.float64), {k: int(getattr(ints, k)) for k, _ in mo_feature_ints._fields_}
 
 
 def mo_spmv(a: Matrix, x: torch.Tensor, y: torch.Tensor, stream=None) -> None:

@@ -88,7 +88,10 @@ def check_arrays(name, e, m, n, ti, tj, ta, params, hyb=(1, 3), td=(1, 2)):
         assert e["csr_val"].astype(np.float64).tobytes() == h["csr_val"].tobytes()
         assert e["nnz_csr"] == h["csr_col"].shape[0]
     if fmt == mo.MO_CSR:
-        assert np.array_equal(e["csr_row_ptr"], rp_of(ti, m)) and np.array_equal(e["csr_col"], tj)
+        wrp, wc, wv = ref.to_csr(m, ti, tj, ta)
+        assert np.array_equal(e["csr_row_ptr"], wrp) and np.array_equal(e["csr_col"], wc)
+        assert e["csr_val"].astype(np.float64).tobytes() == wv.tobytes()
+        assert np.array_equal(wrp, rp_of(ti, m))
 
 
 def rp_of(ti, m):
