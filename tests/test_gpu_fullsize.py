@@ -108,6 +108,18 @@ def run_config(c, dtype, expect_infeasible=()):
         assert gpu_spmv(h, x, m, dtype).tobytes() == y.tobytes()
         if fmt != mo.MO_CSR:
             check_sampled(h.export(), rp, ci, v, dtype, 100 + c, m, n)
+        # features gathered from the held format, and the way back to CSR: no value of these inputs is 0, so both
+        # must reproduce what the CSR input gives, bit for bit
+        assert np.count_nonzero(v) == rp[-1]
+        fh, ih = mo.mo_matrix_features(h)
+        assert fh.tobytes() == fo.tobytes() and ih == io, mo.FORMAT_NAMES[fmt]
+        if fmt != mo.MO_CSR:
+            g = mo.mo_switch(h, mo.MO_CSR)
+            e = g.export()
+            assert np.array_equal(e["csr_row_ptr"], rp) and np.array_equal(e["csr_col"], ci)
+            assert e["csr_val"].tobytes() == v.tobytes(), mo.FORMAT_NAMES[fmt]
+            del e
+            g.free()
         h.free()
         torch.cuda.empty_cache()
     return f, ints
