@@ -158,6 +158,35 @@ mo_status mo_model_info(const mo_model *model, int32_t *n_trees, int32_t *n_node
  * tree is a forest of one. */
 mo_status mo_select(const mo_model *model, const double features[MO_NUM_FEATURES], mo_format *out);
 
+/* Offline training stage on the host (Section V; hyper-parameters of Table III).  A tree is grown greedily: at every
+ * node the admissible cut (between two distinct neighbouring values of one feature, at least min_samples_leaf rows on
+ * each side) with the lowest weighted impurity is taken, rows with value <= threshold go left; a node is a leaf at
+ * max_depth (< 0: no limit), when it holds one class, fewer than min_samples_split or fewer than 2*min_samples_leaf
+ * rows, or no admissible cut.  With max_features < 10 the features of a node are tried in a seeded random order until
+ * max_features were tried and a cut is known.  bootstrap: every tree trains on n rows drawn with replacement.  Equal
+ * costs resolve to the lower feature index, then the lower threshold; a leaf predicts its most frequent class, ties to
+ * the lowest id.  The result is a pure function of the data and the options (seed included). */
+typedef enum { MO_GINI = 0, MO_ENTROPY = 1 } mo_criterion;
+typedef struct {
+    int32_t n_estimators;      /* >= 1; 1 with bootstrap = 0 and max_features = 10 is a plain decision tree */
+    int32_t bootstrap;         /* 0 or 1 */
+    int32_t max_depth;         /* < 0: unlimited */
+    int32_t min_samples_leaf;  /* >= 1 */
+    int32_t min_samples_split; /* >= 2 */
+    int32_t max_features;      /* 1 .. 10 */
+    int32_t criterion;         /* mo_criterion */
+    uint64_t seed;
+} mo_fit_opts;
+/* The baseline column of Table III: 100 estimators, bootstrap, no depth limit, leaf 1, split 2, 10 features, gini; seed 0. */
+void mo_default_fit_opts(mo_fit_opts *out);
+/* features: host, n rows of 10 doubles (row-major, no NaN); labels: host, n format ids in [0, 6); 1 <= n <= 2^20.
+ * NULL opts = the defaults.  The model is owned by the caller (mo_model_free). */
+mo_status mo_model_fit(const double *features, const int32_t *labels, int64_t n, const mo_fit_opts *opts, mo_model **out);
+/* Writes the model in the file format mo_model_load reads.  MO_E_MODEL when the file cannot be written. */
+mo_status mo_model_save(const mo_model *model, const char *path);
+/* mo_select for n feature rows at once (host, n rows of 10 doubles -> n format ids). */
+mo_status mo_predict(const mo_model *model, const double *features, int64_t n, int32_t *out);
+
 /* Run-time switching between any two formats (Section II-C): rebuilds CSR from whatever `a` holds (row lengths ->
  * exclusive scan -> rows written in ascending column order) and converts that to `fmt`.  A handle produced with
  * fmt = MO_CSR OWNS its arrays.  A DIA slab cannot tell a stored zero from padding, so positions holding exactly 0

@@ -12,7 +12,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmo.so")
 
 SOURCES = ["api.hip", "features.hip", "scan.hip", "convert.hip", "spmv_csr.hip", "spmv_coo.hip", "spmv_dia.hip",
-           "spmv_ell.hip", "switch.hip", "model.cpp"]
+           "spmv_ell.hip", "switch.hip", "model.cpp", "fit.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
@@ -24,7 +24,7 @@ DEVICE = ["--offload-arch=" + ARCH, "-Xclang", "-target-feature", "-Xclang", "-p
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
-    cmd = [HIPCC] + COMMON + (DEVICE if src.endswith(".hip") else ["-x", "c++"]) + ["-c", path, "-o", obj]
+    cmd = [HIPCC] + COMMON + (DEVICE if src.endswith(".hip") else ["-x", "c++", "-ffp-contract=off"]) + ["-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")

@@ -5,13 +5,7 @@
 #include <vector>
 
 #include "mo.h"
-
-struct mo_model {
-    int32_t n_trees = 0;
-    std::vector<int32_t> tree_off;   // n_trees + 1
-    std::vector<int32_t> feature, left, right, klass;
-    std::vector<double> threshold;
-};
+#include "model.hpp"
 
 namespace {
 
@@ -89,9 +83,26 @@ mo_status mo_model_info(const mo_model *model, int32_t *n_trees, int32_t *n_node
     return MO_OK;
 }
 
-mo_status mo_select(const mo_model *model, const double features[MO_NUM_FEATURES], mo_format *out)
+mo_status mo_model_save(const mo_model *model, const char *path)
 {
-    if (!model || !features || !out) return MO_E_NULL;
+    if (!model || !path) return MO_E_NULL;
+    FILE *f = std::fopen(path, "wb");
+    if (!f) return MO_E_MODEL;
+    const int32_t hdr[4] = {1, MO_NUM_FEATURES, MO_NUM_FORMATS, model->n_trees};
+    bool ok = std::fwrite("MOMDL1\0\0", 1, 8, f) == 8 && std::fwrite(hdr, 4, 4, f) == 4;
+    for (int32_t t = 0; t < model->n_trees && ok; ++t) {
+        const int32_t base = model->tree_off[t], nn = model->tree_off[t + 1] - base;
+        const size_t k = (size_t)nn;
+        ok = std::fwrite(&nn, 4, 1, f) == 1 && std::fwrite(&model->feature[base], 4, k, f) == k &&
+             std::fwrite(&model->threshold[base], 8, k, f) == k && std::fwrite(&model->left[base], 4, k, f) == k &&
+             std::fwrite(&model->right[base], 4, k, f) == k && std::fwrite(&model->klass[base], 4, k, f) == k;
+    }
+    if (std::fclose(f) != 0) ok = false;
+    return ok ? MO_OK : MO_E_MODEL;
+}
+
+static int vote(const mo_model *model, const double *features)
+{
     int64_t votes[MO_NUM_FORMATS] = {0, 0, 0, 0, 0, 0};
     for (int32_t t = 0; t < model->n_trees; ++t) {
         const int32_t base = model->tree_off[t];
@@ -105,7 +116,21 @@ mo_status mo_select(const mo_model *model, const double features[MO_NUM_FEATURES
     int best = 0;
     for (int c = 1; c < MO_NUM_FORMATS; ++c)
         if (votes[c] > votes[best]) best = c;
-    *out = (mo_format)best;
+    return best;
+}
+
+mo_status mo_select(const mo_model *model, const double features[MO_NUM_FEATURES], mo_format *out)
+{
+    if (!model || !features || !out) return MO_E_NULL;
+    *out = (mo_format)vote(model, features);
+    return MO_OK;
+}
+
+mo_status mo_predict(const mo_model *model, const double *features, int64_t n, int32_t *out)
+{
+    if (!model || (n > 0 && (!features || !out))) return MO_E_NULL;
+    if (n < 0) return MO_E_SHAPE;
+    for (int64_t i = 0; i < n; ++i) out[i] = vote(model, features + i * MO_NUM_FEATURES);
     return MO_OK;
 }
 

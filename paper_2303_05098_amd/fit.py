@@ -1,92 +1,35 @@
-"""Host-side training of the format classifier (Section V and VII-C of the paper: a decision tree over the ten
-features, evaluated with 5-fold cross-validation; accuracy and balanced accuracy as in Section VII-C).
-
-Plain numpy CART, written for a few hundred samples:
-  * criterion gini, threshold = midpoint between consecutive distinct values of a feature,
-  * best split = lowest weighted impurity; ties -> lowest feature index, then lowest threshold,
-  * a node becomes a leaf when it is pure, at max_depth, smaller than 2 * min_samples_leaf, or has no valid split,
-  * leaf class = majority of the training samples at the leaf, ties -> lowest class id.
-The tree comes out in the array layout of the binary model file (children after their parent), ready for
-``mo.write_model``.  Nothing here runs on the GPU.
+"""Model selection around the library's host trainer (Section VII-C): stratified train / test split and folds,
+accuracy and balanced accuracy, 5-fold cross-validation and the exhaustive grid search over the hyper-parameters of
+Table III.  Trees and forests are fitted by ``mo.mo_model_fit`` and evaluated by ``mo.mo_predict`` (native host code
+in the library); this module only deals rows to folds, loops over the grid and counts hits.
 """
 from __future__ import annotations
 
+import itertools
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
-from . import synth
+from . import mo, synth
 
 N_CLASSES = 6
 
+# Baseline column of Table III (scikit-learn's defaults at the time: 100 estimators, bootstrap, unlimited depth).
+BASELINE_FOREST = dict(n_estimators=100, bootstrap=1, max_depth=-1, min_samples_leaf=1, min_samples_split=2,
+                       max_features=10, criterion="gini")
+BASELINE_TREE = dict(n_estimators=1, bootstrap=0, max_depth=-1, min_samples_leaf=1, min_samples_split=2,
+                     max_features=10, criterion="gini")
 
-def _gini_from_counts(counts: np.ndarray) -> np.ndarray:
-    tot = counts.sum(axis=-1)
-    with np.errstate(divide="ignore", invalid="ignore"):
-        g = 1.0 - ((counts / tot[..., None]) ** 2).sum(axis=-1)
-    return np.where(tot > 0, g, 0.0)
-
-
-def _best_split(X: np.ndarray, y: np.ndarray, min_leaf: int):
-    n, nf = X.shape
-    best = None   # (impurity, feature, threshold)
-    onehot = np.eye(N_CLASSES)[y]
-    for f in range(nf):
-        order = np.argsort(X[:, f], kind="stable")
-        xs = X[order, f]
-        left = np.cumsum(onehot[order], axis=0)            # counts with the first i+1 samples on the left
-        total = left[-1]
-        cut = np.nonzero(xs[1:] > xs[:-1])[0]              # split between i and i+1
-        if min_leaf > 1:
-            cut = cut[(cut + 1 >= min_leaf) & (n - cut - 1 >= min_leaf)]
-        if cut.size == 0:
-            continue
-        lc = left[cut]
-        rc = total[None, :] - lc
-        nl = (cut + 1).astype(np.float64)
-        nr = n - nl
-        imp = (nl * _gini_from_counts(lc) + nr * _gini_from_counts(rc)) / n
-        i = int(np.argmin(imp))                            # first minimum = lowest threshold on ties
-        cand = (float(imp[i]), f, 0.5 * (float(xs[cut[i]]) + float(xs[cut[i] + 1])))
-        if best is None or cand[0] < best[0] - 1e-15:
-            best = cand
-    return best
-
-
-def fit_tree(X, y, max_depth: int = 6, min_samples_leaf: int = 1) -> dict:
-    """-> dict(feature, threshold, left, right, klass) in model-file layout."""
-    X = np.asarray(X, dtype=np.float64)
-    y = np.asarray(y, dtype=np.int64)
-    feature, threshold, left, right, klass = [], [], [], [], []
-
-    def grow(idx: np.ndarray, depth: int) -> int:
-        me = len(feature)
-        counts = np.bincount(y[idx], minlength=N_CLASSES)
-        feature.append(-1); threshold.append(0.0); left.append(-1); right.append(-1); klass.append(int(np.argmax(counts)))
-        if depth >= max_depth or np.count_nonzero(counts) <= 1 or idx.size < 2 * min_samples_leaf:
-            return me
-        split = _best_split(X[idx], y[idx], min_samples_leaf)
-        if split is None:
-            return me
-        _, f, t = split
-        go_left = X[idx, f] <= t
-        feature[me], threshold[me], klass[me] = f, t, -1
-        left[me] = grow(idx[go_left], depth + 1)
-        right[me] = grow(idx[~go_left], depth + 1)
-        return me
-
-    grow(np.arange(X.shape[0]), 0)
-    return dict(feature=feature, threshold=threshold, left=left, right=right, klass=klass)
-
-
-def predict_tree(tree: dict, X) -> np.ndarray:
-    """Host prediction for training-time bookkeeping (the deployed path is mo_select in the library)."""
-    X = np.asarray(X, dtype=np.float64)
-    out = np.zeros(X.shape[0], dtype=np.int64)
-    for i, x in enumerate(X):
-        node = 0
-        while tree["feature"][node] >= 0:
-            node = tree["left"][node] if x[tree["feature"][node]] <= tree["threshold"][node] else tree["right"][node]
-        out[i] = tree["klass"][node]
-    return out
+# Search space: the ranges the tuned column of Table III spans (20-90 estimators, depth 10-21, leaf 1-3, split
+# 2 / 5 / 10, 4-10 features, both criteria, with and without bootstrap), thinned to a grid that one host searches
+# in about a minute on a few hundred records.
+FOREST_GRID = dict(n_estimators=[20, 50, 100], bootstrap=[0, 1], max_depth=[5, 10, 15, -1],
+                   min_samples_leaf=[1, 2, 3], min_samples_split=[2, 10], max_features=[4, 7, 10],
+                   criterion=["gini", "entropy"])
+TREE_GRID = dict(n_estimators=[1], bootstrap=[0], max_depth=[2, 3, 4, 5, 6, 8, 10, 12, 16, 20, -1],
+                 min_samples_leaf=[1, 2, 3, 5, 8], min_samples_split=[2, 5, 10, 20], max_features=[10],
+                 criterion=["gini", "entropy"])
 
 
 def stratified_folds(y, k: int = 5, seed: int = synth.BASE_SEED) -> np.ndarray:
@@ -102,6 +45,11 @@ def stratified_folds(y, k: int = 5, seed: int = synth.BASE_SEED) -> np.ndarray:
     return fold
 
 
+def train_test_split(y, test_every: int = 5, seed: int = synth.BASE_SEED + 1) -> np.ndarray:
+    """Boolean mask of the test set: a stratified 1 / test_every share (80 % / 20 % as in Section VII "Setup")."""
+    return stratified_folds(y, test_every, seed) == 0
+
+
 def accuracy(y_true, y_pred) -> float:
     y_true, y_pred = np.asarray(y_true), np.asarray(y_pred)
     return float(np.mean(y_true == y_pred)) if y_true.size else float("nan")
@@ -114,18 +62,68 @@ def balanced_accuracy(y_true, y_pred) -> float:
     return float(np.mean(rec)) if rec else float("nan")
 
 
-def cross_validate(X, y, k: int = 5, max_depth: int = 6, min_samples_leaf: int = 1, seed: int = synth.BASE_SEED) -> dict:
+def fit(X, y, seed: int = 0, **opts) -> "mo.Model":
+    return mo.mo_model_fit(X, y, seed=seed, **opts)
+
+
+def cross_validate(X, y, k: int = 5, seed: int = synth.BASE_SEED, fold=None, **opts) -> dict:
+    """k-fold CV of one hyper-parameter setting: every sample is predicted by the model that did not see it."""
     X = np.asarray(X, dtype=np.float64)
     y = np.asarray(y, dtype=np.int64)
-    fold = stratified_folds(y, k, seed)
+    fold = stratified_folds(y, k, seed) if fold is None else fold
     pred = np.zeros_like(y)
     per_fold = []
     for j in range(k):
         tr, te = fold != j, fold == j
         if not te.any() or not tr.any():
             continue
-        tree = fit_tree(X[tr], y[tr], max_depth, min_samples_leaf)
-        pred[te] = predict_tree(tree, X[te])
+        model = mo.mo_model_fit(X[tr], y[tr], seed=seed + j, **opts)
+        pred[te] = mo.mo_predict(model, X[te])
+        model.free()
         per_fold.append(dict(fold=j, n=int(te.sum()), accuracy=accuracy(y[te], pred[te]),
                              balanced_accuracy=balanced_accuracy(y[te], pred[te])))
     return dict(pred=pred, fold=fold, per_fold=per_fold, accuracy=accuracy(y, pred), balanced_accuracy=balanced_accuracy(y, pred))
+
+
+def grid_points(grid: dict) -> list:
+    keys = list(grid)
+    return [dict(zip(keys, vals)) for vals in itertools.product(*(grid[k] for k in keys))]
+
+
+def model_cost(o: dict) -> tuple:
+    """Prediction cost proxy used to break score ties: fewer trees, then shallower (unlimited counts as deepest)."""
+    return (o["n_estimators"], 1 << 30 if o["max_depth"] < 0 else o["max_depth"])
+
+
+def grid_search(X, y, grid: dict, k: int = 5, seed: int = synth.BASE_SEED, score: str = "balanced_accuracy",
+                workers: int | None = None) -> dict:
+    """Exhaustive search (Section VII-C): the whole k-fold CV for every grid point, on the same folds; the winner has
+    the highest mean-over-samples `score`, ties to the cheaper model, then to the earlier grid point."""
+    X = np.asarray(X, dtype=np.float64)
+    y = np.asarray(y, dtype=np.int64)
+    fold = stratified_folds(y, k, seed)
+    points = grid_points(grid)
+
+    def one(o):
+        cv = cross_validate(X, y, k, seed, fold, **o)
+        return cv["accuracy"], cv["balanced_accuracy"]
+
+    # the trainer is native code called through ctypes, which releases the interpreter lock: threads scale
+    with ThreadPoolExecutor(max_workers=workers or min(16, os.cpu_count() or 1)) as ex:
+        scores = list(ex.map(one, points))
+    col = 1 if score == "balanced_accuracy" else 0
+    order = sorted(range(len(points)), key=lambda i: (-scores[i][col], model_cost(points[i]), i))
+    best = order[0]
+    return dict(best=points[best], best_cv_accuracy=scores[best][0], best_cv_balanced_accuracy=scores[best][1],
+                n_points=len(points), score=score,
+                table=[dict(opts=points[i], cv_accuracy=scores[i][0], cv_balanced_accuracy=scores[i][1]) for i in order])
+
+
+def evaluate(X_train, y_train, X_test, y_test, seed: int = 0, **opts) -> dict:
+    """Fit on the full training set, score on the held-out test set (the two score columns of Table III)."""
+    model = mo.mo_model_fit(X_train, y_train, seed=seed, **opts)
+    pred = mo.mo_predict(model, X_test)
+    nt, nn = model.info()
+    model.free()
+    return dict(opts=opts, accuracy=accuracy(y_test, pred), balanced_accuracy=balanced_accuracy(y_test, pred),
+                n_trees=nt, n_nodes=nn, pred=pred)

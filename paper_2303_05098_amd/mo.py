@@ -31,7 +31,7 @@ MO_F32, MO_F64 = 0, 1
  MO_E_MODEL, MO_E_PARAM) = range(11)
 
 EXPORTS = ("mo_default_params", "mo_features", "mo_convert", "mo_spmv", "mo_tune", "mo_pick", "mo_model_load",
-           "mo_model_free", "mo_model_info", "mo_select", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
+           "mo_model_free", "mo_model_info", "mo_select", "mo_default_fit_opts", "mo_model_fit", "mo_model_save", "mo_predict", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
            "mo_strerror", "mo_last_hip_error")
 
 
@@ -60,6 +60,12 @@ class mo_feature_ints(C.Structure):
 
 class mo_tune_opts(C.Structure):
     _fields_ = [("warmups", C.c_int32), ("reps", C.c_int32)]
+
+
+class mo_fit_opts(C.Structure):
+    _fields_ = [("n_estimators", C.c_int32), ("bootstrap", C.c_int32), ("max_depth", C.c_int32),
+                ("min_samples_leaf", C.c_int32), ("min_samples_split", C.c_int32), ("max_features", C.c_int32),
+                ("criterion", C.c_int32), ("seed", C.c_uint64)]
 
 
 class mo_matrix_view(C.Structure):
@@ -91,6 +97,11 @@ lib.mo_model_free.restype = None
 lib.mo_model_free.argtypes = [C.c_void_p]
 lib.mo_model_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
 lib.mo_select.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int)]
+lib.mo_default_fit_opts.restype = None
+lib.mo_default_fit_opts.argtypes = [C.POINTER(mo_fit_opts)]
+lib.mo_model_fit.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(mo_fit_opts), C.POINTER(C.c_void_p)]
+lib.mo_model_save.argtypes = [C.c_void_p, C.c_char_p]
+lib.mo_predict.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
 lib.mo_matrix_export.argtypes = [C.c_void_p, C.POINTER(mo_matrix_view)]
 lib.mo_matrix_free.restype = None
 lib.mo_matrix_free.argtypes = [C.c_void_p]
@@ -306,6 +317,65 @@ def mo_select(model: Model, features) -> int:
     out = C.c_int(-1)
     _check(lib.mo_select(model.handle, arr, C.byref(out)), "mo_select")
     return out.value
+
+
+MO_GINI, MO_ENTROPY = 0, 1
+CRITERIA = {"gini": MO_GINI, "entropy": MO_ENTROPY}
+
+
+def fit_opts(**kw) -> mo_fit_opts:
+    """The library's defaults (baseline column of Table III) with the given fields replaced."""
+    o = mo_fit_opts()
+    lib.mo_default_fit_opts(C.byref(o))
+    for k, v in kw.items():
+        if k == "criterion" and isinstance(v, str):
+            v = CRITERIA[v]
+        if not hasattr(o, k):
+            raise TypeError(f"unknown training option {k}")
+        setattr(o, k, int(v))
+    return o
+
+
+def mo_model_fit(X, y, **opts) -> Model:
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    if X.ndim != 2 or X.shape[1] != 10 or y.shape != (X.shape[0],):
+        raise ValueError("X must be n x 10 and y of length n")
+    o = fit_opts(**opts)
+    h = C.c_void_p()
+    _check(lib.mo_model_fit(X.ctypes.data, y.ctypes.data, X.shape[0], C.byref(o), C.byref(h)), "mo_model_fit")
+    return Model(h)
+
+
+def mo_model_save(model: Model, path: str) -> None:
+    _check(lib.mo_model_save(model.handle, os.fsencode(path)), "mo_model_save")
+
+
+def mo_predict(model: Model, X) -> np.ndarray:
+    X = np.ascontiguousarray(X, dtype=np.float64).reshape(-1, 10)
+    out = np.empty(X.shape[0], dtype=np.int32)
+    _check(lib.mo_predict(model.handle, X.ctypes.data, X.shape[0], out.ctypes.data), "mo_predict")
+    return out
+
+
+def read_model(path: str) -> list:
+    """Parse a model file back into the list-of-dicts form write_model takes."""
+    raw = open(path, "rb").read()
+    if raw[:8] != b"MOMDL1\0\0":
+        raise ValueError("not a model file")
+    hdr = np.frombuffer(raw, dtype="<i4", count=4, offset=8)
+    pos, trees = 24, []
+    for _ in range(int(hdr[3])):
+        nn = int(np.frombuffer(raw, dtype="<i4", count=1, offset=pos)[0])
+        pos += 4
+        t = {}
+        for key, dt, sz in (("feature", "<i4", 4), ("threshold", "<f8", 8), ("left", "<i4", 4), ("right", "<i4", 4), ("klass", "<i4", 4)):
+            t[key] = np.frombuffer(raw, dtype=dt, count=nn, offset=pos).tolist()
+            pos += nn * sz
+        trees.append(t)
+    if pos != len(raw):
+        raise ValueError("trailing bytes in model file")
+    return trees
 
 
 def write_model(path: str, trees) -> None:

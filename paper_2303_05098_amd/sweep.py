@@ -2,13 +2,15 @@
 matrices.
 
     python -m paper_2303_05098_amd.sweep run --first 0 --count 64 --out gpurun_out/sweep_000.jsonl     (GPU)
-    python -m paper_2303_05098_amd.sweep fit gpurun_out/sweep_*.jsonl --model paper_2303_05098_amd/models/mi355x_tree.bin
+    python -m paper_2303_05098_amd.sweep fit gpurun_out/sweep_*.jsonl --model paper_2303_05098_amd/models/mi355x_forest.bin
 
 ``run``: per matrix, features on the GPU (mo_features), then the run-first tuner (mo_tune, 1000 timed SpMVs per
-feasible format as in Section VII-A); label = format with the smallest time.  ``fit``: stratified 5-fold
-cross-validation of a depth-limited tree, accuracy and balanced accuracy (Section VII-C), geometric-mean speedup
-over CSR of the true best and of the predicted format (SpMV only, and in the form of Eq. 2 with tuner time
-included), then a tree fitted on all records is written as the model file mo_select loads.
+feasible format as in Section VII-A); label = format with the smallest time.  ``fit``: the model-selection procedure
+of Section VII-C (80 / 20 split, exhaustive grid search with 5-fold cross-validation for a decision tree and a
+random forest, baseline against tuned, accuracy and balanced accuracy on the test set), geometric-mean speedup over
+CSR of the true best and of the predicted format on the test set (SpMV only, and in the form of Eq. 2 with tuner
+time included), tuner cost in CSR SpMVs (Section VII-D); the tuned forest, fitted on the training set, is written
+as the model file mo_select loads.
 """
 from __future__ import annotations
 
@@ -73,43 +75,90 @@ def geomean(v) -> float:
     return float(np.exp(np.mean(np.log(v)))) if v.size else float("nan")
 
 
-def analyse(recs, max_depth: int, min_samples_leaf: int, reps_eq2: int = 1000, t_pred_ms: float = 0.001) -> dict:
-    X = np.array([r["features"] for r in recs], dtype=np.float64)
-    ms = np.array([[np.nan if t is None else t for t in r["ms_per_rep"]] for r in recs], dtype=np.float64)
-    y = np.array([r["best"] for r in recs], dtype=np.int64)
-    cv = fitmod.cross_validate(X, y, 5, max_depth, min_samples_leaf)
-    pred = cv["pred"]
+def _speedups(ms, t_fe, conv, y, pred, t_pred_ms, reps_eq2) -> dict:
+    """Speedups over CSR and tuner cost for the rows given (Section VII-D / VII-E, Eq. 2)."""
+    rows = np.arange(len(y))
     t_csr = ms[:, 1]
-    t_best = ms[np.arange(len(recs)), y]
+    t_best = ms[rows, y]
     # a predicted format that is infeasible for the matrix falls back to CSR, as a deployed tuner would
-    t_pred = ms[np.arange(len(recs)), pred]
-    t_pred = np.where(np.isnan(t_pred), t_csr, t_pred)
-    t_fe = np.array([r["t_fe_ms"] for r in recs])
-    eq2 = (t_csr * reps_eq2) / (t_fe + t_pred_ms + t_pred * reps_eq2)
+    t_sel = ms[rows, pred]
+    t_sel = np.where(np.isnan(t_sel), t_csr, t_sel)
+    eq2 = (t_csr * reps_eq2) / (t_fe + t_pred_ms + t_sel * reps_eq2)
     cost = (t_fe + t_pred_ms) / t_csr
     q = np.percentile(cost, [0, 25, 50, 75, 100])
     # SpMVs after which tuning has paid for itself, conversion included (the paper leaves conversion out of Eq. 2):
-    # smallest n with t_fe + t_pred + t_conv + n * t_pred_fmt < n * t_csr; only where the predicted format is faster
-    conv = np.array([[np.nan if t is None else t for t in r["convert_ms"]] for r in recs], dtype=np.float64)
-    t_conv = conv[np.arange(len(recs)), pred]
-    gain = t_csr - t_pred
+    # smallest n with t_fe + t_pred + t_conv + n * t_sel < n * t_csr; only where the predicted format is faster
+    t_conv = conv[rows, pred]
+    gain = t_csr - t_sel
     pays = (gain > 0) & (pred != 1) & ~np.isnan(t_conv)
     breakeven = np.ceil((t_fe + t_pred_ms + t_conv)[pays] / gain[pays])
     bq = np.percentile(breakeven, [25, 50, 75]) if breakeven.size else [float("nan")] * 3
     return dict(
-        n=len(recs), class_histogram={FORMATS[c]: int((y == c).sum()) for c in range(6)},
-        predicted_histogram={FORMATS[c]: int((pred == c).sum()) for c in range(6)},
-        cv_accuracy=cv["accuracy"], cv_balanced_accuracy=cv["balanced_accuracy"], per_fold=cv["per_fold"],
+        n=int(len(y)),
         geomean_speedup_best_vs_csr=geomean(t_csr / t_best),
-        geomean_speedup_predicted_vs_csr=geomean(t_csr / t_pred),
+        geomean_speedup_predicted_vs_csr=geomean(t_csr / t_sel),
         geomean_speedup_eq2_predicted=geomean(eq2),
         max_speedup_best_vs_csr=float(np.max(t_csr / t_best)),
         mean_speedup_best_vs_csr_where_not_csr=float(np.mean((t_csr / t_best)[y != 1])) if (y != 1).any() else None,
         tuner_cost_in_csr_spmv=dict(mean=float(cost.mean()), std=float(cost.std()), min=float(q[0]), q1=float(q[1]),
                                     q2=float(q[2]), q3=float(q[3]), max=float(q[4])),
-        breakeven_spmvs_incl_conversion=dict(n_matrices=int(pays.sum()), q1=float(bq[0]), q2=float(bq[1]), q3=float(bq[2])),
-        max_depth=max_depth, min_samples_leaf=min_samples_leaf,
-    ), X, y
+        breakeven_spmvs_incl_conversion=dict(n_matrices=int(pays.sum()), q1=float(bq[0]), q2=float(bq[1]), q3=float(bq[2])))
+
+
+def time_select(model, X, rounds: int = 20) -> float:
+    """Host time of one mo_select with this model, in ms (T_PRED of Eq. 2), best of `rounds` passes over X."""
+    from . import mo
+    best = float("inf")
+    for _ in range(rounds):
+        t0 = time.perf_counter()
+        mo.mo_predict(model, X)
+        best = min(best, time.perf_counter() - t0)
+    return best * 1e3 / max(1, len(X))
+
+
+def analyse(recs, tree_grid=None, forest_grid=None, reps_eq2: int = 1000, score: str = "balanced_accuracy"):
+    """The procedure of Section VII-C on the records: stratified 80 / 20 split, grid search with 5-fold CV on the
+    training set for a decision tree and a random forest, refit of the winners on the whole training set, accuracy
+    and balanced accuracy of baseline and tuned models on the test set; then speedups over CSR and the tuner cost
+    for the tuned forest on the test set (Sections VII-D, VII-E).  -> (report, tuned forest model, X, y, test mask)"""
+    from . import mo
+    X = np.array([r["features"] for r in recs], dtype=np.float64)
+    ms = np.array([[np.nan if t is None else t for t in r["ms_per_rep"]] for r in recs], dtype=np.float64)
+    conv = np.array([[np.nan if t is None else t for t in r["convert_ms"]] for r in recs], dtype=np.float64)
+    t_fe = np.array([r["t_fe_ms"] for r in recs])
+    y = np.array([r["best"] for r in recs], dtype=np.int64)
+    test = fitmod.train_test_split(y)
+    Xtr, ytr, Xte, yte = X[~test], y[~test], X[test], y[test]
+
+    def strip(e):
+        return {k: v for k, v in e.items() if k != "pred"}
+
+    out = dict(n=len(recs), n_train=int((~test).sum()), n_test=int(test.sum()),
+               class_histogram={FORMATS[c]: int((y == c).sum()) for c in range(6)}, selection_score=score)
+    tuned = {}
+    for kind, base, grid in (("tree", fitmod.BASELINE_TREE, tree_grid or fitmod.TREE_GRID),
+                             ("forest", fitmod.BASELINE_FOREST, forest_grid or fitmod.FOREST_GRID)):
+        gs = fitmod.grid_search(Xtr, ytr, grid, 5, score=score)
+        cvb = fitmod.cross_validate(Xtr, ytr, 5, **base)
+        eb = fitmod.evaluate(Xtr, ytr, Xte, yte, **base)
+        et = fitmod.evaluate(Xtr, ytr, Xte, yte, **gs["best"])
+        tuned[kind] = et
+        out[kind] = dict(
+            grid={k: list(v) for k, v in grid.items()}, grid_points=gs["n_points"],
+            baseline=dict(cv_accuracy=cvb["accuracy"], cv_balanced_accuracy=cvb["balanced_accuracy"], test=strip(eb)),
+            tuned=dict(cv_accuracy=gs["best_cv_accuracy"], cv_balanced_accuracy=gs["best_cv_balanced_accuracy"], test=strip(et)),
+            runners_up=gs["table"][1:6])
+    model = mo.mo_model_fit(Xtr, ytr, **out["forest"]["tuned"]["test"]["opts"])
+    tree_model = mo.mo_model_fit(Xtr, ytr, **out["tree"]["tuned"]["test"]["opts"])
+    t_pred = time_select(model, X)
+    out["t_pred_ms"] = dict(tuned_forest=t_pred, tuned_tree=time_select(tree_model, X))
+    out["predicted_histogram_test"] = {FORMATS[c]: int((tuned["forest"]["pred"] == c).sum()) for c in range(6)}
+    out["test_set_tuned_forest"] = _speedups(ms[test], t_fe[test], conv[test], yte, tuned["forest"]["pred"], t_pred, reps_eq2)
+    out["test_set_tuned_tree"] = _speedups(ms[test], t_fe[test], conv[test], yte, tuned["tree"]["pred"],
+                                           out["t_pred_ms"]["tuned_tree"], reps_eq2)
+    out["all_records_oracle_choice"] = _speedups(ms, t_fe, conv, y, y, t_pred, reps_eq2)
+    tree_model.free()
+    return out, model, X, y, test
 
 
 def main(argv=None) -> int:
@@ -125,15 +174,16 @@ def main(argv=None) -> int:
     f.add_argument("records", nargs="+")
     f.add_argument("--model", default=None)
     f.add_argument("--report", default=None)
-    f.add_argument("--max-depth", type=int, default=6)
-    f.add_argument("--min-samples-leaf", type=int, default=1)
+    f.add_argument("--score", default="balanced_accuracy", choices=["accuracy", "balanced_accuracy"])
+    f.add_argument("--grid", default=None, help="JSON file {\"tree\": {...}, \"forest\": {...}} replacing the built-in grids")
     args = ap.parse_args(argv)
     if args.cmd == "run":
         run(args.first, args.count, args.out, args.reps, args.n_hi)
         return 0
     paths = [p for pat in args.records for p in sorted(glob.glob(pat))]
     recs = load(paths)
-    rep, X, y = analyse(recs, args.max_depth, args.min_samples_leaf)
+    grids = json.load(open(args.grid)) if args.grid else {}
+    rep, model, X, y, test = analyse(recs, grids.get("tree"), grids.get("forest"), score=args.score)
     print(json.dumps(rep, indent=1))
     if args.report:
         with open(args.report, "w") as fh:
@@ -141,7 +191,7 @@ def main(argv=None) -> int:
     if args.model:
         from . import mo
         os.makedirs(os.path.dirname(os.path.abspath(args.model)), exist_ok=True)
-        mo.write_model(args.model, [fitmod.fit_tree(X, y, args.max_depth, args.min_samples_leaf)])
+        mo.mo_model_save(model, args.model)
     return 0
 
 
