@@ -37,9 +37,18 @@ constexpr int FCAP = 1024;        // entries a wave stages in LDS at a time
 
 __device__ __forceinline__ void count_key(int key, uint32_t n, int *ht_key, uint32_t *ht_cnt, int *ht_full, uint32_t *__restrict__ hist)
 {
-    // once the table has overflowed, single counts skip it: they are almost surely keys that do not repeat
-    if (n == 1u && *ht_full) { atomicAdd(&hist[key], 1u); return; }
-    uint32_t h = ((uint32_t)key * 2654435761u) >> 21;   // 11 bits
+    const uint32_t h = ((uint32_t)key * 2654435761u) >> 21;   // 11 bits
+    // once the table has overflowed, single counts of keys it does not hold skip it: they are almost surely keys
+    // that do not repeat.  Keys it holds still go to LDS: a frequent diagonal must not turn into a stream of
+    // same-address global atomics.
+    if (n == 1u && *ht_full) {
+        for (int p = 0; p < HT_PROBES; ++p) {
+            const int s = (int)((h + p) & (HT_SIZE - 1));
+            if (ht_key[s] == key) { atomicAdd(&ht_cnt[s], 1u); return; }
+        }
+        atomicAdd(&hist[key], 1u);
+        return;
+    }
     for (int p = 0; p < HT_PROBES; ++p) {
         const int s = (int)((h + p) & (HT_SIZE - 1));
         const int old = atomicCAS(&ht_key[s], -1, key);

@@ -45,10 +45,9 @@ static View<T> make_view(const mo_matrix &a)
     return v;
 }
 
-// First position p in the sorted COO row array with coo_row[p] >= r.
-__device__ __forceinline__ int64_t coo_lower_bound(const int32_t *__restrict__ coo_row, int64_t nnz, int64_t r)
+// First position p in [lo, hi) of the sorted COO row array with coo_row[p] >= r (hi if there is none).
+__device__ __forceinline__ int64_t coo_lower_bound(const int32_t *__restrict__ coo_row, int64_t lo, int64_t hi, int64_t r)
 {
-    int64_t lo = 0, hi = nnz;
     while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;
         if ((int64_t)coo_row[mid] < r) lo = mid + 1; else hi = mid;
@@ -60,7 +59,16 @@ __device__ __forceinline__ int64_t coo_lower_bound(const int32_t *__restrict__ c
 template <typename T>
 __global__ __launch_bounds__(FB) void k_len_any(View<T> v, int32_t *__restrict__ len)
 {
-    const int64_t row = (int64_t)blockIdx.x * FB + threadIdx.x;
+    // the block's rows own one contiguous range of the sorted COO part: two threads find it in the whole array,
+    // then every lane searches only inside it
+    __shared__ int64_t s_coo[2];
+    const int64_t row0 = (int64_t)blockIdx.x * FB;
+    if (v.nnz_coo > 0 && threadIdx.x < 2) {
+        const int64_t rend = row0 + FB < v.m ? row0 + FB : v.m;
+        s_coo[threadIdx.x] = coo_lower_bound(v.coo_row, 0, v.nnz_coo, threadIdx.x == 0 ? row0 : rend);
+    }
+    __syncthreads();
+    const int64_t row = row0 + threadIdx.x;
     if (row >= v.m) return;
     int c = 0;
     for (int64_t k = 0; k < v.nd; ++k) {
@@ -69,7 +77,10 @@ __global__ __launch_bounds__(FB) void k_len_any(View<T> v, int32_t *__restrict__
     }
     for (int64_t s = 0; s < v.k; ++s)
         if (v.ell_col[s * v.ld + row] >= 0) ++c;
-    if (v.nnz_coo > 0) c += (int)(coo_lower_bound(v.coo_row, v.nnz_coo, row + 1) - coo_lower_bound(v.coo_row, v.nnz_coo, row));
+    if (v.nnz_coo > 0) {
+        const int64_t q = coo_lower_bound(v.coo_row, s_coo[0], s_coo[1], row);
+        c += (int)(coo_lower_bound(v.coo_row, q, s_coo[1], row + 1) - q);
+    }
     if (v.csr_row_ptr) c += v.csr_row_ptr[row + 1] - v.csr_row_ptr[row];
     len[row] = c;
 }
@@ -170,8 +181,11 @@ __global__ __launch_bounds__(FB) void k_hist_parts(View<T> v, int64_t rows_per_b
     const int64_t p_begin = (int64_t)blockIdx.x * coo_per_block;
     int64_t p_end = p_begin + coo_per_block;
     p_end = p_end < v.nnz_coo ? p_end : v.nnz_coo;
-    for (int64_t p = p_begin + threadIdx.x; p < p_end; p += FB)
-        count_key((int)((int64_t)v.coo_col[p] - v.coo_row[p] + (v.m - 1)), 1u, ht_key, ht_cnt, &ht_full, hist);
+    for (int64_t base = p_begin; base < p_end; base += FB) {   // uniform trip count: merged() is a wave operation
+        const int64_t p = base + threadIdx.x;
+        const bool act = p < p_end;
+        merged(act, act ? (int)((int64_t)v.coo_col[p] - v.coo_row[p] + (v.m - 1)) : 0);
+    }
     __syncthreads();
     for (int i = threadIdx.x; i < HT_SIZE; i += FB) {
         const uint32_t c = ht_cnt[i];
@@ -180,42 +194,73 @@ __global__ __launch_bounds__(FB) void k_hist_parts(View<T> v, int64_t rows_per_b
 }
 
 // ------------------------------------------------------------------ any -> CSR
-// One row per lane; the row's entries leave in ascending column order.
+// One row per lane; the row's entries leave in ascending column order.  A block's 256 rows own one contiguous range
+// of the output, which is staged through LDS in chunks of FILL_CH entries so that the global writes are coalesced
+// (a lane writing its row directly would scatter 4- and 8-byte stores one row length apart).
+constexpr int FILL_CH = 2048;
+
 template <typename T>
 __global__ __launch_bounds__(FB) void k_fill_csr_any(View<T> v, const int32_t *__restrict__ out_ptr, int32_t *__restrict__ ocol,
                                                       T *__restrict__ oval)
 {
-    const int64_t row = (int64_t)blockIdx.x * FB + threadIdx.x;
-    if (row >= v.m) return;
-    int64_t pos = out_ptr[row];
-    // DIA part and CSR part (HDC holds both): two ascending column sequences, merged
-    int64_t kd = 0;
-    int p = v.csr_row_ptr ? v.csr_row_ptr[row] : 0;
-    const int pe = v.csr_row_ptr ? v.csr_row_ptr[row + 1] : 0;
-    while (true) {
+    __shared__ int32_t s_col[FILL_CH];
+    __shared__ T s_val[FILL_CH];
+    __shared__ int64_t s_coo[2];
+    const int64_t row0 = (int64_t)blockIdx.x * FB;
+    const int64_t row = row0 + threadIdx.x;
+    const bool rv = row < v.m;
+    const int64_t rend = row0 + FB < v.m ? row0 + FB : v.m;
+    if (v.nnz_coo > 0 && threadIdx.x < 2) s_coo[threadIdx.x] = coo_lower_bound(v.coo_row, 0, v.nnz_coo, threadIdx.x == 0 ? row0 : rend);
+    __syncthreads();
+    const int64_t out_lo = out_ptr[row0], out_hi = out_ptr[rend];
+    int64_t pos = rv ? (int64_t)out_ptr[row] : out_hi;
+    const int64_t pos_end = rv ? (int64_t)out_ptr[row + 1] : out_hi;
+    // cursors into the four possible sources of this row
+    int64_t kd = 0, sl = 0, q = 0, qe = 0;
+    int p = 0, pe = 0;
+    if (rv && v.csr_row_ptr) { p = v.csr_row_ptr[row]; pe = v.csr_row_ptr[row + 1]; }
+    if (rv && v.nnz_coo > 0) {
+        q = coo_lower_bound(v.coo_row, s_coo[0], s_coo[1], row);
+        qe = coo_lower_bound(v.coo_row, q, s_coo[1], row + 1);
+    }
+    // Next entry of the row: the DIA part and the CSR part (HDC holds both) are two ascending column sequences and
+    // are merged; then the ELL part; then the COO part (HYB: the COO entries of a row come after its ELL entries).
+    auto next = [&](int32_t &col, T &val) -> bool {
         int64_t jd = -1;
         T ad = (T)0;
-        while (kd < v.nd) {   // next entry of the DIA part
+        while (kd < v.nd) {
             const int64_t j = row + v.dia_off[kd];
             const T a = (j >= 0 && j < v.n) ? v.dia_val[kd * v.ld + row] : (T)0;
             if (a != (T)0) { jd = j; ad = a; break; }
             ++kd;
         }
         const bool has_d = jd >= 0, has_c = p < pe;
-        if (!has_d && !has_c) break;
-        if (has_d && (!has_c || jd < (int64_t)v.csr_col[p])) { ocol[pos] = (int32_t)jd; oval[pos] = ad; ++kd; }
-        else { ocol[pos] = v.csr_col[p]; oval[pos] = v.csr_val[p]; ++p; }
-        ++pos;
-    }
-    // ELL part, then the COO part (HYB: the COO entries of a row come after its ELL entries)
-    for (int64_t s = 0; s < v.k; ++s) {
-        const int c = v.ell_col[s * v.ld + row];
-        if (c >= 0) { ocol[pos] = c; oval[pos] = v.ell_val[s * v.ld + row]; ++pos; }
-    }
-    if (v.nnz_coo > 0) {
-        for (int64_t q = coo_lower_bound(v.coo_row, v.nnz_coo, row); q < v.nnz_coo && v.coo_row[q] == row; ++q) {
-            ocol[pos] = v.coo_col[q]; oval[pos] = v.coo_val[q]; ++pos;
+        if (has_d && (!has_c || jd < (int64_t)v.csr_col[p])) { col = (int32_t)jd; val = ad; ++kd; return true; }
+        if (has_c) { col = v.csr_col[p]; val = v.csr_val[p]; ++p; return true; }
+        if (sl < v.k) {
+            const int c = v.ell_col[sl * v.ld + row];
+            if (c >= 0) { col = c; val = v.ell_val[sl * v.ld + row]; ++sl; return true; }
+            sl = v.k;   // padding only follows the last entry of a row
         }
+        if (q < qe) { col = v.coo_col[q]; val = v.coo_val[q]; ++q; return true; }
+        return false;
+    };
+    for (int64_t c0 = out_lo; c0 < out_hi; c0 += FILL_CH) {   // uniform trip count across the block
+        const int64_t c1 = c0 + FILL_CH < out_hi ? c0 + FILL_CH : out_hi;
+        while (pos < pos_end && pos < c1) {
+            int32_t col = 0;
+            T val = (T)0;
+            if (!next(col, val)) { pos = pos_end; break; }   // cannot happen: the lengths were counted from the same arrays
+            s_col[pos - c0] = col;
+            s_val[pos - c0] = val;
+            ++pos;
+        }
+        __syncthreads();
+        for (int64_t i = c0 + threadIdx.x; i < c1; i += FB) {
+            ocol[i] = s_col[i - c0];
+            oval[i] = s_val[i - c0];
+        }
+        __syncthreads();
     }
 }
 
@@ -250,8 +295,18 @@ static mo_status rebuild_csr(const mo_matrix &a, TempCsr &out, hipStream_t s)
     out.col = (int32_t *)dev_alloc((size_t)(total > 0 ? total : 1) * 4, s);
     out.val = dev_alloc((size_t)(total > 0 ? total : 1) * sizeof(T), s);
     if (!out.col || !out.val) return MO_E_ALLOC;
-    hipLaunchKernelGGL(k_fill_csr_any<T>, dim3(rb), dim3(FB), 0, s, v, out.row_ptr, out.col, (T *)out.val);
-    MO_LAUNCH_CHECK();
+    if (a.fmt == MO_COO || a.fmt == MO_CSR) {
+        // COO is sorted by (row, col): its column and value arrays already are the CSR ones
+        const int32_t *src_col = a.fmt == MO_COO ? a.coo_col : a.csr_col;
+        const void *src_val = a.fmt == MO_COO ? a.coo_val : a.csr_val;
+        if (total > 0) {
+            MO_HIP(hipMemcpyAsync(out.col, src_col, (size_t)total * 4, hipMemcpyDeviceToDevice, s));
+            MO_HIP(hipMemcpyAsync(out.val, src_val, (size_t)total * sizeof(T), hipMemcpyDeviceToDevice, s));
+        }
+    } else {
+        hipLaunchKernelGGL(k_fill_csr_any<T>, dim3(rb), dim3(FB), 0, s, v, out.row_ptr, out.col, (T *)out.val);
+        MO_LAUNCH_CHECK();
+    }
     MO_HIP(hipStreamSynchronize(s));   // scratch is released on return
     return MO_OK;
 }
@@ -342,6 +397,10 @@ mo_status mo_matrix_features(const mo_matrix *a, const mo_params *params, double
                              void *stream)
 {
     if (!a || !out) return MO_E_NULL;
+    if (a->fmt == MO_CSR) {   // the CSR kernels stage columns through LDS and are the faster walk of these arrays
+        const mo_csr view{a->m, a->n, a->nnz_csr, a->csr_row_ptr, a->csr_col, a->csr_val, a->dtype};
+        return mo_features(&view, params, out, ints_opt, stream);
+    }
     mo_params p;
     MO_TRY(check_params(params, &p));
     Counters c;
