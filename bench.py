@@ -35,7 +35,7 @@ MEASURED_TRAFFIC = {
     (3, "f64", "CSR"): 1334.0e6, (3, "f64", "HYB"): 642.2e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
 }
 REPS = 1000
-MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_tree.bin")
+MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_forest.bin")
 
 
 def algorithmic_bytes(fmt, v, sv):
@@ -151,7 +151,7 @@ def main() -> int:
         for _ in range(1000):
             predicted = mo.mo_select(model, feats)
         t_pred_us = (time.perf_counter() - t0) * 1e3
-        tuner = "decision_tree"
+        tuner = "random_forest" if model.info()[0] > 1 else "decision_tree"
         chosen = predicted if predicted in handles else run_first
     else:
         predicted, t_pred_us, tuner, chosen = None, None, "run_first", run_first
@@ -231,7 +231,7 @@ def main() -> int:
         "per_format": per_format,
         "selected_format": mo.FORMAT_NAMES[chosen],
         "run_first_format": mo.FORMAT_NAMES[run_first],
-        "tree_predicted_format": mo.FORMAT_NAMES[predicted] if predicted is not None else None,
+        "model_predicted_format": mo.FORMAT_NAMES[predicted] if predicted is not None else None,
         "speedup_vs_csr_spmv_only": round(csr_us / best_us, 3),
         "speedup_vs_csr_eq2": round(csr_us * 1e-3 * REPS / ms_per_step, 3),
         "t_fe_ms": round(t_fe, 3), "t_fe_first_call_ms": round(t_fe_first, 3),

@@ -1,5 +1,5 @@
-"""Sweep bookkeeping on the CPU: the committed MI355X records load, the analysis identities hold, the committed
-model file is what a refit of those records gives."""
+"""Sweep bookkeeping on the CPU: the committed MI355X records load, the analysis identities hold, and the committed
+report and model file are what the committed records give (refits of the reported settings, not a new search)."""
 import json
 import math
 import os
@@ -11,31 +11,80 @@ from paper_2303_05098_amd import fit, mo, sweep
 MODELS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2303_05098_amd", "models")
 
 
-def test_committed_records_and_identities():
-    recs = sweep.load([os.path.join(MODELS, "mi355x_sweep.jsonl")])
-    assert len(recs) == 256 and [r["k"] for r in recs] == list(range(256))
+def records():
+    return sweep.load([os.path.join(MODELS, "mi355x_sweep.jsonl")])
+
+
+def arrays(recs):
+    X = np.array([r["features"] for r in recs], dtype=np.float64)
+    y = np.array([r["best"] for r in recs], dtype=np.int64)
+    return X, y
+
+
+def test_committed_records():
+    recs = records()
+    assert len(recs) == 2048 and [r["k"] for r in recs] == list(range(2048))
     for r in recs:
         ms = [math.nan if t is None else t for t in r["ms_per_rep"]]
         assert r["best"] == mo.mo_pick(ms)                      # label = argmin of the timings (Section VII-A)
         assert not math.isnan(ms[0]) and not math.isnan(ms[1]) and not math.isnan(ms[4]) and not math.isnan(ms[5])
-        assert len(r["features"]) == 10 and r["features"][2] == r["nnz"]
-    rep, X, y = sweep.analyse(recs, 6, 1)
-    assert sum(rep["class_histogram"].values()) == 256
-    assert rep["geomean_speedup_best_vs_csr"] >= 1.0            # the best format is never slower than CSR
-    assert rep["geomean_speedup_predicted_vs_csr"] <= rep["geomean_speedup_best_vs_csr"] + 1e-12
-    assert 0.0 <= rep["cv_balanced_accuracy"] <= 1.0 and 0.0 <= rep["cv_accuracy"] <= 1.0
-    saved = json.load(open(os.path.join(MODELS, "mi355x_sweep_report.json")))
-    assert abs(saved["cv_accuracy"] - rep["cv_accuracy"]) < 1e-12
+        assert len(r["features"]) == 10 and r["features"][2] == r["nnz"] and r["reps"] == 1000
 
 
-def test_committed_model_matches_refit(tmp_path):
-    recs = sweep.load([os.path.join(MODELS, "mi355x_sweep.jsonl")])
-    X = np.array([r["features"] for r in recs])
-    y = np.array([r["best"] for r in recs])
-    tree = fit.fit_tree(X, y, 6, 1)
+def test_committed_report_is_what_the_records_give():
+    recs = records()
+    X, y = arrays(recs)
+    rep = json.load(open(os.path.join(MODELS, "mi355x_sweep_report.json")))
+    test = fit.train_test_split(y)
+    assert (rep["n"], rep["n_train"], rep["n_test"]) == (2048, int((~test).sum()), int(test.sum()))
+    assert abs(rep["n_test"] / rep["n"] - 0.2) < 0.005
+    assert sum(rep["class_histogram"].values()) == 2048
+    for kind, base in (("tree", fit.BASELINE_TREE), ("forest", fit.BASELINE_FOREST)):
+        assert rep[kind]["baseline"]["test"]["opts"] == base
+        for which in ("baseline", "tuned"):
+            want = rep[kind][which]["test"]
+            got = fit.evaluate(X[~test], y[~test], X[test], y[test], **want["opts"])
+            assert (got["accuracy"], got["balanced_accuracy"], got["n_trees"], got["n_nodes"]) == \
+                (want["accuracy"], want["balanced_accuracy"], want["n_trees"], want["n_nodes"])
+        # the tuned setting is a point of the reported grid and won the search by the reported score
+        tuned = rep[kind]["tuned"]
+        assert all(tuned["test"]["opts"][k] in rep[kind]["grid"][k] for k in rep[kind]["grid"])
+        assert all(tuned["cv_balanced_accuracy"] >= r["cv_balanced_accuracy"] for r in rep[kind]["runners_up"])
+        cv = fit.cross_validate(X[~test], y[~test], 5, **tuned["test"]["opts"])
+        assert (cv["accuracy"], cv["balanced_accuracy"]) == (tuned["cv_accuracy"], tuned["cv_balanced_accuracy"])
+    # speedups on the test set: the best format is never slower than CSR, a prediction never beats the best
+    for key in ("test_set_tuned_forest", "test_set_tuned_tree", "all_records_oracle_choice"):
+        s = rep[key]
+        assert s["geomean_speedup_best_vs_csr"] >= 1.0
+        assert s["geomean_speedup_predicted_vs_csr"] <= s["geomean_speedup_best_vs_csr"] + 1e-12
+        assert s["geomean_speedup_eq2_predicted"] <= s["geomean_speedup_predicted_vs_csr"]      # tuner time only adds
+    o = rep["all_records_oracle_choice"]
+    assert o["geomean_speedup_predicted_vs_csr"] == o["geomean_speedup_best_vs_csr"]
+
+
+def test_speedup_bookkeeping_on_a_hand_case():
+    ms = np.array([[4.0, 2.0, 1.0, np.nan, 3.0, 2.0], [1.0, 2.0, np.nan, np.nan, 4.0, 8.0]])
+    conv = np.full((2, 6), 10.0)
+    s = sweep._speedups(ms, np.array([1.0, 1.0]), conv, np.array([2, 0]), np.array([2, 3]), 0.5, 1000)
+    # row 0 predicted DIA (2x faster than CSR); row 1 predicted ELL, infeasible -> falls back to CSR (1x)
+    assert abs(s["geomean_speedup_predicted_vs_csr"] - math.sqrt(2.0 * 1.0)) < 1e-12
+    assert abs(s["geomean_speedup_best_vs_csr"] - 2.0) < 1e-12
+    assert abs(s["geomean_speedup_eq2_predicted"] - math.sqrt((2000 / 1001.5) * (2000 / 2001.5))) < 1e-12
+    assert abs(s["tuner_cost_in_csr_spmv"]["mean"] - 0.75) < 1e-12                 # (1 + 0.5) / 2 for both rows
+    # break-even only where the prediction is faster than CSR: (1 + 0.5 + 10) / (2 - 1) -> 12 SpMVs
+    assert s["breakeven_spmvs_incl_conversion"] == dict(n_matrices=1, q1=12.0, q2=12.0, q3=12.0)
+
+
+def test_committed_model_is_the_tuned_forest_fitted_on_the_training_set(tmp_path):
+    recs = records()
+    X, y = arrays(recs)
+    rep = json.load(open(os.path.join(MODELS, "mi355x_sweep_report.json")))
+    test = fit.train_test_split(y)
+    model = mo.mo_model_fit(X[~test], y[~test], **rep["forest"]["tuned"]["test"]["opts"])
     p = str(tmp_path / "m.bin")
-    mo.write_model(p, [tree])
-    assert open(p, "rb").read() == open(os.path.join(MODELS, "mi355x_tree.bin"), "rb").read()
-    mdl = mo.mo_model_load(os.path.join(MODELS, "mi355x_tree.bin"))
-    pred = fit.predict_tree(tree, X)
-    assert [mo.mo_select(mdl, x) for x in X] == list(pred)
+    mo.mo_model_save(model, p)
+    committed = os.path.join(MODELS, "mi355x_forest.bin")
+    assert open(p, "rb").read() == open(committed, "rb").read()
+    loaded = mo.mo_model_load(committed)
+    assert np.array_equal(mo.mo_predict(loaded, X), mo.mo_predict(model, X))
+    assert fit.accuracy(y[test], mo.mo_predict(loaded, X[test])) == rep["forest"]["tuned"]["test"]["accuracy"]
