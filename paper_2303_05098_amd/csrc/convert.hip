@@ -57,10 +57,8 @@ __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo, 
     const int64_t we = wave_max(rv ? hi : (int64_t)0);
     for (int64_t c0 = wb; c0 < we; c0 += WCAP) {
         const int64_t c1 = c0 + WCAP < we ? c0 + WCAP : we;
-        for (int i = lane; i < (int)(c1 - c0); i += WAVE) {
-            s_col[i] = ld_stream(col_idx + c0 + i);
-            s_val[i] = ld_stream(val + c0 + i);
-        }
+        stage_to_lds(col_idx + c0, s_col, (int)(c1 - c0), lane);
+        stage_to_lds(val + c0, s_val, (int)(c1 - c0), lane);
         const int64_t a = lo > c0 ? lo : c0, b = hi < c1 ? hi : c1;
         const int cnt = (is_short && b > a) ? (int)(b - a) : 0;
         const int wmax = wave_max(cnt);

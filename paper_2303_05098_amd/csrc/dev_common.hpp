@@ -57,7 +57,7 @@ __device__ __forceinline__ T wave_sum(T v)
     return v;
 }
 
-__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
 // Streaming accesses for data that is touched once per SpMV (matrix values, indices, y): marked non-temporal so
 // that they do not displace x from the caches.  Measured on MI355X: a plain read stream sustains about 6.4 TB/s,
@@ -66,6 +66,28 @@ template <typename T>
 __device__ __forceinline__ T ld_stream(const T *p) { return __builtin_nontemporal_load(p); }
 template <typename T>
 __device__ __forceinline__ void st_stream(T *p, T v) { __builtin_nontemporal_store(v, p); }
+
+// Copy `count` >= 1 consecutive elements from global memory into a wave's LDS region.  The loads of a batch are all
+// issued before the first one is consumed (registers in between), so a wave keeps STAGE_BATCH cache lines per lane
+// group in flight instead of paying one memory latency per 64 elements.
+constexpr int STAGE_BATCH = 8;
+template <typename T>
+__device__ __forceinline__ void stage_to_lds(const T *__restrict__ g, T *s, int count, int lane)
+{
+    for (int i0 = 0; i0 < count; i0 += WAVE * STAGE_BATCH) {
+        T r[STAGE_BATCH];
+#pragma unroll
+        for (int u = 0; u < STAGE_BATCH; ++u) {   // unconditional loads (index clamped into the run) so that none waits for another
+            const int i = i0 + u * WAVE + lane;
+            r[u] = ld_stream(g + (i < count ? i : count - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < STAGE_BATCH; ++u) {
+            const int i = i0 + u * WAVE + lane;
+            if (i < count) s[i] = r[u];
+        }
+    }
+}
 
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef int int2v __attribute__((ext_vector_type(2)));
