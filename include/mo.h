@@ -52,7 +52,8 @@ typedef enum {
     MO_E_ALLOC = 7,       /* the device allocator returned NULL */
     MO_E_DEVICE = 8,      /* a HIP call failed; see mo_last_hip_error() */
     MO_E_MODEL = 9,       /* model file unreadable, malformed or inconsistent */
-    MO_E_PARAM = 10       /* a parameter struct holds a non-positive denominator or negative value */
+    MO_E_PARAM = 10,      /* a parameter struct holds a non-positive denominator or negative value */
+    MO_E_IO = 11          /* a matrix file is unreadable, malformed or of an unsupported kind */
 } mo_status;
 
 /* Borrowed view of a CSR matrix in device memory (Section II-B: values, column
@@ -200,6 +201,17 @@ mo_status mo_switch(const mo_matrix *a, mo_format fmt, const mo_params *params, 
  * and frees 4*(2m + n) bytes of scratch. */
 mo_status mo_matrix_features(const mo_matrix *a, const mo_params *params, double out[MO_NUM_FEATURES],
                              mo_feature_ints *ints_opt, void *stream);
+
+/* Host: read a Matrix Market file (the format of the SuiteSparse collection the paper profiles, Section VII "Setup")
+ * into CSR.  Coordinate format; field real, integer or pattern (entries mean 1); symmetry general, symmetric or
+ * skew-symmetric (the stored triangle is mirrored).  Indices in the file are 1-based.  Entries naming the same
+ * position are summed (the file's entries in file order, then the mirrored ones); explicit zeros stay entries; columns
+ * come out ascending inside each row.  The three arrays are host memory owned by the caller: release each with
+ * mo_host_free.  MO_E_IO for an unreadable, malformed or unsupported (array format, complex, hermitian) file,
+ * MO_E_SHAPE when sizes exceed the limits stated at the top of this header.  An empty matrix (L = 0) is valid. */
+mo_status mo_mtx_read(const char *path, int64_t *m, int64_t *n, int64_t *nnz, int32_t **row_ptr, int32_t **col_idx,
+                      double **val);
+void mo_host_free(void *p);
 
 mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out);
 void mo_matrix_free(mo_matrix *a);

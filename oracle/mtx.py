@@ -24,7 +24,7 @@ class MtxError(ValueError):
 
 def read_triplets(path: str):
     """-> (m, n, rows, cols, vals): 0-based triplets sorted by (row, col), duplicates summed."""
-    with open(path, "r") as fh:
+    with open(path, "r", newline="\n") as fh:      # lines end with LF; a CR before it is white space
         lines = fh.read().split("\n")
     if not lines or not lines[0].startswith("%%MatrixMarket"):
         raise MtxError("no banner")

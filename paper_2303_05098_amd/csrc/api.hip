@@ -67,6 +67,7 @@ const char *mo_strerror(mo_status s)
     case MO_E_DEVICE: return "HIP call failed";
     case MO_E_MODEL: return "model file unreadable or malformed";
     case MO_E_PARAM: return "invalid parameter";
+    case MO_E_IO: return "matrix file unreadable, malformed or unsupported";
     }
     return "unknown status";
 }

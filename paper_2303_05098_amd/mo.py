@@ -28,10 +28,10 @@ MO_COO, MO_CSR, MO_DIA, MO_ELL, MO_HYB, MO_HDC = range(6)
 FORMAT_NAMES = ("COO", "CSR", "DIA", "ELL", "HYB", "HDC")
 MO_F32, MO_F64 = 0, 1
 (MO_OK, MO_E_NULL, MO_E_SHAPE, MO_E_CSR_INVALID, MO_E_FORMAT, MO_E_DTYPE, MO_E_FILL, MO_E_ALLOC, MO_E_DEVICE,
- MO_E_MODEL, MO_E_PARAM) = range(11)
+ MO_E_MODEL, MO_E_PARAM, MO_E_IO) = range(12)
 
 EXPORTS = ("mo_default_params", "mo_features", "mo_convert", "mo_spmv", "mo_tune", "mo_pick", "mo_model_load",
-           "mo_model_free", "mo_model_info", "mo_select", "mo_default_fit_opts", "mo_model_fit", "mo_model_save", "mo_predict", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
+           "mo_model_free", "mo_model_info", "mo_select", "mo_default_fit_opts", "mo_model_fit", "mo_model_save", "mo_predict", "mo_mtx_read", "mo_host_free", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
            "mo_strerror", "mo_last_hip_error")
 
 
@@ -102,6 +102,10 @@ lib.mo_default_fit_opts.argtypes = [C.POINTER(mo_fit_opts)]
 lib.mo_model_fit.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(mo_fit_opts), C.POINTER(C.c_void_p)]
 lib.mo_model_save.argtypes = [C.c_void_p, C.c_char_p]
 lib.mo_predict.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+lib.mo_mtx_read.argtypes = [C.c_char_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                            C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+lib.mo_host_free.restype = None
+lib.mo_host_free.argtypes = [C.c_void_p]
 lib.mo_matrix_export.argtypes = [C.c_void_p, C.POINTER(mo_matrix_view)]
 lib.mo_matrix_free.restype = None
 lib.mo_matrix_free.argtypes = [C.c_void_p]
@@ -317,6 +321,20 @@ def mo_select(model: Model, features) -> int:
     out = C.c_int(-1)
     _check(lib.mo_select(model.handle, arr, C.byref(out)), "mo_select")
     return out.value
+
+
+def mo_mtx_read(path: str):
+    """Matrix Market file -> (m, n, row_ptr, col_idx, val) as numpy arrays on the host."""
+    m, n, nnz = C.c_int64(), C.c_int64(), C.c_int64()
+    rp, ci, va = C.c_void_p(), C.c_void_p(), C.c_void_p()
+    _check(lib.mo_mtx_read(os.fsencode(path), C.byref(m), C.byref(n), C.byref(nnz), C.byref(rp), C.byref(ci), C.byref(va)), "mo_mtx_read")
+    try:
+        row_ptr = np.ctypeslib.as_array(C.cast(rp, C.POINTER(C.c_int32)), shape=(m.value + 1,)).copy()
+        col_idx = np.ctypeslib.as_array(C.cast(ci, C.POINTER(C.c_int32)), shape=(max(nnz.value, 1),))[:nnz.value].copy()
+        val = np.ctypeslib.as_array(C.cast(va, C.POINTER(C.c_double)), shape=(max(nnz.value, 1),))[:nnz.value].copy()
+    finally:
+        lib.mo_host_free(rp); lib.mo_host_free(ci); lib.mo_host_free(va)
+    return m.value, n.value, row_ptr, col_idx, val
 
 
 MO_GINI, MO_ENTROPY = 0, 1
