@@ -75,6 +75,35 @@ int orc_spmv(int64_t m, int64_t n, int64_t nnz, const int32_t *ti, const int32_t
     return ORC_OK;
 }
 
+/* Y = A X for k right-hand sides at once: the operation of Section I applied to every column of X (the paper's tuning
+ * interface, Section VI-B, is meant for further operations of this kind).  X is n x k and Y is m x k, both row-major.
+ * acc_iv = sum_j a_ij x_jv and mag_iv = sum_j |a_ij||x_jv| over the triplets of row i, in extended precision. */
+int orc_spmm(int64_t m, int64_t n, int64_t nnz, const int32_t *ti, const int32_t *tj, const double *ta, int64_t k,
+             const double *x, double *y, double *mag)
+{
+    if (m < 0 || n < 0 || nnz < 0 || k < 1) return ORC_E_ARG;
+    size_t cells = (size_t)(m > 0 ? m : 1) * (size_t)k;
+    long double *sum = (long double *)calloc(cells, sizeof(long double));
+    long double *abs_sum = (long double *)calloc(cells, sizeof(long double));
+    if (!sum || !abs_sum) { free(sum); free(abs_sum); return ORC_E_MEM; }
+    for (int64_t e = 0; e < nnz; ++e) {
+        int64_t row = ti[e], col = tj[e];
+        if (row < 0 || row >= m || col < 0 || col >= n) { free(sum); free(abs_sum); return ORC_E_ARG; }
+        long double a = (long double)ta[e];
+        for (int64_t v = 0; v < k; ++v) {
+            long double xv = (long double)x[col * k + v];
+            sum[row * k + v] += a * xv;
+            abs_sum[row * k + v] += fabsl(a) * fabsl(xv);
+        }
+    }
+    for (int64_t c = 0; c < m * k; ++c) {
+        y[c] = (double)sum[c];
+        if (mag) mag[c] = (double)abs_sum[c];
+    }
+    free(sum); free(abs_sum);
+    return ORC_OK;
+}
+
 /* The same loop split over row ranges, for the benchmark's host baseline.
  * Needs row-sorted triplets so that ranges never share a row. */
 typedef struct {

@@ -69,6 +69,21 @@ def spmv(m, n, ti, tj, ta, x):
     return y[:m], mag[:m]
 
 
+def spmm(m, n, ti, tj, ta, x):
+    """Y = A X, X of shape (n, k) -> (Y, |A||X|), both (m, k)."""
+    ti, tj, ta = _i32(ti), _i32(tj), _f64(ta)
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    assert x.ndim == 2 and x.shape[0] == n
+    k = x.shape[1]
+    y = np.zeros((max(m, 1), k), dtype=np.float64)
+    mag = np.zeros((max(m, 1), k), dtype=np.float64)
+    rc = lib().orc_spmm(_i64(m), _i64(n), _i64(ti.shape[0]), _p(ti, I32P), _p(tj, I32P), _p(ta, F64P), _i64(k),
+                        _p(x, F64P), _p(y, F64P), _p(mag, F64P))
+    if rc != 0:
+        raise ValueError(f"orc_spmm failed: {rc}")
+    return y[:m], mag[:m]
+
+
 def spmv_rowsorted_mt(m, ti, tj, ta, x, nthreads):
     ti, tj, ta, x = _i32(ti), _i32(tj), _f64(ta), _f64(x)
     y = np.zeros(max(m, 1), dtype=np.float64)

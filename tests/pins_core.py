@@ -24,6 +24,11 @@ def check_all():
         y, mag = ref.spmv(m, n, ti, tj, ta, x)
         assert np.allclose(y, a @ x, rtol=0, atol=1e-14 * n)
         assert np.allclose(mag, np.abs(a) @ np.abs(x), rtol=1e-14, atol=0)
+        # --- the multi-vector product against the dense product (k = 3, rectangular X catches a transposed layout)
+        X = synth.uniform_pm1(seed, 41, np.arange(n * 3)).reshape(n, 3)
+        Y, Mg = ref.spmm(m, n, ti, tj, ta, X)
+        assert np.allclose(Y, a @ X, rtol=0, atol=1e-14 * n)
+        assert np.allclose(Mg, np.abs(a) @ np.abs(X), rtol=1e-14, atol=0)
         # --- features, three thresholds
         for td in ((1, 2), (1, 4), (1, 1)):
             f, _ = ref.features(m, n, ti, tj, td)

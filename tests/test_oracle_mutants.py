@@ -15,6 +15,10 @@ MUTANTS = [
     ("spmv_transposed", "int64_t i = ti[t], j = tj[t];\n        if (i < 0 || i >= m || j < 0 || j >= n)", "int64_t i = tj[t], j = ti[t];\n        if (i < 0 || i >= m || j < 0 || j >= n)"),
     ("spmv_mag_signed", "mg[i] += fabsl(a) * fabsl(xv);", "mg[i] += a * xv;"),
     ("spmv_drops_first_term", "for (int64_t t = 0; t < nnz; ++t) {\n        int64_t i = ti[t], j = tj[t];", "for (int64_t t = 1; t < nnz; ++t) {\n        int64_t i = ti[t], j = tj[t];"),
+    ("spmm_transposed_x", "long double xv = (long double)x[col * k + v];", "long double xv = (long double)x[v * n + col];"),
+    ("spmm_transposed_a", "int64_t row = ti[e], col = tj[e];", "int64_t row = tj[e], col = ti[e];"),
+    ("spmm_mag_signed", "abs_sum[row * k + v] += fabsl(a) * fabsl(xv);", "abs_sum[row * k + v] += a * xv;"),
+    ("spmm_y_column_major", "sum[row * k + v] += a * xv;", "sum[v * m + row] += a * xv;"),
     ("avg_by_columns", "out[3] = (double)nnz / (double)m;", "out[3] = (double)nnz / (double)n;"),
     ("density_m_squared", "out[4] = (double)nnz / ((double)m * (double)n);", "out[4] = (double)nnz / ((double)m * (double)m);"),
     ("min_skips_empty_rows", "if (len[i] < mn) mn = len[i];", "if (len[i] < mn && len[i] > 0) mn = len[i];"),
