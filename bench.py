@@ -193,6 +193,29 @@ def main() -> int:
     tune_best, tune_ms, _ = mo.mo_tune(a, warmups=5, reps=50)
     t_tune = (time.perf_counter() - t0) * 1e3
 
+    # ---- the second operation: Y = A X with 8 right-hand sides, every format (not part of the timed step) ----------
+    SPMM_K = 8
+    xk = torch.as_tensor(np.ascontiguousarray(synth.uniform_pm1(synth.BASE_SEED + 40, 0, np.arange(n * SPMM_K)).reshape(n, SPMM_K),
+                                              dtype=np_dtype)).cuda()
+    yk = torch.empty((m, SPMM_K), dtype=xk.dtype, device="cuda")
+    spmm = {}
+    for fmt, hh in handles.items():
+        for _ in range(3):
+            mo.mo_spmm(hh, xk, yk)
+        tb = math.inf
+        for _ in range(3):
+            e0, e1 = ev(), ev()
+            e0.record(stream)
+            for _ in range(20):
+                mo.mo_spmm(hh, xk, yk)
+            e1.record(stream)
+            e1.synchronize()
+            tb = min(tb, e0.elapsed_time(e1) / 20.0)
+        bk = algorithmic_bytes(fmt, hh.view(), sv) + (SPMM_K - 1) * (n + m) * sv
+        spmm[mo.FORMAT_NAMES[fmt]] = {"us": round(tb * 1e3, 1), "gflops": round(2.0 * nnz * SPMM_K / tb / 1e6, 1),
+                                      "frac_hbm": round(bk / tb / 1e6 / HBM_PEAK_GBS, 4)}
+    del xk, yk
+
     # ---- CPU baseline: the oracle, as it stands, on this host -------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -237,6 +260,7 @@ def main() -> int:
         "t_fe_ms": round(t_fe, 3), "t_fe_first_call_ms": round(t_fe_first, 3),
         "t_pred_us": round(t_pred_us, 3) if t_pred_us is not None else None,
         "tuner_cost_in_csr_spmv": round((t_fe + (t_pred_us or 0.0) * 1e-3) / (csr_us * 1e-3), 1),
+        "spmm_8_rhs_per_format": spmm,
         "convert_ms": convert_ms,
         "mo_tune": {"best": mo.FORMAT_NAMES[tune_best], "wall_ms": round(t_tune, 1),
                     "ms_per_rep": [None if math.isnan(t) else round(float(t), 5) for t in tune_ms]},

@@ -142,6 +142,16 @@ mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream);
 mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
                   double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream);
 
+/* A second operation under the same interface (Section VI-B leaves the tuning interface open to further operations):
+ * Y = A X for k right-hand sides, 1 <= k <= MO_MAX_RHS.  X: device, n x k, row-major (the k values of one row of X are
+ * contiguous); Y: device, m x k, row-major, overwritten.  Same rules as mo_spmv: asynchronous on `stream`, no
+ * allocation, no synchronisation, X and Y must not overlap, bit-identical reruns.  mo_tune_spmm is mo_tune with this
+ * operation timed in place of SpMV. */
+#define MO_MAX_RHS 64
+mo_status mo_spmm(const mo_matrix *a, const void *x, void *y, int32_t k, void *stream);
+mo_status mo_tune_spmm(const mo_csr *a, int32_t k, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
+                       double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream);
+
 /* Pure host: index of the smallest non-NaN entry, ties to the lowest id; MO_E_PARAM if all are NaN. */
 mo_status mo_pick(const double ms[MO_NUM_FORMATS], mo_format *best);
 

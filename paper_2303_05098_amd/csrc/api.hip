@@ -163,8 +163,17 @@ mo_status mo_pick(const double ms[MO_NUM_FORMATS], mo_format *best)
     return MO_OK;
 }
 
-mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
-                  double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream)
+mo_status mo_spmm(const mo_matrix *a, const void *x, void *y, int32_t k, void *stream)
+{
+    if (!a || !x || !y) return MO_E_NULL;
+    if (k < 1 || k > MO_MAX_RHS) return MO_E_PARAM;
+    if (k == 1) return mo_spmv(a, x, y, stream);   // an n x 1 matrix is a vector
+    return spmm(*a, x, y, (int)k, (hipStream_t)stream);
+}
+
+// The run-first tuner for either operation: k = 0 times mo_spmv, k >= 1 times mo_spmm with k right-hand sides.
+static mo_status tune_impl(const mo_csr *a, int k, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
+                           double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream)
 {
     if (!best || !ms_per_rep) return MO_E_NULL;
     MO_TRY(check_csr_args(a));
@@ -182,11 +191,12 @@ mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *
     Analysis an;
     MO_TRY(analyse(*a, p, true, &an, scr, s));
     const size_t sv = dtype_size(a->dtype);
-    void *x = scr.get((size_t)a->n * sv);
-    void *y = scr.get((size_t)a->m * sv);
+    const int64_t width = k > 0 ? k : 1;
+    void *x = scr.get((size_t)(a->n * width) * sv);
+    void *y = scr.get((size_t)(a->m * width) * sv);
     if (!x || !y) return MO_E_ALLOC;
     // x = 0 is as good as any vector for timing: no kernel here branches on values
-    MO_TRY(fill_zero(x, a->n, a->dtype, s));
+    MO_TRY(fill_zero(x, a->n * width, a->dtype, s));
     hipEvent_t e0, e1;
     MO_HIP(hipEventCreate(&e0));
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return MO_E_DEVICE; }
@@ -199,9 +209,9 @@ mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *
         if (c != MO_OK) { rc = c; break; }
         const auto t1 = std::chrono::steady_clock::now();
         if (convert_ms) convert_ms[f] = std::chrono::duration<double, std::milli>(t1 - t0).count();
-        for (int i = 0; i < warm && rc == MO_OK; ++i) rc = mo_spmv(h, x, y, s);
+        for (int i = 0; i < warm && rc == MO_OK; ++i) rc = k > 1 ? spmm(*h, x, y, k, s) : mo_spmv(h, x, y, s);
         if (rc == MO_OK && hipEventRecord(e0, s) != hipSuccess) rc = MO_E_DEVICE;
-        for (int i = 0; i < reps && rc == MO_OK; ++i) rc = mo_spmv(h, x, y, s);
+        for (int i = 0; i < reps && rc == MO_OK; ++i) rc = k > 1 ? spmm(*h, x, y, k, s) : mo_spmv(h, x, y, s);
         if (rc == MO_OK && hipEventRecord(e1, s) != hipSuccess) rc = MO_E_DEVICE;
         if (rc == MO_OK && hipEventSynchronize(e1) != hipSuccess) rc = MO_E_DEVICE;
         float ms = 0.f;
@@ -214,6 +224,19 @@ mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *
     (void)hipEventDestroy(e1);
     if (rc != MO_OK) return rc;
     return mo_pick(ms_per_rep, best);
+}
+
+mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
+                  double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream)
+{
+    return tune_impl(a, 0, params, opts, best, ms_per_rep, convert_ms, stream);
+}
+
+mo_status mo_tune_spmm(const mo_csr *a, int32_t k, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
+                       double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream)
+{
+    if (k < 1 || k > MO_MAX_RHS) return MO_E_PARAM;
+    return tune_impl(a, (int)k, params, opts, best, ms_per_rep, convert_ms, stream);
 }
 
 mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out)

@@ -500,8 +500,11 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         h->coo_row = (int32_t *)b.own(e * 4);
         h->coo_col = (int32_t *)b.own(e * 4);
         h->coo_val = b.own(e * sizeof(T));
+        int32_t *rp_copy = (int32_t *)b.own((size_t)(a.m + 1) * 4);
         setup_coo_tiles(b, sizeof(T));
         if (b.failed) return MO_E_ALLOC;
+        MO_HIP(hipMemcpyAsync(rp_copy, a.row_ptr, (size_t)(a.m + 1) * 4, hipMemcpyDeviceToDevice, s));
+        h->coo_rp = rp_copy;
         if (a.nnz > 0) {
             hipLaunchKernelGGL(k_csr_to_coo<T>, dim3((unsigned)((a.nnz + COO_CT - 1) / COO_CT)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval,
                                a.m, a.nnz, h->coo_row, h->coo_col, (T *)h->coo_val);
@@ -551,7 +554,8 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
             h->coo_val = b.own(e * sizeof(T));
             setup_coo_tiles(b, sizeof(T));
             int32_t *cnt = (int32_t *)scr.get((size_t)a.m * 4);
-            coo_ptr = (int32_t *)scr.get((size_t)(a.m + 1) * 4);
+            coo_ptr = (int32_t *)b.own((size_t)(a.m + 1) * 4);   // kept: start of each row's run in the COO part
+            h->coo_rp = coo_ptr;
             void *tmp = scr.get(scan_tmp_bytes(a.m));
             if (b.failed || !cnt || !coo_ptr || !tmp) return MO_E_ALLOC;
             hipLaunchKernelGGL(k_surplus, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.m, K, cnt);

@@ -93,6 +93,8 @@ struct mo_matrix {
     int32_t *csr_carry_row = nullptr;
     void *csr_carry_val = nullptr;
     int32_t *csr_tile_rp = nullptr;   // (first row, its row_ptr) per tile, tiles + 1 pairs
+    const int32_t *coo_rp = nullptr;  // m + 1 positions: where each row's run starts in the sorted COO part (launch data
+                                      // of the multi-vector product; not part of the format)
     int64_t coo_tiles = 0;
     int32_t coo_strip = 4;            // entries per thread of the COO kernel (4 or 2)
     int32_t *coo_carry_row = nullptr; // one per COO tile
@@ -139,6 +141,9 @@ bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_e
 constexpr int64_t DIA_LDS_BYTES = 48 * 1024;  // LDS budget for staged x windows per block
 constexpr int64_t HDC_FUSED_MAX_ROW = 64;   // longest row for which HDC runs as one fused kernel
 mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s);
+
+// ---------------------------------------------------------------- multi-vector product (spmm.hip)
+mo_status spmm(const mo_matrix &a, const void *x, void *y, int k, hipStream_t s);
 int64_t csr_tile_count(int64_t nnz, int tile_size);
 // y[row] += carries of every chain of consecutive tiles with the same carry row (shared by the COO and CSR kernels)
 mo_status carry_fixup(const int32_t *carry_row, const void *carry_val, int64_t tiles, void *y, mo_dtype dt, hipStream_t s);

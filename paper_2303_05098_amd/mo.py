@@ -30,7 +30,7 @@ MO_F32, MO_F64 = 0, 1
 (MO_OK, MO_E_NULL, MO_E_SHAPE, MO_E_CSR_INVALID, MO_E_FORMAT, MO_E_DTYPE, MO_E_FILL, MO_E_ALLOC, MO_E_DEVICE,
  MO_E_MODEL, MO_E_PARAM, MO_E_IO) = range(12)
 
-EXPORTS = ("mo_default_params", "mo_features", "mo_convert", "mo_spmv", "mo_tune", "mo_pick", "mo_model_load",
+EXPORTS = ("mo_default_params", "mo_features", "mo_convert", "mo_spmv", "mo_spmm", "mo_tune", "mo_tune_spmm", "mo_pick", "mo_model_load",
            "mo_model_free", "mo_model_info", "mo_select", "mo_default_fit_opts", "mo_model_fit", "mo_model_save", "mo_predict", "mo_mtx_read", "mo_host_free", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
            "mo_strerror", "mo_last_hip_error")
 
@@ -89,6 +89,9 @@ lib.mo_convert.argtypes = [C.POINTER(mo_csr), C.c_int, C.POINTER(mo_params), C.P
 lib.mo_switch.argtypes = [C.c_void_p, C.c_int, C.POINTER(mo_params), C.POINTER(C.c_void_p), C.c_void_p]
 lib.mo_matrix_features.argtypes = [C.c_void_p, C.POINTER(mo_params), C.POINTER(C.c_double), C.POINTER(mo_feature_ints), C.c_void_p]
 lib.mo_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.mo_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+lib.mo_tune_spmm.argtypes = [C.POINTER(mo_csr), C.c_int32, C.POINTER(mo_params), C.POINTER(mo_tune_opts), C.POINTER(C.c_int),
+                             C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
 lib.mo_tune.argtypes = [C.POINTER(mo_csr), C.POINTER(mo_params), C.POINTER(mo_tune_opts), C.POINTER(C.c_int),
                         C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
 lib.mo_pick.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
@@ -279,6 +282,24 @@ def mo_tune(a: Csr, params=None, warmups=5, reps=50, stream=None):
     opts = mo_tune_opts(int(warmups), int(reps))
     st = a.struct()
     _check(lib.mo_tune(C.byref(st), _params(params), C.byref(opts), C.byref(best), ms, cv, _stream_ptr(stream)), "mo_tune")
+    return best.value, np.array(list(ms)), np.array(list(cv))
+
+
+def mo_spmm(a: Matrix, x: torch.Tensor, y: torch.Tensor, stream=None) -> None:
+    """Y = A X; x: (n, k) and y: (m, k) contiguous row-major tensors of the handle's dtype."""
+    if x.dim() != 2 or y.dim() != 2 or x.shape[1] != y.shape[1] or not x.is_contiguous() or not y.is_contiguous():
+        raise ValueError("x must be (n, k) and y (m, k), both contiguous")
+    _check(lib.mo_spmm(a.handle, x.data_ptr(), y.data_ptr(), int(x.shape[1]), _stream_ptr(stream)), "mo_spmm")
+
+
+def mo_tune_spmm(a: Csr, k: int, params=None, warmups=5, reps=50, stream=None):
+    """mo_tune with the k-vector product timed in place of SpMV."""
+    best = C.c_int(-1)
+    ms = (C.c_double * 6)()
+    cv = (C.c_double * 6)()
+    opts = mo_tune_opts(int(warmups), int(reps))
+    st = a.struct()
+    _check(lib.mo_tune_spmm(C.byref(st), int(k), _params(params), C.byref(opts), C.byref(best), ms, cv, _stream_ptr(stream)), "mo_tune_spmm")
     return best.value, np.array(list(ms)), np.array(list(cv))
 
 
