@@ -7,6 +7,38 @@
 namespace mo {
 
 constexpr int ELL_B = 256;
+constexpr int ELL_U = 8;   // slots fetched together
+
+// sum += A(row, slots s, s + step, ...) * x over the slots [s0, s1) of one row.  The loads of ELL_U slots are issued
+// together and unconditionally (a padded slot reads x[0] twice and is masked out of the sum), so that no load waits
+// for a branch on the one before it.  The order of the additions is the slot order.
+template <typename T>
+__device__ __forceinline__ T ell_row_sum(const int32_t *__restrict__ c, const T *__restrict__ v, int64_t ld, int64_t s0, int64_t s1,
+                                         int64_t step, const T *__restrict__ x)
+{
+    T sum = (T)0;
+    int64_t s = s0;
+    for (; s + (ELL_U - 1) * step < s1; s += ELL_U * step) {
+        int32_t j[ELL_U];
+        T a[ELL_U], xv[ELL_U];
+#pragma unroll
+        for (int u = 0; u < ELL_U; ++u) j[u] = ld_stream(c + (s + u * step) * ld);
+#pragma unroll
+        for (int u = 0; u < ELL_U; ++u) {   // a padded slot reads x[0] in place of its value: no slab traffic for padding
+            a[u] = ld_stream(j[u] >= 0 ? v + (s + u * step) * ld : x);
+            xv[u] = x[j[u] >= 0 ? j[u] : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < ELL_U; ++u) sum += j[u] >= 0 ? a[u] * xv[u] : (T)0;
+    }
+    for (; s < s1; s += step) {
+        const int32_t j = ld_stream(c + s * ld);
+        const T a = ld_stream(j >= 0 ? v + s * ld : x);
+        const T xv = x[j >= 0 ? j : 0];
+        sum += j >= 0 ? a * xv : (T)0;
+    }
+    return sum;
+}
 // The slot-split kernel pays off while one-row-per-lane blocks cannot fill the chip (measured: faster up to about
 // 260 000 rows at K = 27, slower beyond; no gain for K < 16).
 constexpr int64_t ELL_SPLIT_MAX_ROWS = 300000;
@@ -19,15 +51,7 @@ __global__ __launch_bounds__(ELL_B) void k_ell(const int32_t *__restrict__ col, 
     const int64_t lb = xcd_block(blockIdx.x, gridDim.x);
     const int64_t row = lb * ELL_B + threadIdx.x;
     if (row >= m) return;
-    T sum = (T)0;
-    const int32_t *c = col + row;
-    const T *v = val + row;
-#pragma unroll 4
-    for (int64_t s = 0; s < K; ++s) {
-        const int32_t j = ld_stream(c + s * ld);
-        if (j >= 0) sum += ld_stream(v + s * ld) * x[j];
-    }
-    st_stream(y + row, sum);
+    st_stream(y + row, ell_row_sum<T>(col + row, val + row, ld, 0, K, 1, x));
 }
 
 // Small matrices: one row per lane leaves most of the chip idle and makes every lane walk all K slots in sequence.
@@ -42,15 +66,7 @@ __global__ __launch_bounds__(ELL_B) void k_ell_split(const int32_t *__restrict__
     const int lane = lane_id(), w = threadIdx.x / WAVE;
     const int64_t row = (int64_t)blockIdx.x * WAVE + lane;
     T sum = (T)0;
-    if (row < m) {
-        const int32_t *c = col + row;
-        const T *v = val + row;
-#pragma unroll 4
-        for (int64_t s = w; s < K; s += NW) {
-            const int32_t j = ld_stream(c + s * ld);
-            if (j >= 0) sum += ld_stream(v + s * ld) * x[j];
-        }
-    }
+    if (row < m) sum = ell_row_sum<T>(col + row, val + row, ld, w, K, NW, x);
     part[w][lane] = sum;
     __syncthreads();
     if (w == 0 && row < m) {
