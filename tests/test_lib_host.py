@@ -30,8 +30,9 @@ def test_default_params():
 
 
 def test_strerror_covers_every_status():
-    seen = {mo.lib.mo_strerror(s).decode() for s in range(11)}
-    assert len(seen) == 11 and "unknown status" not in seen
+    seen = {mo.lib.mo_strerror(s).decode() for s in range(12)}
+    assert len(seen) == 12 and "unknown status" not in seen
+    assert mo.lib.mo_strerror(12).decode() == "unknown status"
 
 
 @pytest.mark.parametrize("ms", [
@@ -182,3 +183,19 @@ def test_argument_checks_need_no_gpu():
     assert mo.lib.mo_matrix_export(None, None) == mo.MO_E_NULL
     mo.lib.mo_matrix_free(None)
     mo.lib.mo_model_free(None)
+    # the calls added for switching, the second operation, training and files
+    assert mo.lib.mo_switch(None, 1, None, C.byref(h), None) == mo.MO_E_NULL
+    assert mo.lib.mo_switch(dummy, 1, None, None, None) == mo.MO_E_NULL
+    assert mo.lib.mo_matrix_features(None, None, out, None, None) == mo.MO_E_NULL
+    assert mo.lib.mo_spmm(None, dummy, dummy, 4, None) == mo.MO_E_NULL
+    best, ms6 = C.c_int(-1), (C.c_double * 6)()
+    for k in (0, -3, 65):
+        assert mo.lib.mo_tune_spmm(C.byref(ok), k, None, None, C.byref(best), ms6, None, None) == mo.MO_E_PARAM
+    assert mo.lib.mo_tune_spmm(C.byref(ok), 4, None, None, None, ms6, None, None) == mo.MO_E_NULL
+    assert mo.lib.mo_tune(C.byref(ok), None, None, None, ms6, None, None) == mo.MO_E_NULL
+    assert mo.lib.mo_model_fit(None, None, 5, None, C.byref(h)) == mo.MO_E_NULL
+    assert mo.lib.mo_model_save(None, b"/tmp/x") == mo.MO_E_NULL
+    assert mo.lib.mo_predict(None, None, 0, None) == mo.MO_E_NULL
+    i64 = C.c_int64()
+    assert mo.lib.mo_mtx_read(None, C.byref(i64), C.byref(i64), C.byref(i64), C.byref(h), C.byref(h), C.byref(h)) == mo.MO_E_NULL
+    mo.lib.mo_host_free(None)
