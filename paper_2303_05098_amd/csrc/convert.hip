@@ -63,7 +63,7 @@ __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo, 
         const int cnt = (is_short && b > a) ? (int)(b - a) : 0;
         const int wmax = wave_max(cnt);
         for (int k = 0; k < wmax; ++k)
-            if (k < cnt) f(row, a + k, a + k - lo, s_col[a + k - c0], s_val[a + k - c0]);
+            if (k < cnt) f(row, a + k, a + k - lo, s_col[a + k - c0], s_val[a + k - c0], true);
     }
     uint64_t longmask = ballot64(rv && len > SHORT_ROW);
     while (longmask) {
@@ -72,7 +72,7 @@ __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo, 
         const int64_t r = __shfl(row, l, WAVE);
         const int64_t rlo = __shfl(lo, l, WAVE);
         const int64_t rhi = __shfl(hi, l, WAVE);
-        for (int64_t q = rlo + lane; q < rhi; q += WAVE) f(r, q, q - rlo, col_idx[q], val[q]);
+        for (int64_t q = rlo + lane; q < rhi; q += WAVE) f(r, q, q - rlo, col_idx[q], val[q], false);
     }
 }
 
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(CB) void k_offsets_and_slots(const int32_t *__restr
 template <typename T>
 __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
-                                                  int64_t ld, T *__restrict__ dval)
+                                                  int64_t ld, T *__restrict__ dval, int32_t *__restrict__ rest_cnt)
 {
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
     __shared__ T s_val[(CB / WAVE) * WCAP];
@@ -178,10 +178,22 @@ __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row
     const bool rv = row < m;
     const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
     const int w = threadIdx.x / WAVE;
-    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP, [&](int64_t r, int64_t, int64_t, int32_t c, T v) {
+    // HDC: the entries that are on no kept diagonal are counted per row on the way (rest_cnt starts at zero): a row
+    // walked by its own lane adds its count once at the end, a long row walked by the whole wave adds per 64 entries.
+    int32_t mine = 0;
+    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP,
+                     [&](int64_t r, int64_t, int64_t, int32_t c, T v, bool own) {
         const int k = slot[(int64_t)c - r + (m - 1)];
         if (k >= 0) dval[(int64_t)k * ld + r] = v;
+        if (rest_cnt) {
+            if (own) mine += k < 0;
+            else {   // all active lanes are on the same long row r: one atomic for the 64 entries
+                const uint64_t rest = ballot64(k < 0);
+                if (rest && lane_id() == __ffsll((unsigned long long)rest) - 1) atomicAdd(&rest_cnt[r], (int32_t)__popcll(rest));
+            }
+        }
     });
+    if (rest_cnt && mine) atomicAdd(&rest_cnt[row], mine);
 }
 
 // ------------------------------------------------------------------ ELL (and the ELL part of HYB)
@@ -206,7 +218,7 @@ __global__ __launch_bounds__(CB) void k_fill_ell(const int32_t *__restrict__ row
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
     __shared__ T s_val[(CB / WAVE) * WCAP];
     const int w = threadIdx.x / WAVE;
-    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP, [&](int64_t r, int64_t, int64_t s, int32_t c, T v) {
+    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP, [&](int64_t r, int64_t, int64_t s, int32_t c, T v, bool) {
         if (s < K) {
             ecol[s * ld + r] = c;
             eval[s * ld + r] = v;
@@ -264,31 +276,32 @@ __global__ __launch_bounds__(CB) void k_surplus(const int32_t *__restrict__ row_
 }
 
 // ------------------------------------------------------------------ HDC remainder
-// FILL = false: cnt[row] = number of entries of the row that are not on a kept diagonal.
-// FILL = true : those entries are written, in row order, to the CSR part starting at rest_ptr[row].
-template <typename T, bool FILL>
+// The entries of a row that are on no kept diagonal are written, in row order, to the CSR part starting at
+// rest_ptr[row] (their number per row was counted while the DIA part was filled).  Short rows are walked by their
+// own lane out of the wave's LDS stage; a long row is compacted by the whole wave, 64 entries at a time, with a
+// ballot prefix so that the order inside the row is kept.
+template <typename T>
 __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
-                                                  int32_t *__restrict__ cnt, const int32_t *__restrict__ rest_ptr,
-                                                  int32_t *__restrict__ rcol, T *__restrict__ rval)
+                                                  const int32_t *__restrict__ rest_ptr, int32_t *__restrict__ rcol, T *__restrict__ rval)
 {
+    __shared__ int32_t s_col[(CB / WAVE) * WCAP];
+    __shared__ T s_val[(CB / WAVE) * WCAP];
     const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
     const bool rv = row < m;
     const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
     const int64_t len = hi - lo;
-    const int sl = (int)(len < SHORT_ROW ? len : SHORT_ROW);
-    const int wmax = wave_max(rv ? sl : 0);
-    const int64_t base = (FILL && rv) ? rest_ptr[row] : 0;
+    const int64_t base = rv ? rest_ptr[row] : 0;
+    const int w = threadIdx.x / WAVE;
     int64_t mine = 0;
-    for (int k = 0; k < wmax; ++k) {
-        if (rv && k < sl) {
-            const int32_t c = col_idx[lo + k];
-            if (slot[(int64_t)c - row + (m - 1)] < 0) {
-                if (FILL) { rcol[base + mine] = c; rval[base + mine] = val[lo + k]; }
-                ++mine;
-            }
+    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP,
+                     [&](int64_t r, int64_t, int64_t, int32_t c, T v, bool own) {
+        if (own && slot[(int64_t)c - r + (m - 1)] < 0) {
+            rcol[base + mine] = c;
+            rval[base + mine] = v;
+            ++mine;
         }
-    }
+    });
     uint64_t longmask = ballot64(rv && len > SHORT_ROW);
     const int lane = lane_id();
     const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (WAVE - lane));
@@ -297,9 +310,9 @@ __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row
         longmask &= longmask - 1;
         const int64_t r = __shfl(row, l, WAVE);
         const int64_t rlo = __shfl(lo, l, WAVE), rhi = __shfl(hi, l, WAVE);
-        int64_t run = __shfl(mine, l, WAVE);
         const int64_t rbase = __shfl(base, l, WAVE);
-        for (int64_t q0 = rlo + SHORT_ROW; q0 < rhi; q0 += WAVE) {
+        int64_t run = 0;
+        for (int64_t q0 = rlo; q0 < rhi; q0 += WAVE) {
             const int64_t q = q0 + lane;
             bool rest = false;
             int32_t c = 0;
@@ -308,16 +321,14 @@ __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row
                 rest = slot[(int64_t)c - r + (m - 1)] < 0;
             }
             const uint64_t mask = ballot64(rest);
-            if (FILL && rest) {
+            if (rest) {
                 const int64_t pos = rbase + run + __popcll(mask & below);
                 rcol[pos] = c;
                 rval[pos] = val[q];
             }
             run += __popcll(mask);
         }
-        if (lane == l) mine = run;
     }
-    if (!FILL && rv) cnt[row] = (int32_t)mine;
 }
 
 // ------------------------------------------------------------------ host side
@@ -409,7 +420,7 @@ mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, i
 // Slot map for the DIA part: offsets (ascending) into h->dia_off, slot[] (m + n - 1 ints, scratch) for the fill.
 template <typename T>
 mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an, bool all_nonempty, int64_t nd,
-                         Builder &b, Scratch &scr, int32_t **slot_out)
+                         Builder &b, Scratch &scr, int32_t **slot_out, int32_t *rest_cnt = nullptr)
 {
     hipStream_t s = b.s;
     const int64_t ndiag = a.m + a.n - 1;
@@ -432,8 +443,15 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
     if (nd > 0) {
         hipLaunchKernelGGL(k_fill_val<T>, dim3(fill_grid(nd * h->ld)), dim3(CB), 0, s, (T *)h->dia_val, nd * h->ld);
         MO_LAUNCH_CHECK();
+        if (rest_cnt) {
+            hipLaunchKernelGGL(k_fill_i32, dim3(fill_grid(a.m)), dim3(CB), 0, s, rest_cnt, a.m, 0);
+            MO_LAUNCH_CHECK();
+        }
         hipLaunchKernelGGL(k_fill_dia<T>, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.col_idx, (const T *)a.val, a.m,
-                           pos, h->ld, (T *)h->dia_val);
+                           pos, h->ld, (T *)h->dia_val, rest_cnt);
+        MO_LAUNCH_CHECK();
+    } else if (rest_cnt) {   // no diagonal is kept: every entry is remainder
+        hipLaunchKernelGGL(k_surplus, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.m, (int64_t)0, rest_cnt);
         MO_LAUNCH_CHECK();
     }
     *slot_out = pos;
@@ -574,14 +592,11 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
     }
     case MO_HDC: {
         int32_t *slot = nullptr;
-        MO_TRY(build_dia_part<T>(a, p, an, false, an.n_true, b, scr, &slot));
         int32_t *cnt = (int32_t *)scr.get((size_t)a.m * 4);
         int32_t *rest_ptr = (int32_t *)b.own((size_t)(a.m + 1) * 4);
         void *tmp = scr.get(scan_tmp_bytes(a.m));
         if (b.failed || !cnt || !tmp) return MO_E_ALLOC;
-        hipLaunchKernelGGL((k_hdc_rest<T, false>), dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot, cnt,
-                           (const int32_t *)nullptr, (int32_t *)nullptr, (T *)nullptr);
-        MO_LAUNCH_CHECK();
+        MO_TRY(build_dia_part<T>(a, p, an, false, an.n_true, b, scr, &slot, cnt));   // also counts the remainder per row
         MO_TRY(exclusive_scan_i32(cnt, rest_ptr, a.m, tmp, s));
         int32_t total = 0;
         MO_HIP(hipMemcpyAsync(&total, rest_ptr + a.m, 4, hipMemcpyDeviceToHost, s));
@@ -591,9 +606,10 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         int32_t *rcol = (int32_t *)b.own(e * 4);
         T *rval = (T *)b.own(e * sizeof(T));
         if (b.failed) return MO_E_ALLOC;
-        hipLaunchKernelGGL((k_hdc_rest<T, true>), dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot,
-                           (int32_t *)nullptr, rest_ptr, rcol, rval);
-        MO_LAUNCH_CHECK();
+        if (total > 0) {
+            hipLaunchKernelGGL(k_hdc_rest<T>, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot, rest_ptr, rcol, rval);
+            MO_LAUNCH_CHECK();
+        }
         h->csr_row_ptr = rest_ptr; h->csr_col = rcol; h->csr_val = rval;
         MO_TRY(plan_csr(b, rest_ptr, a.m, total, an.max_row));
         break;
