@@ -116,8 +116,10 @@ void mo_default_params(mo_params *out);
  * of the number of entries per row, number of non-empty diagonals, number of true diagonals (Section IV-A).
  * The integer counts come from device kernels over the CSR arrays; the four derived doubles are formed on the
  * host from those integers (std = sqrt((M*sum_sq_row - NNZ^2) / M^2), correctly rounded operations only).
- * out: host array of 10 doubles.  ints_opt: optional host struct.  Synchronises `stream`.  Allocates and
- * frees device scratch of 4*(m+n) bytes through the installed allocator. */
+ * out: host array of 10 doubles.  ints_opt: optional host struct.  Synchronises `stream`.  This is the call a deployed
+ * tuner pays per matrix, so it keeps its device scratch (about 6*(m+n) bytes, grown on demand through the installed
+ * allocator) and a small pinned host block between calls; mo_set_allocator releases the device block.  Calls from
+ * several threads are safe: one of them uses the kept block, the others allocate and free per call. */
 mo_status mo_features(const mo_csr *a, const mo_params *params, double out[MO_NUM_FEATURES],
                       mo_feature_ints *ints_opt, void *stream);
 

@@ -49,6 +49,7 @@ void mo_default_params(mo_params *out)
 mo_status mo_set_allocator(void *(*alloc)(size_t, void *, void *), void (*free_)(void *, void *, void *), void *user)
 {
     if ((alloc == nullptr) != (free_ == nullptr)) return MO_E_NULL;
+    release_feature_cache();   // through the allocator it came from
     g_alloc = alloc; g_free = free_; g_user = user;
     return MO_OK;
 }
@@ -82,10 +83,7 @@ mo_status mo_features(const mo_csr *a, const mo_params *params, double out[MO_NU
     MO_TRY(check_params(params, &p));
     hipStream_t s = (hipStream_t)stream;
     Analysis an;
-    {
-        Scratch scr(s);
-        MO_TRY(analyse(*a, p, true, &an, scr, s));
-    }
+    MO_TRY(analyse_cached(*a, p, &an, s));
     // Table I, from exact integers.  M * sum(len^2) - NNZ^2 equals M^2 times the mean squared deviation of the row
     // lengths; every floating-point operation below is a single correctly rounded IEEE operation.
     const unsigned __int128 num = (unsigned __int128)a->m * (unsigned __int128)an.sum_sq -

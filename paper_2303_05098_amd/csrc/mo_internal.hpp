@@ -117,6 +117,9 @@ struct Analysis {
 // Validates the CSR arrays and gathers the row statistics; with want_hist also the per-diagonal counts and the
 // two diagonal features.  Synchronises the stream.
 mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis *out, Scratch &scratch, hipStream_t s);
+// The same numbers (histogram included in the counts, not handed out) with scratch that is kept between calls.
+mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hipStream_t s);
+void release_feature_cache();
 
 // ---------------------------------------------------------------- conversions (convert.hip)
 mo_status convert_impl(const mo_csr &a, mo_format fmt, const mo_params &p, const Analysis &an, mo_matrix **out, hipStream_t s);

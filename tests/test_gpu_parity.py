@@ -270,3 +270,30 @@ def test_other_stream_and_default_allocator():
             err, ok = ref.spmv_error(y.cpu().numpy(), y_ref, mag)
             assert err <= 1e-13 and ok
             h.free()
+
+
+def test_features_scratch_is_reused_safely():
+    """mo_features keeps its scratch between calls: growing and shrinking matrices, a rejected matrix in between, another
+    stream and a change of allocator must all leave the next result exact."""
+    seq = [("c1", None), ("c4s", None), ("tiny", None), ("bad", "col_high"), ("c2s", None), ("bad", "rp_decreasing"),
+           ("rect_wide", None), ("c4s", None), ("empty", None), ("long_row", None)]
+    other = torch.cuda.Stream()
+    for step, (name, kind) in enumerate(seq):
+        if name == "bad":
+            a = upload(*bad_csr(kind))
+            with pytest.raises(mo.MoError) as e:
+                mo.mo_features(a)
+            assert e.value.status == mo.MO_E_CSR_INVALID
+            continue
+        _, m, n, rp, ci, v = CASES[IDS.index(name)]
+        a = upload(m, n, rp, ci, v)
+        ti, tj, _ = ref.csr_to_triplets(rp, ci, v)
+        fo, io = ref.features(m, n, ti, tj)
+        if step == 6:       # back to hipMalloc / hipFree and on to torch's allocator again: the kept block is released
+            assert mo.lib.mo_set_allocator(C.cast(None, mo._ALLOC_T), C.cast(None, mo._FREE_T), None) == mo.MO_OK
+            f, ints = mo.mo_features(a)
+            assert f.tobytes() == fo.tobytes() and ints == io
+            assert mo.lib.mo_set_allocator(mo._alloc_cb, mo._free_cb, None) == mo.MO_OK
+        for stream in (None, other):
+            f, ints = mo.mo_features(a, stream=stream)
+            assert f.tobytes() == fo.tobytes() and ints == io, (name, stream)
