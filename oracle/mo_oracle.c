@@ -11,9 +11,12 @@
  * promised).  Stored zeros are entries like any other.
  *
  * What is a definition and what is a procedure:
- *   - SpMV, the five conversions and the ten features are definitions: the
- *     code below writes each one out directly (Section II-B for the formats,
- *     Table I and Section IV-A for the features).
+ *   - SpMV, its multi-vector form Y = A X, the five conversions, the way back
+ *     from each format to triplets and to CSR, and the ten features are
+ *     definitions: the code below writes each one out directly (Section II-B
+ *     for the formats, Table I and Section IV-A for the features).  A DIA slab
+ *     cannot tell a stored zero from padding: on the way back positions
+ *     holding exactly 0 are not entries.
  *   - The HYB width K_H, the true-diagonal test, tree/forest evaluation
  *     (Section VI-A: traverse each tree, majority vote) and the run-first pick
  *     (Section VII-A: the format with the minimum runtime) are procedures and
@@ -36,7 +39,8 @@
  * Pins (tests, CPU only): dense matvec on tiny matrices, closed forms for the
  * 2-D 5-point and 3-D 27-point stencils, scipy.sparse cross-checks, brute
  * force on small random inputs, round trips of every conversion, hand-built
- * trees and scikit-learn tree arrays.  Run-first timings are hardware
+ * trees and scikit-learn tree arrays, and a mutation run that plants mistakes
+ * in copies of this file and requires the pins to catch each.  Run-first timings are hardware
  * measurements: parity unpinned for those (only argmin bookkeeping is pinned).
  */
 #include <math.h>

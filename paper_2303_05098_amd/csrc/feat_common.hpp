@@ -30,6 +30,15 @@ static __global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
     for (; i < n; i += stride) p[i] = v;
 }
 
+// p[0, n) = 0 and the counter block reset, in one launch.
+static __global__ void k_zero_and_reset(uint32_t *p, int64_t n, Counters *c)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (i == 0) { c->max_row = 0ull; c->min_row = ~0ull; c->sum_sq = 0ull; c->n_diag = 0ull; c->n_true = 0ull; c->err = 0u; c->pad = 0u; }
+    for (; i < n; i += stride) p[i] = 0u;
+}
+
 constexpr int HT_SIZE = 2048;     // LDS table slots (power of two)
 constexpr int HT_PROBES = 4;
 constexpr int MERGE_ROUNDS = 4;

@@ -43,15 +43,6 @@ struct RowPart {
     unsigned long long max_row, min_row, sum_sq, err;
 };
 
-// hist[0, n) = 0 and the diagonal counters reset, in one launch.
-__global__ void k_prepare(uint32_t *hist, int64_t n, Counters *c)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    if (i == 0) { c->max_row = 0ull; c->min_row = ~0ull; c->sum_sq = 0ull; c->n_diag = 0ull; c->n_true = 0ull; c->err = 0u; c->pad = 0u; }
-    for (; i < n; i += stride) hist[i] = 0u;
-}
-
 template <bool DO_HIST>
 __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   int64_t m, int64_t n, int64_t nnz, int64_t rows_per_block,
@@ -73,6 +64,7 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
     __syncthreads();
     const int lane = lane_id();
     bool err = false;
+    uint64_t errm = 0ull;   // lanes of this wave that met a column out of range or out of order
     unsigned long long mx = 0ull, mn = ~0ull, sq = 0ull;
     // per-step cache of (diagonal, count): step k owns lanes k and k + SHORT_ROW of the pairs A and B (four ways)
     int ckeyA = -1, ckeyB = -1;
@@ -121,25 +113,31 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
             const int cnt = mine_now ? len : 0;   // <= SHORT_ROW
             const int32_t *mine = s_col + (mine_now ? lo - start : 0);
             int prev = -1;
-            for (int k = 0; ballot64(k < cnt) != 0ull; ++k) {
+            const int cm1 = cnt > 0 ? cnt - 1 : 0;
+            // Lane masks are built from the compare instructions' own 64-bit results and combined with scalar
+            // operations: every per-lane boolean that is turned into a mask costs two more vector instructions.
+            for (int k = 0;; ++k) {
+                const uint64_t actm = __builtin_amdgcn_sicmp(k, cnt, 40 /* signed < */);
+                if (!actm) break;
                 const int ks = __builtin_amdgcn_readfirstlane(k);
-                const bool act = k < cnt;
-                const int c = act ? mine[k] : 0;
-                const bool ok = act && (unsigned)c < (unsigned)n && c > prev;
-                if (act && !ok) err = true;
-                if (act) prev = c;
+                const int c = mine[k < cm1 ? k : cm1];   // lanes past their row end re-read their last entry (unused)
+                const uint64_t okm = actm & __builtin_amdgcn_uicmp((unsigned)c, (unsigned)n, 36 /* unsigned < */) &
+                                     __builtin_amdgcn_sicmp(c, prev, 38 /* signed > */);
+                errm |= actm & ~okm;
+                prev = c;                                 // a lane past its row end never becomes active again in this chunk
                 if (DO_HIST) {
                     const int key = c + krow;
                     // the four cached diagonals of step k: lanes k and k + SHORT_ROW of two register pairs; the
                     // second pair is only looked at when the first does not cover the step
-                    const uint64_t okm = ballot64(ok);
                     const int k0 = __builtin_amdgcn_readlane(ckeyA, ks), k1 = __builtin_amdgcn_readlane(ckeyA, ks + SHORT_ROW);
-                    const uint64_t h0 = ballot64(ok && key == k0), h1 = ballot64(ok && key == k1);
+                    const uint64_t h0 = okm & __builtin_amdgcn_sicmp(key, k0, 32 /* == */);
+                    const uint64_t h1 = okm & __builtin_amdgcn_sicmp(key, k1, 32);
                     ccntA += lane == ks ? __popcll(h0) : (lane == ks + SHORT_ROW ? __popcll(h1) : 0);
                     uint64_t todo = okm & ~(h0 | h1);
                     if (todo) {
                         const int k2 = __builtin_amdgcn_readlane(ckeyB, ks), k3 = __builtin_amdgcn_readlane(ckeyB, ks + SHORT_ROW);
-                        const uint64_t h2 = ballot64(ok && key == k2), h3 = ballot64(ok && key == k3);
+                        const uint64_t h2 = okm & __builtin_amdgcn_sicmp(key, k2, 32);
+                        const uint64_t h3 = okm & __builtin_amdgcn_sicmp(key, k3, 32);
                         ccntB += lane == ks ? __popcll(h2) : (lane == ks + SHORT_ROW ? __popcll(h3) : 0);
                         todo &= ~(h2 | h3);
                     }
@@ -152,7 +150,7 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
                         while (todo && rounds-- > 0) {
                             const int leader = __ffsll((unsigned long long)todo) - 1;
                             const int lkey = __builtin_amdgcn_readlane(key, leader);
-                            const uint64_t same = ballot64(ok && key == lkey) & todo;
+                            const uint64_t same = __builtin_amdgcn_sicmp(key, lkey, 32) & todo;   // todo holds valid lanes only
                             const int mult = __popcll(same);
                             const int n0 = __builtin_amdgcn_readlane(ccntA, ks), n1 = __builtin_amdgcn_readlane(ccntA, ks + SHORT_ROW);
                             const int n2 = __builtin_amdgcn_readlane(ccntB, ks), n3 = __builtin_amdgcn_readlane(ccntB, ks + SHORT_ROW);
@@ -208,6 +206,7 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
         }
     }
     // row-length statistics and the error flag of this block
+    if (errm) err = true;
     mx = wave_max(mx); mn = wave_min(mn); sq = wave_sum(sq);
     __shared__ unsigned long long s_mx[TB / WAVE], s_mn[TB / WAVE], s_sq[TB / WAVE];
     __shared__ int s_err;
@@ -242,7 +241,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     RowPart *part = (RowPart *)(base + 256);
     uint32_t *hist = want_hist ? (uint32_t *)(base + head) : nullptr;
     if (want_hist) {
-        hipLaunchKernelGGL(k_prepare, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr);
+        hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr);
         MO_LAUNCH_CHECK();
         hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
                            rows_per_block, hist, part, (Counters *)nullptr);
@@ -368,7 +367,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     const bool was_clean = g_fc.clean;
     g_fc.clean = false;
     if (!was_clean) {
-        hipLaunchKernelGGL(k_prepare, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, ctr);
+        hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, ctr);
         MO_LAUNCH_CHECK();
     }
     int64_t rows_per_block = (a.m + TRAV_BLOCKS - 1) / TRAV_BLOCKS;

@@ -335,16 +335,15 @@ static mo_status features_any(const mo_matrix &a, const mo_params &p, Counters *
     const View<T> v = make_view<T>(a);
     Scratch scr(s);
     const int64_t ndiag = a.m + a.n - 1;
-    int32_t *len = (int32_t *)scr.get((size_t)a.m * 4);
-    uint32_t *hist = (uint32_t *)scr.get((size_t)ndiag * 4);
-    Counters *ctr = (Counters *)scr.get(sizeof(Counters) + 8);
-    if (!len || !hist || !ctr) return MO_E_ALLOC;
-    unsigned long long *total = (unsigned long long *)(ctr + 1);
-    hipLaunchKernelGGL(k_init_counters, dim3(1), dim3(64), 0, s, ctr);
-    MO_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(ndiag + 2, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, 0u);
-    MO_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, (uint32_t *)total, (int64_t)2, 0u);
+    // one block of scratch: [counters, 256 bytes | entry total, 256 bytes | diagonal counters | row lengths]
+    char *base = (char *)scr.get(512 + (size_t)ndiag * 4 + (size_t)a.m * 4);
+    if (!base) return MO_E_ALLOC;
+    Counters *ctr = (Counters *)base;
+    unsigned long long *total = (unsigned long long *)(base + 256);
+    uint32_t *hist = (uint32_t *)(base + 512);
+    int32_t *len = (int32_t *)(base + 512 + (size_t)ndiag * 4);
+    // the total and the histogram are contiguous: one launch zeroes both and resets the counters
+    hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag + 64, FB * 4, 4096)), dim3(FB), 0, s, (uint32_t *)total, ndiag + 64, ctr);
     MO_LAUNCH_CHECK();
     const unsigned rb = (unsigned)((a.m + FB - 1) / FB);
     hipLaunchKernelGGL(k_len_any<T>, dim3(rb), dim3(FB), 0, s, v, len);
@@ -368,8 +367,9 @@ static mo_status features_any(const mo_matrix &a, const mo_params &p, Counters *
     hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
                        (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
     MO_LAUNCH_CHECK();
-    struct { Counters c; unsigned long long total; } host;
-    MO_HIP(hipMemcpyAsync(&host, ctr, sizeof(Counters) + 8, hipMemcpyDeviceToHost, s));
+    struct { Counters c; char pad[256 - sizeof(Counters)]; unsigned long long total; } host;   // mirrors the head of the block
+    static_assert(sizeof(host) == 264, "counters in the first 256 bytes, the total right after");
+    MO_HIP(hipMemcpyAsync(&host, base, sizeof(host), hipMemcpyDeviceToHost, s));
     MO_HIP(hipStreamSynchronize(s));
     *h_out = host.c;
     *nnz_out = host.total;
