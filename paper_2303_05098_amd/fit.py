@@ -96,9 +96,11 @@ def model_cost(o: dict) -> tuple:
 
 
 def grid_search(X, y, grid: dict, k: int = 5, seed: int = synth.BASE_SEED, score: str = "balanced_accuracy",
-                workers: int | None = None) -> dict:
-    """Exhaustive search (Section VII-C): the whole k-fold CV for every grid point, on the same folds; the winner has
-    the highest mean-over-samples `score`, ties to the cheaper model, then to the earlier grid point."""
+                workers: int | None = None, tolerance: float = 0.0) -> dict:
+    """Exhaustive search (Section VII-C): the whole k-fold CV for every grid point, on the same folds.  The winner is
+    the cheapest model (fewest trees, then shallowest, then the earlier grid point) among the points whose
+    mean-over-samples `score` is within `tolerance` of the highest one; tolerance 0 is the plain arg-max with ties to
+    the cheaper model."""
     X = np.asarray(X, dtype=np.float64)
     y = np.asarray(y, dtype=np.int64)
     fold = stratified_folds(y, k, seed)
@@ -113,9 +115,10 @@ def grid_search(X, y, grid: dict, k: int = 5, seed: int = synth.BASE_SEED, score
         scores = list(ex.map(one, points))
     col = 1 if score == "balanced_accuracy" else 0
     order = sorted(range(len(points)), key=lambda i: (-scores[i][col], model_cost(points[i]), i))
-    best = order[0]
+    top = scores[order[0]][col]
+    best = min((i for i in order if scores[i][col] >= top - tolerance), key=lambda i: (model_cost(points[i]), -scores[i][col], i))
     return dict(best=points[best], best_cv_accuracy=scores[best][0], best_cv_balanced_accuracy=scores[best][1],
-                n_points=len(points), score=score,
+                top_cv_score=top, tolerance=tolerance, n_points=len(points), score=score,
                 table=[dict(opts=points[i], cv_accuracy=scores[i][0], cv_balanced_accuracy=scores[i][1]) for i in order])
 
 

@@ -56,8 +56,15 @@ def test_grid_search_bookkeeping():
         cv = fit.cross_validate(X, y, 5, seed=5, **r["opts"])
         assert (cv["accuracy"], cv["balanced_accuracy"]) == (r["cv_accuracy"], r["cv_balanced_accuracy"])
     # ties go to the cheaper model: with a constant label every point scores 1.0 and the smallest forest wins
-    gs = fit.grid_search(X, np.full(160, 3), grid, 5, workers=2)
-    assert gs["best_cv_accuracy"] == 1.0 and gs["best"]["n_estimators"] == 1 and gs["best"]["max_depth"] == 1
+    gc = fit.grid_search(X, np.full(160, 3), grid, 5, workers=2)
+    assert gc["best_cv_accuracy"] == 1.0 and gc["best"]["n_estimators"] == 1 and gc["best"]["max_depth"] == 1
+    # a tolerance trades score for a cheaper model: the winner is the cheapest point within it
+    gt = fit.grid_search(X, y, grid, 5, seed=5, workers=4, tolerance=0.05)
+    top = gt["table"][0]["cv_balanced_accuracy"]
+    assert gt["top_cv_score"] == top and top - 0.05 <= gt["best_cv_balanced_accuracy"] <= top
+    within = [r["opts"] for r in gt["table"] if r["cv_balanced_accuracy"] >= top - 0.05]
+    assert fit.model_cost(gt["best"]) == min(fit.model_cost(o) for o in within)
+    assert fit.model_cost(gt["best"]) <= fit.model_cost(gs["best"])
     # selection by plain accuracy
     ga = fit.grid_search(X, y, grid, 5, seed=5, score="accuracy", workers=4)
     acc = [r["cv_accuracy"] for r in ga["table"]]

@@ -96,12 +96,25 @@ def run_config(c, dtype, expect_infeasible=()):
     f, ints = mo.mo_features(a)
     fo, io = ref.features(m, n, ti, tj)
     assert f.tobytes() == fo.tobytes() and ints == io
+    # the second operation at full size: 8 right-hand sides, every entry of Y against the oracle
+    K = 8
+    X = synth.uniform_pm1(synth.BASE_SEED + 40 + c, 0, np.arange(n * K)).reshape(n, K).astype(dtype)
+    Y_ref, Mag = ref.spmm(m, n, ti, tj, ta, X.astype(np.float64))
+    Xd = torch.as_tensor(X).cuda()
     for fmt in range(6):
         h = try_convert(a, fmt)
         if mo.FORMAT_NAMES[fmt] in expect_infeasible:
             assert h is None
             continue
         assert h is not None
+        Yd = torch.full((m, K), float("nan"), dtype=Xd.dtype, device="cuda")
+        mo.mo_spmm(h, Xd, Yd)
+        torch.cuda.synchronize()
+        Y = Yd.cpu().numpy().astype(np.float64)
+        nz = Mag > 0
+        assert float(np.max(np.abs(Y[nz] - Y_ref[nz]) / Mag[nz])) <= TOL[dtype], mo.FORMAT_NAMES[fmt]
+        assert np.all(Y[~nz] == 0)
+        del Yd, Y
         y = gpu_spmv(h, x, m, dtype)
         err, zeros_ok = ref.spmv_error(y, y_ref, mag)
         assert err <= TOL[dtype] and zeros_ok, (mo.FORMAT_NAMES[fmt], err)

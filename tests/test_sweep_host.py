@@ -49,7 +49,13 @@ def test_committed_report_is_what_the_records_give():
         # the tuned setting is a point of the reported grid and won the search by the reported score
         tuned = rep[kind]["tuned"]
         assert all(tuned["test"]["opts"][k] in rep[kind]["grid"][k] for k in rep[kind]["grid"])
-        assert all(tuned["cv_balanced_accuracy"] >= r["cv_balanced_accuracy"] for r in rep[kind]["runners_up"])
+        # ... and won the search: within the tolerance of the best score, and none of the higher-scoring points is cheaper
+        top, tol = rep[kind]["top_cv_score"], rep["selection_tolerance"]
+        assert rep[kind]["best_by_score"][0]["cv_balanced_accuracy"] == top
+        assert top - tol <= tuned["cv_balanced_accuracy"] <= top
+        for r in rep[kind]["best_by_score"]:
+            if r["cv_balanced_accuracy"] >= top - tol:
+                assert fit.model_cost(tuned["test"]["opts"]) <= fit.model_cost(r["opts"])
         cv = fit.cross_validate(X[~test], y[~test], 5, **tuned["test"]["opts"])
         assert (cv["accuracy"], cv["balanced_accuracy"]) == (tuned["cv_accuracy"], tuned["cv_balanced_accuracy"])
     # speedups on the test set: the best format is never slower than CSR, a prediction never beats the best
