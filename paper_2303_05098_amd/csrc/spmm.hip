@@ -18,6 +18,7 @@ namespace mo {
 
 constexpr int MB = 256;
 constexpr int RCAP = 1024;   // entries a wave stages at a time in the row-pointer kernel
+constexpr int SPMM_LONG_ROW = 64;   // rows longer than this are walked by the whole wave
 
 template <typename T, int K>
 __device__ __forceinline__ void fma_row(T (&acc)[K], T a, const T *__restrict__ xr)
@@ -67,9 +68,10 @@ __global__ __launch_bounds__(MB) void k_spmm_ell(const int32_t *__restrict__ col
 }
 
 // Rows by row pointer.  The entries of a wave's 64 rows are one contiguous run: it is staged in LDS in chunks of whole
-// rows (as many consecutive rows as fit RCAP entries) and every lane walks its own row out of LDS.  A row longer
-// than a chunk is walked by its lane straight from memory.  rp comes from a validated CSR or was built by the
-// conversions, so it is non-decreasing; the conditions below still keep every LDS index inside the chunk.
+// rows (as many consecutive rows as fit RCAP entries) and every lane walks its own row out of LDS.  Rows of more
+// than SPMM_LONG_ROW entries are left to the whole wave, so that one long row does not keep 63 lanes waiting.  rp
+// comes from a validated CSR or was built by the conversions, so it is non-decreasing; the conditions below still
+// keep every LDS index inside the chunk.
 template <typename T, int K, bool ACC>
 __global__ __launch_bounds__(MB) void k_spmm_rows(const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
                                                    const T *__restrict__ val, int64_t m, int64_t ldk, const T *__restrict__ x,
@@ -86,18 +88,14 @@ __global__ __launch_bounds__(MB) void k_spmm_rows(const int32_t *__restrict__ rp
     T acc[K];
 #pragma unroll
     for (int v = 0; v < K; ++v) acc[v] = (T)0;
+    const bool is_long = rv && hi - lo > SPMM_LONG_ROW;
     const int nvalid = __popcll(ballot64(rv));
     int first = 0;
     while (first < nvalid) {
         const int start = __builtin_amdgcn_readlane(lo, first);
         const uint64_t fits = ballot64(rv && lo >= start && hi >= lo && hi - start <= RCAP) >> first;
         const int nrun = ~fits ? __ffsll((unsigned long long)~fits) - 1 : WAVE;
-        if (nrun <= 0) {
-            if (lane == first)
-                for (int p = lo; p < hi; ++p) fma_row<T, K>(acc, val[p], x + (int64_t)col[p] * ldk);
-            ++first;
-            continue;
-        }
+        if (nrun <= 0) { ++first; continue; }   // longer than a chunk: a long row, walked by the whole wave below
         const int last = first + nrun - 1;
         const int end = __builtin_amdgcn_readlane(hi, last);
         const int total = end - start;   // 0 .. RCAP
@@ -105,9 +103,26 @@ __global__ __launch_bounds__(MB) void k_spmm_rows(const int32_t *__restrict__ rp
             stage_to_lds(col + start, s_col, total, lane);
             stage_to_lds(val + start, s_val, total, lane);
         }
-        if (lane >= first && lane <= last && hi <= end)
+        if (!is_long && lane >= first && lane <= last && hi <= end)
             for (int p = lo - start; p < hi - start; ++p) fma_row<T, K>(acc, s_val[p], x + (int64_t)s_col[p] * ldk);
         first = last + 1;
+    }
+    // Long rows: the 64 lanes share the row's entries (coalesced loads straight from memory), the K partial sums of
+    // every lane are added across the wave in a fixed order, and the row's own lane keeps the result.
+    uint64_t longmask = ballot64(is_long);
+    while (longmask) {
+        const int l = __ffsll((unsigned long long)longmask) - 1;
+        longmask &= longmask - 1;
+        const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
+        T part[K];
+#pragma unroll
+        for (int v = 0; v < K; ++v) part[v] = (T)0;
+        for (int p = rlo + lane; p < rhi; p += WAVE) fma_row<T, K>(part, val[p], x + (int64_t)col[p] * ldk);
+#pragma unroll
+        for (int v = 0; v < K; ++v) {
+            const T t = wave_sum(part[v]);
+            if (lane == l) acc[v] = t;
+        }
     }
     if (rv && (!ACC || hi > lo)) store_row<T, K, ACC>(y + i * ldk, acc);
 }
