@@ -47,32 +47,35 @@ __device__ __forceinline__ void walk_rows(bool rv, int64_t row, int64_t lo, int6
 constexpr int WCAP = 1024;
 
 template <typename T, class F>
-__device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo, int64_t hi, const int32_t *__restrict__ col_idx,
+__device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo64, int64_t hi64, const int32_t *__restrict__ col_idx,
                                               const T *__restrict__ val, int32_t *s_col, T *s_val, F f)
 {
     const int lane = lane_id();
-    const int64_t len = hi - lo;
+    const int lo = (int)lo64, hi = (int)hi64;   // positions fit 32 bits: nnz < 2^31
+    const int len = hi - lo;
     const bool is_short = rv && len <= SHORT_ROW;
-    const int64_t wb = wave_min(rv ? lo : (int64_t)0x7fffffffffffll);
-    const int64_t we = wave_max(rv ? hi : (int64_t)0);
-    for (int64_t c0 = wb; c0 < we; c0 += WCAP) {
-        const int64_t c1 = c0 + WCAP < we ? c0 + WCAP : we;
-        stage_to_lds(col_idx + c0, s_col, (int)(c1 - c0), lane);
-        stage_to_lds(val + c0, s_val, (int)(c1 - c0), lane);
-        const int64_t a = lo > c0 ? lo : c0, b = hi < c1 ? hi : c1;
-        const int cnt = (is_short && b > a) ? (int)(b - a) : 0;
-        const int wmax = wave_max(cnt);
-        for (int k = 0; k < wmax; ++k)
-            if (k < cnt) f(row, a + k, a + k - lo, s_col[a + k - c0], s_val[a + k - c0], true);
+    // The valid rows of a wave are a prefix of its lanes and row_ptr is non-decreasing (conversions run on a CSR that
+    // has passed validation), so the wave's run starts at the first lane's lo and ends at the last valid lane's hi.
+    const int nvalid = __popcll(ballot64(rv));
+    const int wb = __builtin_amdgcn_readfirstlane(lo);
+    const int we = nvalid ? __builtin_amdgcn_readlane(hi, nvalid - 1) : 0;
+    for (int c0 = wb; c0 < we; c0 += WCAP) {
+        const int c1 = we - c0 > WCAP ? c0 + WCAP : we;
+        stage_to_lds(col_idx + c0, s_col, c1 - c0, lane);
+        stage_to_lds(val + c0, s_val, c1 - c0, lane);
+        const int a = lo > c0 ? lo : c0, b = hi < c1 ? hi : c1;
+        const int cnt = (is_short && b > a) ? b - a : 0;
+        const int off = cnt ? a - c0 : 0;
+        for (int k = 0; ballot64(k < cnt) != 0ull; ++k)
+            if (k < cnt) f(row, (int64_t)a + k, (int64_t)(a + k - lo), s_col[off + k], s_val[off + k], true);
     }
     uint64_t longmask = ballot64(rv && len > SHORT_ROW);
     while (longmask) {
         const int l = __ffsll((unsigned long long)longmask) - 1;
         longmask &= longmask - 1;
-        const int64_t r = __shfl(row, l, WAVE);
-        const int64_t rlo = __shfl(lo, l, WAVE);
-        const int64_t rhi = __shfl(hi, l, WAVE);
-        for (int64_t q = rlo + lane; q < rhi; q += WAVE) f(r, q, q - rlo, col_idx[q], val[q], false);
+        const int64_t r = row - lane + l;
+        const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
+        for (int q = rlo + lane; q < rhi; q += WAVE) f(r, (int64_t)q, (int64_t)(q - rlo), col_idx[q], val[q], false);
     }
 }
 
