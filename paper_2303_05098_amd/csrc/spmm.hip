@@ -4,9 +4,9 @@
 //
 // The product is computed in column panels of width 8, 4, 2 or 1 (k = 13 is 8 + 4 + 1): one row per lane as in the
 // SpMV kernels, so the matrix is streamed coalesced once per panel, the panel's accumulators live in registers and
-// the panel's values of a row of X are fetched with wide loads.  Panels are no wider than 8 because the rows of X a
-// block touches must stay in the 4 MB L2 of its XCD between their uses by neighbouring rows: at 16 columns the
-// 27-point stencil on 128^3 points fell out of L2 and a single pass took 3.6 times as long as at 8.
+// the panel's values of a row of X are fetched with wide loads.  Wider panels would not help: what limits the
+// product beyond 8 columns is the footprint of the rows of X that neighbouring matrix rows share, which at 16 columns
+// (128-byte rows) no longer fits the 4 MB L2 of an XCD for a 27-point stencil on 128^3 points.
 // Rows given by a row pointer (CSR, the CSR remainder of HDC, the sorted COO arrays with the positions of their row
 // runs) reach the lanes through a per-wave LDS stage filled with coalesced loads, as in the conversion kernels.
 // Every output is summed by one thread in a fixed order: results are bit-identical from run to run.  HYB and HDC run
@@ -18,6 +18,8 @@ namespace mo {
 
 constexpr int MB = 256;
 constexpr int RCAP = 1024;   // entries a wave stages at a time in the row-pointer kernel
+constexpr size_t SPMM_DIA_LDS = 80 * 1024;   // LDS a block may spend on staged rows of X: two blocks per CU (one block per CU
+                                             // measured 1.7x slower than the direct kernel on the banded matrix)
 constexpr int SPMM_LONG_ROW = 64;   // rows longer than this are walked by the whole wave
 
 template <typename T, int K>
@@ -48,6 +50,41 @@ __global__ __launch_bounds__(MB) void k_spmm_dia(const int32_t *__restrict__ off
         const int64_t j = i + off[d];
         if (j >= 0 && j < n) fma_row<T, K>(acc, ld_stream(val + d * ld + i), x + j * ldk);
     }
+    store_row<T, K, false>(y + i * ldk, acc);
+}
+
+// DIA with the window plan of the SpMV kernel (offsets closer than one block of rows share a window of x): the
+// block stages the windows' rows of X, K values each, in LDS once and serves every diagonal from there, instead of
+// fetching K values per row and diagonal through the L1 / texture path.  One row per thread, blockDim.x rows per
+// block (the block size the plan was made for).
+template <typename T, int K>
+__global__ __launch_bounds__(1024) void k_spmm_dia_lds(const int32_t *__restrict__ xpos, const int32_t *__restrict__ cl, int ncl,
+                                                        const T *__restrict__ val, int64_t nd, int64_t ld, int64_t m, int64_t n,
+                                                        int64_t ldk, const T *__restrict__ x, T *__restrict__ y)
+{
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    T *xs = reinterpret_cast<T *>(s_raw);
+    const int rows = blockDim.x;
+    const int64_t row0 = xcd_block(blockIdx.x, gridDim.x) * rows;
+    for (int c = 0; c < ncl; ++c) {
+        const int64_t first = row0 + cl[3 * c];
+        const int len = cl[3 * c + 1], base = cl[3 * c + 2];
+        for (int i = threadIdx.x; i < len * K; i += rows) {
+            const int e = i / K, v = i - e * K;
+            const int64_t j = first + e;
+            xs[(base + e) * K + v] = (j >= 0 && j < n) ? x[j * ldk + v] : (T)0;
+        }
+    }
+    __syncthreads();
+    const int64_t i = row0 + threadIdx.x;
+    if (i >= m) return;
+    T acc[K];
+#pragma unroll
+    for (int v = 0; v < K; ++v) acc[v] = (T)0;
+    const T *vp = val + i;
+    const T *xl = xs + (int64_t)threadIdx.x * K;
+#pragma unroll 4
+    for (int64_t d = 0; d < nd; ++d) fma_row<T, K>(acc, ld_stream(vp + d * ld), xl + (int64_t)xpos[d] * K);
     store_row<T, K, false>(y + i * ldk, acc);
 }
 
@@ -127,15 +164,34 @@ __global__ __launch_bounds__(MB) void k_spmm_rows(const int32_t *__restrict__ rp
     if (rv && (!ACC || hi > lo)) store_row<T, K, ACC>(y + i * ldk, acc);
 }
 
+// One column panel of the DIA part (DIA, or HDC with kept diagonals).  use_lds: the window kernel.
 template <typename T, int K>
-static mo_status spmm_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, hipStream_t s)
+static mo_status dia_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, bool use_lds, hipStream_t s)
+{
+    if (use_lds) {
+        const int64_t rows = (int64_t)a.dia_block * a.dia_rows;   // rows per block the window plan was made for
+        const size_t lds = (size_t)a.dia_lds_elems * K * sizeof(T);
+        static bool raised = false;   // more than 64 KB of dynamic LDS has to be asked for, once per kernel
+        if (!raised) {
+            MO_HIP(hipFuncSetAttribute((const void *)k_spmm_dia_lds<T, K>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SPMM_DIA_LDS));
+            raised = true;
+        }
+        hipLaunchKernelGGL((k_spmm_dia_lds<T, K>), dim3((unsigned)((a.m + rows - 1) / rows)), dim3((unsigned)rows), lds, s, a.dia_xpos,
+                           a.dia_clusters, (int)a.dia_ncl, (const T *)a.dia_val, a.nd, a.ld, a.m, a.n, ldk, x, y);
+    } else {
+        hipLaunchKernelGGL((k_spmm_dia<T, K>), dim3((unsigned)((a.m + MB - 1) / MB)), dim3(MB), 0, s, a.dia_off, (const T *)a.dia_val, a.nd,
+                           a.ld, a.m, a.n, ldk, x, y);
+    }
+    MO_LAUNCH_CHECK();
+    return MO_OK;
+}
+
+// One column panel of everything that is not a DIA part.  after_dia: the DIA part of an HDC handle has already
+// written this panel of Y, the remainder is added to it.
+template <typename T, int K>
+static mo_status rest_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, bool after_dia, hipStream_t s)
 {
     const unsigned grid = (unsigned)((a.m + MB - 1) / MB);
-    const bool dia = a.fmt == MO_DIA || (a.fmt == MO_HDC && a.nd > 0);
-    if (dia) {
-        hipLaunchKernelGGL((k_spmm_dia<T, K>), dim3(grid), dim3(MB), 0, s, a.dia_off, (const T *)a.dia_val, a.nd, a.ld, a.m, a.n, ldk, x, y);
-        MO_LAUNCH_CHECK();
-    }
     switch (a.fmt) {
     case MO_DIA:
         return MO_OK;
@@ -157,7 +213,7 @@ static mo_status spmm_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, h
         MO_LAUNCH_CHECK();
         return MO_OK;
     case MO_HDC:
-        if (!dia) {
+        if (!after_dia) {
             hipLaunchKernelGGL((k_spmm_rows<T, K, false>), dim3(grid), dim3(MB), 0, s, a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, a.m, ldk, x, y);
             MO_LAUNCH_CHECK();
         } else if (a.nnz_csr > 0) {
@@ -172,13 +228,31 @@ static mo_status spmm_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, h
 template <typename T>
 static mo_status spmm_typed(const mo_matrix &a, const T *x, T *y, int k, hipStream_t s)
 {
-    int v0 = 0;
-    while (v0 < k) {
+    const bool dia = a.fmt == MO_DIA || (a.fmt == MO_HDC && a.nd > 0);
+    if (dia) {
+        // The window kernel is worth it when a panel of at least 4 columns (or all k of them) fits its LDS budget;
+        // otherwise the slabs would be streamed too many times and the direct kernel with 8-column panels is used.
+        int widest = 8;
+        const int64_t rows = (int64_t)a.dia_block * a.dia_rows;
+        bool use_lds = rows > 0 && rows <= 1024;
+        if (use_lds) {
+            while (widest > 1 && (size_t)a.dia_lds_elems * widest * sizeof(T) > SPMM_DIA_LDS) widest >>= 1;
+            if ((size_t)a.dia_lds_elems * widest * sizeof(T) > SPMM_DIA_LDS || widest < (k < 4 ? k : 4)) { use_lds = false; widest = 8; }
+        }
+        for (int v0 = 0; v0 < k;) {
+            const int left = k - v0 < widest ? k - v0 : widest;
+            if (left >= 8) { MO_TRY((dia_panel<T, 8>(a, x + v0, y + v0, k, use_lds, s))); v0 += 8; }
+            else if (left >= 4) { MO_TRY((dia_panel<T, 4>(a, x + v0, y + v0, k, use_lds, s))); v0 += 4; }
+            else if (left >= 2) { MO_TRY((dia_panel<T, 2>(a, x + v0, y + v0, k, use_lds, s))); v0 += 2; }
+            else { MO_TRY((dia_panel<T, 1>(a, x + v0, y + v0, k, use_lds, s))); v0 += 1; }
+        }
+    }
+    for (int v0 = 0; v0 < k;) {
         const int left = k - v0;
-        if (left >= 8) { MO_TRY((spmm_panel<T, 8>(a, x + v0, y + v0, k, s))); v0 += 8; }
-        else if (left >= 4) { MO_TRY((spmm_panel<T, 4>(a, x + v0, y + v0, k, s))); v0 += 4; }
-        else if (left >= 2) { MO_TRY((spmm_panel<T, 2>(a, x + v0, y + v0, k, s))); v0 += 2; }
-        else { MO_TRY((spmm_panel<T, 1>(a, x + v0, y + v0, k, s))); v0 += 1; }
+        if (left >= 8) { MO_TRY((rest_panel<T, 8>(a, x + v0, y + v0, k, dia, s))); v0 += 8; }
+        else if (left >= 4) { MO_TRY((rest_panel<T, 4>(a, x + v0, y + v0, k, dia, s))); v0 += 4; }
+        else if (left >= 2) { MO_TRY((rest_panel<T, 2>(a, x + v0, y + v0, k, dia, s))); v0 += 2; }
+        else { MO_TRY((rest_panel<T, 1>(a, x + v0, y + v0, k, dia, s))); v0 += 1; }
     }
     return MO_OK;
 }
