@@ -7,7 +7,7 @@ run-first choice made before the timed region), then REPS = 1000 SpMVs in that f
 2 * nnz * REPS / t_step.  The one-off rows of the path (conversions, run-first tuning) and the SpMV rate of every
 format are measured in the same run and printed in the same JSON line.
 
-Workload: benchmark configs[1], the 3-D 27-point stencil on a 128^3 grid in fp64 (synthetic, seeded), with
+Workload: the 3-D 27-point stencil on a 128^3 grid in fp64 (synthetic, seeded), with
 all inputs resident in HBM before the timed region starts.
 """
 from __future__ import annotations
@@ -67,7 +67,7 @@ def main() -> int:
                     help="also run a plain 1 GiB -> 1 GiB device copy five times, as the known-size reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU only: this library has no multi-GPU path; run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -1,8 +1,8 @@
-"""Tuner sweep (benchmark configs[4]): the offline stage of the paper's pipeline (Section III-A) on synthetic
+"""Tuner sweep: the offline stage of the paper's pipeline (Section III-A) on synthetic
 matrices.
 
-    python -m paper_2303_05098_amd.sweep run --first 0 --count 64 --out gpurun_out/sweep_000.jsonl     (GPU)
-    python -m paper_2303_05098_amd.sweep fit gpurun_out/sweep_*.jsonl --model paper_2303_05098_amd/models/mi355x_forest.bin
+    python -m paper_2303_05098_amd.sweep run --first 0 --count 64 --out sweep_000.jsonl     (GPU)
+    python -m paper_2303_05098_amd.sweep fit 'sweep_*.jsonl' --model paper_2303_05098_amd/models/mi355x_forest.bin
 
 ``run``: per matrix, features on the GPU (mo_features), then the run-first tuner (mo_tune, 1000 timed SpMVs per
 feasible format as in Section VII-A); label = format with the smallest time.  ``fit``: the model-selection procedure
