@@ -140,8 +140,28 @@ __global__ __launch_bounds__(MB) void k_spmm_rows(const int32_t *__restrict__ rp
             stage_to_lds(col + start, s_col, total, lane);
             stage_to_lds(val + start, s_val, total, lane);
         }
-        if (!is_long && lane >= first && lane <= last && hi <= end)
-            for (int p = lo - start; p < hi - start; ++p) fma_row<T, K>(acc, s_val[p], x + (int64_t)s_col[p] * ldk);
+        if (!is_long && lane >= first && lane <= last && hi <= end) {
+            constexpr int ROWS_U = K >= 8 ? 4 : 8;   // entries fetched together; fewer for wide panels (registers)
+            int p = lo - start;
+            const int pe = hi - start;
+            for (; p + ROWS_U <= pe; p += ROWS_U) {   // ROWS_U entries at a time: their LDS reads and their gathers of X overlap
+                int32_t cj[ROWS_U];
+                T aj[ROWS_U];
+#pragma unroll
+                for (int u = 0; u < ROWS_U; ++u) { cj[u] = s_col[p + u]; aj[u] = s_val[p + u]; }
+                if constexpr (K == 1) {
+                    T xj[ROWS_U];
+#pragma unroll
+                    for (int u = 0; u < ROWS_U; ++u) xj[u] = x[(int64_t)cj[u] * ldk];
+#pragma unroll
+                    for (int u = 0; u < ROWS_U; ++u) acc[0] += aj[u] * xj[u];
+                } else {
+#pragma unroll
+                    for (int u = 0; u < ROWS_U; ++u) fma_row<T, K>(acc, aj[u], x + (int64_t)cj[u] * ldk);
+                }
+            }
+            for (; p < pe; ++p) fma_row<T, K>(acc, s_val[p], x + (int64_t)s_col[p] * ldk);
+        }
         first = last + 1;
     }
     // Long rows: the 64 lanes share the row's entries (coalesced loads straight from memory), the K partial sums of
