@@ -137,6 +137,7 @@ mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
     case MO_DIA: return spmv_dia(*a, x, y, s);
     case MO_ELL: return spmv_ell(*a, x, y, s);
     case MO_HYB:
+        if (a->nnz_coo > 0 && a->hyb_max_surplus <= HYB_FUSED_MAX_SURPLUS && a->coo_rp) return spmv_hyb_fused(*a, x, y, s);
         MO_TRY(spmv_ell(*a, x, y, s));
         return a->nnz_coo > 0 ? spmv_coo(*a, x, y, true, s) : MO_OK;
     case MO_HDC:

@@ -569,6 +569,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
             int64_t surplus = 0;
             for (int64_t len = K + 1; len <= an.max_row; ++len) surplus += (int64_t)hh[(size_t)len] * (len - K);
             h->nnz_coo = surplus;
+            h->hyb_max_surplus = an.max_row > K ? an.max_row - K : 0;
             const size_t e = (size_t)(surplus > 0 ? surplus : 1);
             h->coo_row = (int32_t *)b.own(e * 4);
             h->coo_col = (int32_t *)b.own(e * 4);

@@ -95,6 +95,7 @@ struct mo_matrix {
     int32_t *csr_tile_rp = nullptr;   // (first row, its row_ptr) per tile, tiles + 1 pairs
     const int32_t *coo_rp = nullptr;  // m + 1 positions: where each row's run starts in the sorted COO part (launch data
                                       // of the multi-vector product; not part of the format)
+    int64_t hyb_max_surplus = 0;      // HYB: longest row minus the ELL width (entries of one row in the COO part)
     int64_t coo_tiles = 0;
     int32_t coo_strip = 4;            // entries per thread of the COO kernel (4 or 2)
     int32_t *coo_carry_row = nullptr; // one per COO tile
@@ -138,6 +139,8 @@ mo_status spmv_csr(const mo_matrix &a, const void *x, void *y, bool accumulate, 
 mo_status spmv_coo(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s);
 mo_status spmv_dia(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 mo_status spmv_ell(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+mo_status spmv_hyb_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+constexpr int64_t HYB_FUSED_MAX_SURPLUS = 16;   // longer COO runs per row go through the COO kernel
 mo_status spmv_hdc_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_elems, std::vector<int32_t> *xpos,
                        std::vector<int32_t> *clusters, int64_t *total_elems);

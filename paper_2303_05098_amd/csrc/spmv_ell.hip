@@ -77,6 +77,33 @@ __global__ __launch_bounds__(ELL_B) void k_ell_split(const int32_t *__restrict__
     }
 }
 
+// HYB whose rows keep only a few entries in the COO part: the row's lane adds its own COO run (found through the
+// positions of the row runs that the handle keeps) right after its ELL slots, so y is written once by one kernel
+// instead of being written by the ELL kernel and read, updated and written again by the COO kernel.
+template <typename T>
+__global__ __launch_bounds__(ELL_B) void k_ell_hyb(const int32_t *__restrict__ col, const T *__restrict__ val, int64_t m, int64_t K,
+                                                    int64_t ld, const int32_t *__restrict__ coo_rp, const int32_t *__restrict__ ccol,
+                                                    const T *__restrict__ cval, const T *__restrict__ x, T *__restrict__ y)
+{
+    const int64_t lb = xcd_block(blockIdx.x, gridDim.x);
+    const int64_t row = lb * ELL_B + threadIdx.x;
+    if (row >= m) return;
+    const int32_t p0 = coo_rp[row], p1 = coo_rp[row + 1];
+    T sum = ell_row_sum<T>(col + row, val + row, ld, 0, K, 1, x);
+    for (int32_t p = p0; p < p1; ++p) sum += cval[p] * x[ccol[p]];
+    st_stream(y + row, sum);
+}
+
+template <typename T>
+static mo_status hyb_fused_typed(const mo_matrix &a, const void *x, void *y, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((a.m + ELL_B - 1) / ELL_B);
+    hipLaunchKernelGGL(k_ell_hyb<T>, dim3(grid), dim3(ELL_B), 0, s, a.ell_col, (const T *)a.ell_val, a.m, a.k, a.ld, a.coo_rp, a.coo_col,
+                       (const T *)a.coo_val, (const T *)x, (T *)y);
+    MO_LAUNCH_CHECK();
+    return MO_OK;
+}
+
 template <typename T>
 static mo_status ell_typed(const mo_matrix &a, const void *x, void *y, hipStream_t s)
 {
@@ -90,6 +117,11 @@ static mo_status ell_typed(const mo_matrix &a, const void *x, void *y, hipStream
     hipLaunchKernelGGL(k_ell<T>, dim3(grid), dim3(ELL_B), 0, s, a.ell_col, (const T *)a.ell_val, a.m, a.k, a.ld, (const T *)x, (T *)y);
     MO_LAUNCH_CHECK();
     return MO_OK;
+}
+
+mo_status spmv_hyb_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s)
+{
+    return a.dtype == MO_F32 ? hyb_fused_typed<float>(a, x, y, s) : hyb_fused_typed<double>(a, x, y, s);
 }
 
 mo_status spmv_ell(const mo_matrix &a, const void *x, void *y, hipStream_t s)
