@@ -88,9 +88,12 @@ __global__ __launch_bounds__(1024) void k_spmm_dia_lds(const int32_t *__restrict
     store_row<T, K, false>(y + i * ldk, acc);
 }
 
+// coo_rp != nullptr: a HYB handle whose rows keep few entries in the COO part; the row's lane adds its own COO run.
 template <typename T, int K>
 __global__ __launch_bounds__(MB) void k_spmm_ell(const int32_t *__restrict__ col, const T *__restrict__ val, int64_t W, int64_t ld,
-                                                  int64_t m, int64_t ldk, const T *__restrict__ x, T *__restrict__ y)
+                                                  int64_t m, int64_t ldk, const int32_t *__restrict__ coo_rp,
+                                                  const int32_t *__restrict__ ccol, const T *__restrict__ cval,
+                                                  const T *__restrict__ x, T *__restrict__ y)
 {
     const int64_t i = xcd_block(blockIdx.x, gridDim.x) * MB + threadIdx.x;
     if (i >= m) return;
@@ -100,6 +103,10 @@ __global__ __launch_bounds__(MB) void k_spmm_ell(const int32_t *__restrict__ col
     for (int64_t s = 0; s < W; ++s) {
         const int32_t j = ld_stream(col + s * ld + i);
         if (j >= 0) fma_row<T, K>(acc, ld_stream(val + s * ld + i), x + (int64_t)j * ldk);
+    }
+    if (coo_rp) {
+        const int32_t p1 = coo_rp[i + 1];
+        for (int32_t p = coo_rp[i]; p < p1; ++p) fma_row<T, K>(acc, cval[p], x + (int64_t)ccol[p] * ldk);
     }
     store_row<T, K, false>(y + i * ldk, acc);
 }
@@ -217,13 +224,17 @@ static mo_status rest_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, b
         return MO_OK;
     case MO_ELL:
     case MO_HYB:
-        hipLaunchKernelGGL((k_spmm_ell<T, K>), dim3(grid), dim3(MB), 0, s, a.ell_col, (const T *)a.ell_val, a.k, a.ld, a.m, ldk, x, y);
+    {
+        const bool fused = a.fmt == MO_HYB && a.nnz_coo > 0 && a.hyb_max_surplus <= HYB_FUSED_MAX_SURPLUS && a.coo_rp;
+        hipLaunchKernelGGL((k_spmm_ell<T, K>), dim3(grid), dim3(MB), 0, s, a.ell_col, (const T *)a.ell_val, a.k, a.ld, a.m, ldk,
+                           fused ? a.coo_rp : (const int32_t *)nullptr, a.coo_col, (const T *)a.coo_val, x, y);
         MO_LAUNCH_CHECK();
-        if (a.fmt == MO_HYB && a.nnz_coo > 0) {
+        if (a.fmt == MO_HYB && a.nnz_coo > 0 && !fused) {
             hipLaunchKernelGGL((k_spmm_rows<T, K, true>), dim3(grid), dim3(MB), 0, s, a.coo_rp, a.coo_col, (const T *)a.coo_val, a.m, ldk, x, y);
             MO_LAUNCH_CHECK();
         }
         return MO_OK;
+    }
     case MO_COO:
         hipLaunchKernelGGL((k_spmm_rows<T, K, false>), dim3(grid), dim3(MB), 0, s, a.coo_rp, a.coo_col, (const T *)a.coo_val, a.m, ldk, x, y);
         MO_LAUNCH_CHECK();
