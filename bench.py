@@ -30,11 +30,13 @@ MEASURED_TRAFFIC = {
     (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 732.2e6, (2, "f64", "ELL"): 710.2e6,
     (2, "f64", "COO"): 959.4e6 + 16.8e6 + 9.1e6,
     # profiles/spmv_all_formats_banded_scatter_f64.md: the 1.17 M scattered entries gather one 128-byte line of x each
-    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 700.9e6, (4, "f64", "ELL"): 683.7e6, (4, "f64", "COO"): 835.6e6 + 33.6e6 + 3.0e6,
+    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 700.8e6, (4, "f64", "ELL"): 784.5e6, (4, "f64", "HYB"): 684.9e6,
+    (4, "f64", "COO"): 835.6e6 + 33.6e6 + 5.9e6,
     # profiles/spmv_all_formats_lognormal_f64.md: 16.8 M random gathers of x miss L2; bytes counted at the L2 boundary
-    (3, "f64", "CSR"): 1334.0e6, (3, "f64", "HYB"): 642.2e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
+    (3, "f64", "CSR"): 1333.9e6, (3, "f64", "HYB"): 659.5e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
 }
 REPS = 1000
+LLC_BYTES = 256 << 20     # last-level (Infinity) cache of the MI355X
 MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_forest.bin")
 
 
@@ -63,6 +65,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="2 = 27-point stencil 128^3 (default), 4 = banded+scatter, 3 = lognormal")
     ap.add_argument("--dtype", default="f64", choices=["f64", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copies", type=int, default=0,
+                    help="device copies of each format the SpMV launches rotate over; 0 = as many as it takes for their "
+                         "bytes to exceed twice the 256 MB last-level cache (at most 4), so that the streams come from HBM")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB device copy five times, as the known-size reference for HBM byte counters")
     args = ap.parse_args()
@@ -135,22 +140,26 @@ def main() -> int:
         out_bytes = 0 if fmt == 1 else algorithmic_bytes(fmt, h.view(), sv) - (n + m) * sv
         convert_ms[mo.FORMAT_NAMES[fmt]] = {"first_call": round(t_cold, 3), "warm": round(t_warm, 3),
                                             "gbs": round((csr_bytes + out_bytes) / t_warm / 1e6, 1)}
-        handles[fmt] = h
-        for _ in range(10):
-            mo.mo_spmv(h, x, y)
+        # A format whose arrays fit the last-level cache is timed over several copies in rotation (own device arrays
+        # each, same contents), so that its value / index streams are read from HBM as they are at the other sizes.
+        b = algorithmic_bytes(fmt, h.view(), sv)
+        ncopies = args.copies if args.copies > 0 else (1 if b >= 1.25 * LLC_BYTES else min(4, math.ceil(2 * LLC_BYTES / b)))
+        hs = [h] + [mo.mo_convert(a, fmt) for _ in range(ncopies - 1)]
+        handles[fmt] = hs
+        for i in range(10):
+            mo.mo_spmv(hs[i % ncopies], x, y)
         best = math.inf
         for _ in range(5):
             e0, e1 = ev(), ev()
             e0.record(stream)
-            for _ in range(200):
-                mo.mo_spmv(h, x, y)
+            for i in range(200):
+                mo.mo_spmv(hs[i % ncopies], x, y)
             e1.record(stream)
             e1.synchronize()
             best = min(best, e0.elapsed_time(e1) / 200.0)
-        b = algorithmic_bytes(fmt, h.view(), sv)
         per_format[mo.FORMAT_NAMES[fmt]] = {"us": round(best * 1e3, 2), "gflops": round(2.0 * nnz / best / 1e6, 1),
                                             "gbs": round(b / best / 1e6, 1), "frac_hbm": round(b / best / 1e6 / HBM_PEAK_GBS, 4),
-                                            "alg_mbytes": round(b / 1e6, 1)}
+                                            "alg_mbytes": round(b / 1e6, 1), "copies_in_rotation": ncopies}
 
     # ---- format choice ----------------------------------------------------------------------------------------------
     ms_vec = [per_format[nm]["us"] / 1e3 if per_format[nm] else float("nan") for nm in mo.FORMAT_NAMES]
@@ -165,17 +174,18 @@ def main() -> int:
         chosen = predicted if predicted in handles else run_first
     else:
         predicted, t_pred_us, tuner, chosen = None, None, "run_first", run_first
-    h = handles[chosen]
+    hs = handles[chosen]
+    h = hs[0]
 
     # ---- timed region: K steps of (features + select + REPS SpMVs in the chosen format) --------------------------
     def step(timed_events=None):
         f, _ = mo.mo_features(a)
         fmt = mo.mo_select(model, f) if model is not None else chosen
-        hh = handles.get(fmt, h)
+        hh = handles.get(fmt, hs)
         if timed_events is not None:
             timed_events[0].record(stream)
-        for _ in range(REPS):
-            mo.mo_spmv(hh, x, y)
+        for i in range(REPS):
+            mo.mo_spmv(hh[i % len(hh)], x, y)
         if timed_events is not None:
             timed_events[1].record(stream)
 
@@ -209,7 +219,8 @@ def main() -> int:
                                               dtype=np_dtype)).cuda()
     yk = torch.empty((m, SPMM_K), dtype=xk.dtype, device="cuda")
     spmm = {}
-    for fmt, hh in handles.items():
+    for fmt, hl in handles.items():
+        hh = hl[0]
         for _ in range(3):
             mo.mo_spmm(hh, xk, yk)
         tb = math.inf
@@ -258,7 +269,8 @@ def main() -> int:
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"{names[args.config]}, {args.dtype}, m={m}, nnz={nnz}", "spmv_reps_per_step": REPS, "tuner": tuner},
+        "config": {"workload": f"{names[args.config]}, {args.dtype}, m={m}, nnz={nnz}", "spmv_reps_per_step": REPS, "tuner": tuner,
+                   "matrix_copies_in_rotation": len(hs)},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "per_format": per_format,
