@@ -258,9 +258,15 @@ def main() -> int:
         mo.mo_spmv(h, x, y)
         torch.cuda.synchronize()
         err, zeros_ok = ref.spmv_error(y.cpu().numpy(), y1, mag)
+        cpu_model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as fh:
+                cpu_model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), cpu_model)
+        except OSError:
+            pass
         cpu = {"value": round(2.0 * nnz / (t_mt / reps_mt) / 1e9, 3), "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
                "sample": f"{reps_mt} full SpMVs of the workload matrix, long-double COO-triplet loop split over {cores} threads by row range",
-               "single_thread_gflops": round(2.0 * nnz / t_1 / 1e9, 3), "gpu_vs_oracle_max_rel_err": err, "zeros_ok": zeros_ok}
+               "single_thread_gflops": round(2.0 * nnz / t_1 / 1e9, 3), "cpu_model": cpu_model, "gpu_vs_oracle_max_rel_err": err, "zeros_ok": zeros_ok}
 
     csr_us = per_format["CSR"]["us"]
     best_us = per_format[mo.FORMAT_NAMES[chosen]]["us"]
