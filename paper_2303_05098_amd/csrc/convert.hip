@@ -45,6 +45,7 @@ __device__ __forceinline__ void walk_rows(bool rv, int64_t row, int64_t lo, int6
 // and step; this way every line is read once.  Rows longer than SHORT_ROW are left to the cooperative loop, which
 // reads global memory with consecutive lanes anyway.  No block barrier: a wave's LDS accesses execute in order.
 constexpr int WCAP = 1024;
+constexpr int WALK_U = 4;
 
 template <typename T, class F>
 __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo64, int64_t hi64, const int32_t *__restrict__ col_idx,
@@ -61,13 +62,25 @@ __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo64
     const int we = nvalid ? __builtin_amdgcn_readlane(hi, nvalid - 1) : 0;
     for (int c0 = wb; c0 < we; c0 += WCAP) {
         const int c1 = we - c0 > WCAP ? c0 + WCAP : we;
-        stage_to_lds(col_idx + c0, s_col, c1 - c0, lane);
-        stage_to_lds(val + c0, s_val, c1 - c0, lane);
+        stage_pair_to_lds(col_idx + c0, val + c0, s_col, s_val, c1 - c0, lane);
         const int a = lo > c0 ? lo : c0, b = hi < c1 ? hi : c1;
         const int cnt = (is_short && b > a) ? b - a : 0;
         const int off = cnt ? a - c0 : 0;
-        for (int k = 0; ballot64(k < cnt) != 0ull; ++k)
-            if (k < cnt) f(row, (int64_t)a + k, (int64_t)(a + k - lo), s_col[off + k], s_val[off + k], true);
+        // WALK_U entries per lane and step: their LDS reads are issued together (clamped inside the lane's run, so
+        // unconditional), then handed to f one by one
+        for (int k = 0; ballot64(k < cnt) != 0ull; k += WALK_U) {
+            int32_t cc[WALK_U];
+            T vv[WALK_U];
+#pragma unroll
+            for (int u = 0; u < WALK_U; ++u) {
+                const int kk = k + u < cnt ? k + u : (cnt > 0 ? cnt - 1 : 0);
+                cc[u] = s_col[off + kk];
+                vv[u] = s_val[off + kk];
+            }
+#pragma unroll
+            for (int u = 0; u < WALK_U; ++u)
+                if (k + u < cnt) f(row, (int64_t)a + k + u, (int64_t)(a + k + u - lo), cc[u], vv[u], true);
+        }
     }
     uint64_t longmask = ballot64(rv && len > SHORT_ROW);
     while (longmask) {
@@ -84,14 +97,6 @@ __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) p[i] = v;
-}
-
-template <typename T>
-__global__ void k_fill_val(T *p, int64_t n)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) p[i] = (T)0;
 }
 
 // ------------------------------------------------------------------ COO
@@ -170,33 +175,90 @@ __global__ __launch_bounds__(CB) void k_offsets_and_slots(const int32_t *__restr
     else pos[i] = -1;
 }
 
+// DIA part of DIA / HDC.  A wave owns rw consecutive rows and stages their run of entries in LDS once.  Columns ascend
+// inside a row (CSR precondition) and so do the kept offsets, so a row is merged against the offset list: the loop
+// runs over the kept diagonals, the same for every lane, and each lane either consumes its next entry (when that
+// entry lies on the diagonal) or contributes a zero.  Every slot of the slab is therefore written exactly once, by
+// stores that cover rw consecutive rows of one diagonal; no zero-fill pass and no per-entry slot lookup are needed.
+// Entries that fall between kept diagonals (HDC) are skipped and counted into rest_cnt[row].
+// Rows that do not fit the staged window are merged straight from global memory; rows longer than SHORT_ROW are
+// handled by the whole wave through the slot map (zero the row's slots, wait for those stores, then scatter).
+template <typename T, class ColAt, class ValAt>
+__device__ __forceinline__ int dia_merge_row(bool act, bool store, int cnt, int64_t row, const int32_t *__restrict__ dia_off, int nd,
+                                             int64_t ld, T *__restrict__ dval, ColAt col_at, ValAt val_at)
+{
+    constexpr int32_t NONE = 0x7fffffff;        // no entry left: larger than any offset (m + n <= 2^31 - 1)
+    int e = 0, matched = 0;
+    int32_t cur = (act && cnt > 0) ? (int32_t)((int64_t)col_at(0) - row) : NONE;
+    for (int d = 0; d < nd; ++d) {
+        const int32_t target = dia_off[d];
+        while (cur < target) {                   // entries on diagonals that are not kept
+            ++e;
+            cur = e < cnt ? (int32_t)((int64_t)col_at(e) - row) : NONE;
+        }
+        T out = (T)0;
+        if (cur == target) {
+            out = val_at(e);
+            ++e;
+            ++matched;
+            cur = e < cnt ? (int32_t)((int64_t)col_at(e) - row) : NONE;
+        }
+        if (store) dval[(int64_t)d * ld + row] = out;
+    }
+    return matched;
+}
+
 template <typename T>
 __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
-                                                  int64_t ld, T *__restrict__ dval, int32_t *__restrict__ rest_cnt)
+                                                  const int32_t *__restrict__ dia_off, int nd, int64_t ld, T *__restrict__ dval,
+                                                  int32_t *__restrict__ rest_cnt, int rw)
 {
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
     __shared__ T s_val[(CB / WAVE) * WCAP];
-    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
-    const bool rv = row < m;
-    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
-    const int w = threadIdx.x / WAVE;
-    // HDC: the entries that are on no kept diagonal are counted per row on the way (rest_cnt starts at zero): a row
-    // walked by its own lane adds its count once at the end, a long row walked by the whole wave adds per 64 entries.
-    int32_t mine = 0;
-    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP,
-                     [&](int64_t r, int64_t, int64_t, int32_t c, T v, bool own) {
-        const int k = slot[(int64_t)c - r + (m - 1)];
-        if (k >= 0) dval[(int64_t)k * ld + r] = v;
-        if (rest_cnt) {
-            if (own) mine += k < 0;
-            else {   // all active lanes are on the same long row r: one atomic for the 64 entries
-                const uint64_t rest = ballot64(k < 0);
-                if (rest && lane_id() == __ffsll((unsigned long long)rest) - 1) atomicAdd(&rest_cnt[r], (int32_t)__popcll(rest));
+    const int lane = lane_id();
+    int32_t *sc = s_col + (threadIdx.x / WAVE) * WCAP;
+    T *sv = s_val + (threadIdx.x / WAVE) * WCAP;
+    const int64_t row = (xcd_block(blockIdx.x, gridDim.x) * (CB / WAVE) + threadIdx.x / WAVE) * rw + lane;
+    const bool rv = lane < rw && row < m;
+    const bool pad = lane < rw && row >= m && row < ld;      // rows of the slab beyond the matrix hold zeros
+    const int lo = row_ptr[row < m ? row : m], hi = row_ptr[row + 1 < m ? row + 1 : m];   // empty run past the last row
+    const int len = hi - lo;
+    const int nvalid = __popcll(ballot64(rv));   // the valid rows of a wave are a prefix of its lanes
+    const int wb = __builtin_amdgcn_readfirstlane(lo);
+    const int we = nvalid ? __builtin_amdgcn_readlane(hi, nvalid - 1) : wb;
+    const int staged = we - wb < WCAP ? we - wb : WCAP;
+    if (staged > 0) stage_pair_to_lds(col_idx + wb, val + wb, sc, sv, staged, lane);
+    const bool is_short = rv && len <= SHORT_ROW;
+    const bool in_lds = is_short && hi - wb <= staged;
+    const int off = in_lds ? lo - wb : 0;
+    int matched = dia_merge_row<T>(in_lds, in_lds || pad, in_lds ? len : 0, row, dia_off, nd, ld, dval,
+                                   [&](int e) { return sc[off + e]; }, [&](int e) { return sv[off + e]; });
+    const bool direct = is_short && !in_lds;
+    if (ballot64(direct) != 0ull)
+        matched += dia_merge_row<T>(direct, direct, direct ? len : 0, row, dia_off, nd, ld, dval,
+                                    [&](int e) { return col_idx[lo + e]; }, [&](int e) { return val[lo + e]; });
+    if (rest_cnt && is_short) rest_cnt[row] = len - matched;
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+    while (longmask) {
+        const int l = __ffsll((unsigned long long)longmask) - 1;
+        longmask &= longmask - 1;
+        const int64_t r = row - lane + l;
+        const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
+        for (int d = lane; d < nd; d += WAVE) dval[(int64_t)d * ld + r] = (T)0;
+        __threadfence();                         // the zeros are in place before other lanes store values of this row
+        int rest = 0;
+        for (int q0 = rlo; q0 < rhi; q0 += WAVE) {
+            const int q = q0 + lane;
+            int k = 0;
+            if (q < rhi) {
+                k = slot[(int64_t)col_idx[q] - r + (m - 1)];
+                if (k >= 0) dval[(int64_t)k * ld + r] = val[q];
             }
+            rest += (int)__popcll(ballot64(k < 0));
         }
-    });
-    if (rest_cnt && mine) atomicAdd(&rest_cnt[row], mine);
+        if (rest_cnt && lane == 0) rest_cnt[r] = rest;
+    }
 }
 
 // ------------------------------------------------------------------ ELL (and the ELL part of HYB)
@@ -207,12 +269,12 @@ __global__ __launch_bounds__(CB) void k_fill_ell(const int32_t *__restrict__ row
                                                   const T *__restrict__ val, int64_t m, int64_t K, int64_t ld,
                                                   int32_t *__restrict__ ecol, T *__restrict__ eval,
                                                   const int32_t *__restrict__ coo_ptr, int32_t *__restrict__ crow,
-                                                  int32_t *__restrict__ ccol, T *__restrict__ cval)
+                                                  int32_t *__restrict__ ccol, T *__restrict__ cval, int rw)
 {
-    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
-    const bool rv = row < m;
-    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
-    if (row < ld) {
+    const int64_t row = (xcd_block(blockIdx.x, gridDim.x) * (CB / WAVE) + threadIdx.x / WAVE) * rw + lane_id();
+    const bool rv = lane_id() < rw && row < m;
+    const int64_t lo = row_ptr[row < m ? row : m], hi = row_ptr[row + 1 < m ? row + 1 : m];   // empty run past the last row
+    if (lane_id() < rw && row < ld) {
         for (int64_t s = (hi - lo); s < K; ++s) {
             ecol[s * ld + row] = -1;
             eval[s * ld + row] = (T)0;
@@ -280,43 +342,85 @@ __global__ __launch_bounds__(CB) void k_surplus(const int32_t *__restrict__ row_
 
 // ------------------------------------------------------------------ HDC remainder
 // The entries of a row that are on no kept diagonal are written, in row order, to the CSR part starting at
-// rest_ptr[row] (their number per row was counted while the DIA part was filled).  Short rows are walked by their
-// own lane out of the wave's LDS stage; a long row is compacted by the whole wave, 64 entries at a time, with a
-// ballot prefix so that the order inside the row is kept.
+// rest_ptr[row] (their number per row was counted while the DIA part was filled).  Same staging and the same merge
+// against the ascending offset list as the DIA fill, except that here the entries the merge steps over are the
+// output; rows without remainder take no part.  A long row is compacted by the whole wave, 64 entries at a time,
+// with a ballot prefix so that the order inside the row is kept.
+template <typename T, class ColAt, class ValAt>
+__device__ __forceinline__ void hdc_rest_row(bool act, int cnt, int need, int64_t row, int64_t base, const int32_t *__restrict__ dia_off,
+                                             int nd, int32_t *__restrict__ rcol, T *__restrict__ rval, ColAt col_at, ValAt val_at)
+{
+    constexpr int32_t NONE = 0x7fffffff;
+    int e = 0, done = 0;
+    if (!act) need = 0;
+    int32_t c = (need > 0 && cnt > 0) ? col_at(0) : 0;
+    int32_t cur = (need > 0 && cnt > 0) ? (int32_t)((int64_t)c - row) : NONE;
+    for (int d = 0; d < nd; ++d) {
+        if (ballot64(done < need) == 0ull) return;            // every row of the wave has its remainder
+        const int32_t target = dia_off[d];
+        while (done < need && cur <= target) {
+            if (cur < target) {
+                rcol[base + done] = c;
+                rval[base + done] = val_at(e);
+                ++done;
+            }
+            ++e;
+            c = e < cnt ? col_at(e) : 0;
+            cur = e < cnt ? (int32_t)((int64_t)c - row) : NONE;
+        }
+    }
+    while (done < need) {                                     // entries beyond the last kept diagonal
+        rcol[base + done] = c;
+        rval[base + done] = val_at(e);
+        ++done;
+        ++e;
+        c = e < cnt ? col_at(e) : 0;
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
-                                                  const int32_t *__restrict__ rest_ptr, int32_t *__restrict__ rcol, T *__restrict__ rval)
+                                                  const int32_t *__restrict__ dia_off, int nd, const int32_t *__restrict__ rest_ptr,
+                                                  int32_t *__restrict__ rcol, T *__restrict__ rval, int rw)
 {
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
     __shared__ T s_val[(CB / WAVE) * WCAP];
-    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
-    const bool rv = row < m;
-    const int64_t lo = rv ? row_ptr[row] : 0, hi = rv ? row_ptr[row + 1] : 0;
-    const int64_t len = hi - lo;
-    const int64_t base = rv ? rest_ptr[row] : 0;
-    const int w = threadIdx.x / WAVE;
-    int64_t mine = 0;
-    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP,
-                     [&](int64_t r, int64_t, int64_t, int32_t c, T v, bool own) {
-        if (own && slot[(int64_t)c - r + (m - 1)] < 0) {
-            rcol[base + mine] = c;
-            rval[base + mine] = v;
-            ++mine;
-        }
-    });
-    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
     const int lane = lane_id();
+    int32_t *sc = s_col + (threadIdx.x / WAVE) * WCAP;
+    T *sv = s_val + (threadIdx.x / WAVE) * WCAP;
+    const int64_t row = (xcd_block(blockIdx.x, gridDim.x) * (CB / WAVE) + threadIdx.x / WAVE) * rw + lane;
+    const bool rv = lane < rw && row < m;
+    const int lo = row_ptr[row < m ? row : m], hi = row_ptr[row + 1 < m ? row + 1 : m];   // empty run past the last row
+    const int len = hi - lo;
+    const int64_t base = rest_ptr[row < m ? row : m];
+    const int need = rv ? rest_ptr[row + 1 < m ? row + 1 : m] - (int32_t)base : 0;
+    if (ballot64(need > 0) == 0ull) return;                   // no remainder in these rows
+    const int nvalid = __popcll(ballot64(rv));                // the valid rows of a wave are a prefix of its lanes
+    const int wb = __builtin_amdgcn_readfirstlane(lo);
+    const int we = nvalid ? __builtin_amdgcn_readlane(hi, nvalid - 1) : wb;
+    const int staged = we - wb < WCAP ? we - wb : WCAP;
+    if (staged > 0) stage_pair_to_lds(col_idx + wb, val + wb, sc, sv, staged, lane);
+    const bool is_short = rv && len <= SHORT_ROW;
+    const bool in_lds = is_short && hi - wb <= staged;
+    const int off = in_lds ? lo - wb : 0;
+    hdc_rest_row<T>(in_lds, len, need, row, base, dia_off, nd, rcol, rval,
+                    [&](int e) { return sc[off + e]; }, [&](int e) { return sv[off + e]; });
+    const bool direct = is_short && !in_lds;
+    if (ballot64(direct && need > 0) != 0ull)
+        hdc_rest_row<T>(direct, len, need, row, base, dia_off, nd, rcol, rval,
+                        [&](int e) { return col_idx[lo + e]; }, [&](int e) { return val[lo + e]; });
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW && need > 0);
     const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (WAVE - lane));
     while (longmask) {
         const int l = __ffsll((unsigned long long)longmask) - 1;
         longmask &= longmask - 1;
-        const int64_t r = __shfl(row, l, WAVE);
-        const int64_t rlo = __shfl(lo, l, WAVE), rhi = __shfl(hi, l, WAVE);
+        const int64_t r = row - lane + l;
+        const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
         const int64_t rbase = __shfl(base, l, WAVE);
         int64_t run = 0;
-        for (int64_t q0 = rlo; q0 < rhi; q0 += WAVE) {
-            const int64_t q = q0 + lane;
+        for (int q0 = rlo; q0 < rhi; q0 += WAVE) {
+            const int q = q0 + lane;
             bool rest = false;
             int32_t c = 0;
             if (q < rhi) {
@@ -336,6 +440,22 @@ __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row
 
 // ------------------------------------------------------------------ host side
 static unsigned blocks_for(int64_t n) { return (unsigned)((n + CB - 1) / CB > 0 ? (n + CB - 1) / CB : 1); }
+// Rows per wave of the fill kernels: as many (64, 32, 16 or 8) as keep the wave's run of entries within one LDS stage
+// at the mean row length.  A second stage in the same wave would have to wait until the stores of the first have
+// drained (loads and stores share one in-order counter), which cost a third of the bandwidth on the 27-point stencil.
+static int rows_per_wave(int64_t m, int64_t nnz)
+{
+    const double avg = m > 0 ? (double)nnz / (double)m : 0.0;
+    int rw = WAVE;
+    while (rw > 8 && avg * rw > 0.9 * WCAP) rw >>= 1;
+    return rw;
+}
+static unsigned wave_blocks_for(int64_t rows, int rw)
+{
+    const int64_t per_block = (int64_t)rw * (CB / WAVE);
+    const int64_t g = (rows + per_block - 1) / per_block;
+    return (unsigned)(g > 0 ? g : 1);
+}
 static unsigned fill_grid(int64_t n)
 {
     int64_t g = (n + (int64_t)CB * 8 - 1) / ((int64_t)CB * 8);
@@ -444,14 +564,9 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
     hipLaunchKernelGGL(k_offsets_and_slots, dim3(blocks_for(ndiag)), dim3(CB), 0, s, flag, pos, ndiag, a.m, h->dia_off);
     MO_LAUNCH_CHECK();
     if (nd > 0) {
-        hipLaunchKernelGGL(k_fill_val<T>, dim3(fill_grid(nd * h->ld)), dim3(CB), 0, s, (T *)h->dia_val, nd * h->ld);
-        MO_LAUNCH_CHECK();
-        if (rest_cnt) {
-            hipLaunchKernelGGL(k_fill_i32, dim3(fill_grid(a.m)), dim3(CB), 0, s, rest_cnt, a.m, 0);
-            MO_LAUNCH_CHECK();
-        }
-        hipLaunchKernelGGL(k_fill_dia<T>, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.col_idx, (const T *)a.val, a.m,
-                           pos, h->ld, (T *)h->dia_val, rest_cnt);
+        const int rw = rows_per_wave(a.m, a.nnz);
+        hipLaunchKernelGGL(k_fill_dia<T>, dim3(wave_blocks_for(h->ld, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, (const T *)a.val, a.m,
+                           pos, h->dia_off, (int)nd, h->ld, (T *)h->dia_val, rest_cnt, rw);
         MO_LAUNCH_CHECK();
     } else if (rest_cnt) {   // no diagonal is kept: every entry is remainder
         hipLaunchKernelGGL(k_surplus, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.m, (int64_t)0, rest_cnt);
@@ -589,8 +704,9 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         h->ell_col = (int32_t *)b.own(slots * 4);
         h->ell_val = b.own(slots * sizeof(T));
         if (b.failed) return MO_E_ALLOC;
-        hipLaunchKernelGGL(k_fill_ell<T>, dim3(blocks_for(h->ld)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, K, h->ld,
-                           h->ell_col, (T *)h->ell_val, coo_ptr, h->coo_row, h->coo_col, (T *)h->coo_val);
+        const int rw = rows_per_wave(a.m, a.nnz);
+        hipLaunchKernelGGL(k_fill_ell<T>, dim3(wave_blocks_for(h->ld, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, K, h->ld,
+                           h->ell_col, (T *)h->ell_val, coo_ptr, h->coo_row, h->coo_col, (T *)h->coo_val, rw);
         MO_LAUNCH_CHECK();
         break;
     }
@@ -610,8 +726,13 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         int32_t *rcol = (int32_t *)b.own(e * 4);
         T *rval = (T *)b.own(e * sizeof(T));
         if (b.failed) return MO_E_ALLOC;
-        if (total > 0) {
-            hipLaunchKernelGGL(k_hdc_rest<T>, dim3(row_blocks), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot, rest_ptr, rcol, rval);
+        if (total > 0 && h->nd == 0) {   // no diagonal is kept: the remainder is the matrix itself
+            MO_HIP(hipMemcpyAsync(rcol, a.col_idx, (size_t)total * 4, hipMemcpyDeviceToDevice, s));
+            MO_HIP(hipMemcpyAsync(rval, aval, (size_t)total * sizeof(T), hipMemcpyDeviceToDevice, s));
+        } else if (total > 0) {
+            const int rw = rows_per_wave(a.m, a.nnz);
+            hipLaunchKernelGGL(k_hdc_rest<T>, dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot,
+                               h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw);
             MO_LAUNCH_CHECK();
         }
         h->csr_row_ptr = rest_ptr; h->csr_col = rcol; h->csr_val = rval;

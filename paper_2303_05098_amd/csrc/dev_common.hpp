@@ -89,6 +89,34 @@ __device__ __forceinline__ void stage_to_lds(const T *__restrict__ g, T *s, int 
     }
 }
 
+// The same for two arrays that are indexed alike (column indices and values of one run of entries): the loads of
+// both arrays, PAIR_BATCH per lane and array, are in flight together, so a run of up to 64 * PAIR_BATCH entries costs
+// one memory latency instead of one per array and batch.
+constexpr int PAIR_BATCH = 16;
+template <typename A, typename B>
+__device__ __forceinline__ void stage_pair_to_lds(const A *__restrict__ ga, const B *__restrict__ gb, A *sa, B *sb, int count, int lane)
+{
+    for (int i0 = 0; i0 < count; i0 += WAVE * PAIR_BATCH) {
+        A ra[PAIR_BATCH];
+        B rb[PAIR_BATCH];
+#pragma unroll
+        for (int u = 0; u < PAIR_BATCH; ++u) {
+            const int i = i0 + u * WAVE + lane;
+            ra[u] = ld_stream(ga + (i < count ? i : count - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < PAIR_BATCH; ++u) {
+            const int i = i0 + u * WAVE + lane;
+            rb[u] = ld_stream(gb + (i < count ? i : count - 1));
+        }
+#pragma unroll
+        for (int u = 0; u < PAIR_BATCH; ++u) {
+            const int i = i0 + u * WAVE + lane;
+            if (i < count) { sa[i] = ra[u]; sb[i] = rb[u]; }
+        }
+    }
+}
+
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef int int2v __attribute__((ext_vector_type(2)));
 typedef double dbl2v __attribute__((ext_vector_type(2)));

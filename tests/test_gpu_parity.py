@@ -39,6 +39,19 @@ def small_cases():
     ci2 = np.concatenate([ci[:rp[1500]], np.arange(3000, dtype=np.int32), ci[rp[1501]:]])
     v2 = synth.uniform_pm1(13, 0, np.arange(ci2.shape[0]))
     out.append(("long_row", m, n, rp2.astype(np.int32), ci2.astype(np.int32), v2))
+    # a tridiagonal matrix with a 256-row stretch of 29 diagonals: the mean row is short, so a wave takes 64 rows, and in
+    # the stretch their entries exceed one LDS stage of the conversion kernels (rows past the staged window)
+    m = n = 4096
+    rows, cols = [], []
+    for i in range(m):
+        reach = 14 if 1024 <= i < 1280 else 1
+        js = np.arange(max(0, i - reach), min(n, i + reach + 1))
+        rows.append(np.full(js.size, i))
+        cols.append(js)
+    ti, tj = np.concatenate(rows), np.concatenate(cols)
+    rp3 = np.zeros(m + 1, np.int64)
+    np.cumsum(np.bincount(ti, minlength=m), out=rp3[1:])
+    out.append(("bulge", m, n, rp3.astype(np.int32), tj.astype(np.int32), synth.uniform_pm1(14, 0, np.arange(tj.size))))
     return out
 
 
