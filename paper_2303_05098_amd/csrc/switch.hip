@@ -199,22 +199,30 @@ __global__ __launch_bounds__(FB) void k_hist_parts(View<T> v, int64_t rows_per_b
 // (a lane writing its row directly would scatter 4- and 8-byte stores one row length apart).
 constexpr int FILL_CH = 2048;
 
-template <typename T>
+// MODE 0: any mix of parts, one entry at a time.  MODE 1: DIA part merged by column with the CSR part, if there is
+// one (DIA, HDC); MODE 2: ELL part followed by the COO part (ELL, HYB): the slab is read FILL_U slots at a time with
+// unconditional loads, so that a lane has FILL_U lines in flight instead of one per memory latency.  These two modes
+// walk the row from its start for every chunk and keep what falls into the chunk; rpb (rows per block) is chosen on
+// the host so that a block normally needs one chunk.
+constexpr int FILL_U = 8;
+
+template <typename T, int MODE>
 __global__ __launch_bounds__(FB) void k_fill_csr_any(View<T> v, const int32_t *__restrict__ out_ptr, int32_t *__restrict__ ocol,
-                                                      T *__restrict__ oval)
+                                                      T *__restrict__ oval, int rpb)
 {
     __shared__ int32_t s_col[FILL_CH];
     __shared__ T s_val[FILL_CH];
     __shared__ int64_t s_coo[2];
-    const int64_t row0 = (int64_t)blockIdx.x * FB;
+    const int64_t row0 = (int64_t)blockIdx.x * rpb;
     const int64_t row = row0 + threadIdx.x;
-    const bool rv = row < v.m;
-    const int64_t rend = row0 + FB < v.m ? row0 + FB : v.m;
+    const bool rv = (int)threadIdx.x < rpb && row < v.m;
+    const int64_t rend = row0 + rpb < v.m ? row0 + rpb : v.m;
     if (v.nnz_coo > 0 && threadIdx.x < 2) s_coo[threadIdx.x] = coo_lower_bound(v.coo_row, 0, v.nnz_coo, threadIdx.x == 0 ? row0 : rend);
     __syncthreads();
     const int64_t out_lo = out_ptr[row0], out_hi = out_ptr[rend];
-    int64_t pos = rv ? (int64_t)out_ptr[row] : out_hi;
+    const int64_t pos_begin = rv ? (int64_t)out_ptr[row] : out_hi;
     const int64_t pos_end = rv ? (int64_t)out_ptr[row + 1] : out_hi;
+    int64_t pos = pos_begin;
     // cursors into the four possible sources of this row
     int64_t kd = 0, sl = 0, q = 0, qe = 0;
     int p = 0, pe = 0;
@@ -245,15 +253,67 @@ __global__ __launch_bounds__(FB) void k_fill_csr_any(View<T> v, const int32_t *_
         if (q < qe) { col = v.coo_col[q]; val = v.coo_val[q]; ++q; return true; }
         return false;
     };
+    const int64_t rc = rv ? row : (v.m - 1);                  // a row every lane may load from
     for (int64_t c0 = out_lo; c0 < out_hi; c0 += FILL_CH) {   // uniform trip count across the block
         const int64_t c1 = c0 + FILL_CH < out_hi ? c0 + FILL_CH : out_hi;
-        while (pos < pos_end && pos < c1) {
-            int32_t col = 0;
-            T val = (T)0;
-            if (!next(col, val)) { pos = pos_end; break; }   // cannot happen: the lengths were counted from the same arrays
-            s_col[pos - c0] = col;
-            s_val[pos - c0] = val;
-            ++pos;
+        if constexpr (MODE == 0) {
+            while (pos < pos_end && pos < c1) {
+                int32_t col = 0;
+                T val = (T)0;
+                if (!next(col, val)) { pos = pos_end; break; }   // cannot happen: the lengths were counted from the same arrays
+                s_col[pos - c0] = col;
+                s_val[pos - c0] = val;
+                ++pos;
+            }
+        } else {
+            const bool touch = rv && pos_begin < c1 && pos_end > c0;
+            pos = pos_begin;
+            auto emit = [&](int32_t col, T val) {
+                if (pos >= c0 && pos < c1) { s_col[pos - c0] = col; s_val[pos - c0] = val; }
+                ++pos;
+            };
+            if constexpr (MODE == 1) {
+                // HDC: the row's CSR entries (ascending columns, as the diagonals are) are slipped in before the first
+                // DIA entry of a larger column
+                int pc = p;
+                int32_t cc = (touch && pc < pe) ? v.csr_col[pc] : 0x7fffffff;
+                for (int64_t k0 = 0; k0 < v.nd && ballot64(touch && pos < pos_end && pos < c1) != 0ull; k0 += FILL_U) {
+                    T a[FILL_U];
+#pragma unroll
+                    for (int u = 0; u < FILL_U; ++u) a[u] = v.dia_val[(k0 + u < v.nd ? k0 + u : v.nd - 1) * v.ld + rc];
+#pragma unroll
+                    for (int u = 0; u < FILL_U; ++u) {
+                        if (k0 + u >= v.nd) break;
+                        const int64_t j = row + v.dia_off[k0 + u];
+                        if (touch && j >= 0 && j < v.n && a[u] != (T)0) {
+                            while ((int64_t)cc < j) {
+                                emit(cc, v.csr_val[pc]);
+                                ++pc;
+                                cc = pc < pe ? v.csr_col[pc] : 0x7fffffff;
+                            }
+                            emit((int32_t)j, a[u]);
+                        }
+                    }
+                }
+                if (touch)
+                    for (; pc < pe; ++pc) emit(v.csr_col[pc], v.csr_val[pc]);
+            } else {
+                for (int64_t s0 = 0; s0 < v.k && ballot64(touch && pos < pos_end && pos < c1) != 0ull; s0 += FILL_U) {
+                    int32_t c[FILL_U];
+                    T a[FILL_U];
+#pragma unroll
+                    for (int u = 0; u < FILL_U; ++u) {
+                        const int64_t at = (s0 + u < v.k ? s0 + u : v.k - 1) * v.ld + rc;
+                        c[u] = v.ell_col[at];
+                        a[u] = v.ell_val[at];
+                    }
+#pragma unroll
+                    for (int u = 0; u < FILL_U; ++u)
+                        if (touch && s0 + u < v.k && c[u] >= 0) emit(c[u], a[u]);
+                }
+                if (touch)
+                    for (int64_t t = q; t < qe; ++t) emit(v.coo_col[t], v.coo_val[t]);
+            }
         }
         __syncthreads();
         for (int64_t i = c0 + threadIdx.x; i < c1; i += FB) {
@@ -304,7 +364,16 @@ static mo_status rebuild_csr(const mo_matrix &a, TempCsr &out, hipStream_t s)
             MO_HIP(hipMemcpyAsync(out.val, src_val, (size_t)total * sizeof(T), hipMemcpyDeviceToDevice, s));
         }
     } else {
-        hipLaunchKernelGGL(k_fill_csr_any<T>, dim3(rb), dim3(FB), 0, s, v, out.row_ptr, out.col, (T *)out.val);
+        // rows per block: as many as keep the block's output within one LDS chunk at the mean row length
+        int rpb = FB;
+        while (rpb > 32 && (double)total / (double)a.m * rpb > 0.9 * FILL_CH) rpb >>= 1;
+        const dim3 grid((unsigned)((a.m + rpb - 1) / rpb));
+        if (v.nd > 0 && v.k == 0 && v.nnz_coo == 0)
+            hipLaunchKernelGGL((k_fill_csr_any<T, 1>), grid, dim3(FB), 0, s, v, out.row_ptr, out.col, (T *)out.val, rpb);
+        else if (v.k > 0 && v.nd == 0 && !v.csr_row_ptr)
+            hipLaunchKernelGGL((k_fill_csr_any<T, 2>), grid, dim3(FB), 0, s, v, out.row_ptr, out.col, (T *)out.val, rpb);
+        else
+            hipLaunchKernelGGL((k_fill_csr_any<T, 0>), grid, dim3(FB), 0, s, v, out.row_ptr, out.col, (T *)out.val, rpb);
         MO_LAUNCH_CHECK();
     }
     MO_HIP(hipStreamSynchronize(s));   // scratch is released on return
