@@ -17,20 +17,22 @@ namespace mo {
 // Section VI-C): row lengths (max, min, sum of squares) from row_ptr and entries per diagonal from col_idx.
 //
 // Lane l of a wave owns row r0 + l and walks its entries (rows of at most SHORT_ROW entries; the columns reach the
-// lanes through LDS so that global loads stay coalesced), so for banded and stencil matrices all lanes meet the
-// same diagonal in the same step.  Counts are merged three times before they reach memory:
-//   1. registers: for step k of the walk, lanes k and k + 32 of two register pairs remember four diagonals and
-//      their running counts (a four-way cache per step, private to the wave).  A banded matrix meets the same few
-//      diagonals at the same step in every group of 64 rows, so the common case is four compares, ballots and
-//      popcounts, no memory at all;
-//   2. LDS: keys that miss the cache either replace its least used way (whose count moves to the block's hash
-//      table) or, when they were met once only or the rows share no diagonals at all, go to the table directly;
+// lanes through LDS so that global loads stay coalesced).  Counts are merged three times before they reach memory:
+//   1. registers: the wave keeps a list of candidate diagonals, ascending, one per lane, with a running count each
+//      (taken from the longest row it has staged: in a banded or stencil matrix every other row holds a subset of
+//      that row's diagonals).  Columns ascend inside a row, so every row is merged against the list: the loop runs
+//      over the candidates, the same for all lanes; a lane whose current entry lies on the candidate is counted by
+//      ballot and moves on to its next entry.  One compare, one ballot and one add count a diagonal for 64 rows,
+//      whether or not the rows are aligned step by step (boundary rows of a stencil hold fewer entries);
+//   2. LDS: entries the merge steps over (diagonals not in the list) go to the block's hash table one by one; when
+//      they are more than a quarter of a chunk the list is written to the table and rebuilt from the next chunk,
+//      and after two lists in a row that did not fit (rows that share no diagonals) the wave goes without one;
 //   3. the table is flushed to the global histogram once per block (same-address atomics serialise in L2: a
 //      stencil's 27 diagonals cost 27 global atomics per block, not one per wave and step).
 // Keys that find no free slot within a few probes (matrices with many distinct diagonals) go straight to memory.
 // A row longer than SHORT_ROW is walked by the whole wave with coalesced loads; entries of one row lie on distinct
 // diagonals, so they are counted directly.
-static_assert(2 * SHORT_ROW <= WAVE, "the per-step cache lives in lanes k and k + SHORT_ROW");
+static_assert(SHORT_ROW <= WAVE, "one candidate diagonal per lane");
 
 constexpr int TB = 512;           // threads per block of the traversal: 8 waves share one hash table
 constexpr int TCAP = 2 * FCAP;    // entries a wave stages at a time: 64 rows of SHORT_ROW entries, so that the rows of a
@@ -66,9 +68,10 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
     bool err = false;
     uint64_t errm = 0ull;   // lanes of this wave that met a column out of range or out of order
     unsigned long long mx = 0ull, mn = ~0ull, sq = 0ull;
-    // per-step cache of (diagonal, count): step k owns lanes k and k + SHORT_ROW of the pairs A and B (four ways)
-    int ckeyA = -1, ckeyB = -1;
-    int ccntA = 0, ccntB = 0;
+    // candidate diagonals of this wave: lane d holds the d-th key (ascending; NONE beyond ncand) and its count
+    constexpr int NONE = 0x7fffffff;
+    int cand = NONE, ccnt = 0;
+    int ncand = 0, tmpl_fail = 0, chunks = 0;   // wave-uniform
     const int kbias = (int)(m - 1);
     const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
     int64_t row_end = row_begin + rows_per_block;
@@ -114,69 +117,91 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
             const int32_t *mine = s_col + (mine_now ? lo - start : 0);
             int prev = -1;
             const int cm1 = cnt > 0 ? cnt - 1 : 0;
-            // Lane masks are built from the compare instructions' own 64-bit results and combined with scalar
-            // operations: every per-lane boolean that is turned into a mask costs two more vector instructions.
-            for (int k = 0;; ++k) {
-                const uint64_t actm = __builtin_amdgcn_sicmp(k, cnt, 40 /* signed < */);
-                if (!actm) break;
-                const int ks = __builtin_amdgcn_readfirstlane(k);
-                const int c = mine[k < cm1 ? k : cm1];   // lanes past their row end re-read their last entry (unused)
-                const uint64_t okm = actm & __builtin_amdgcn_uicmp((unsigned)c, (unsigned)n, 36 /* unsigned < */) &
-                                     __builtin_amdgcn_sicmp(c, prev, 38 /* signed > */);
-                errm |= actm & ~okm;
-                prev = c;                                 // a lane past its row end never becomes active again in this chunk
-                if (DO_HIST) {
-                    const int key = c + krow;
-                    // the four cached diagonals of step k: lanes k and k + SHORT_ROW of two register pairs; the
-                    // second pair is only looked at when the first does not cover the step
-                    const int k0 = __builtin_amdgcn_readlane(ckeyA, ks), k1 = __builtin_amdgcn_readlane(ckeyA, ks + SHORT_ROW);
-                    const uint64_t h0 = okm & __builtin_amdgcn_sicmp(key, k0, 32 /* == */);
-                    const uint64_t h1 = okm & __builtin_amdgcn_sicmp(key, k1, 32);
-                    ccntA += lane == ks ? __popcll(h0) : (lane == ks + SHORT_ROW ? __popcll(h1) : 0);
-                    uint64_t todo = okm & ~(h0 | h1);
-                    if (todo) {
-                        const int k2 = __builtin_amdgcn_readlane(ckeyB, ks), k3 = __builtin_amdgcn_readlane(ckeyB, ks + SHORT_ROW);
-                        const uint64_t h2 = okm & __builtin_amdgcn_sicmp(key, k2, 32);
-                        const uint64_t h3 = okm & __builtin_amdgcn_sicmp(key, k3, 32);
-                        ccntB += lane == ks ? __popcll(h2) : (lane == ks + SHORT_ROW ? __popcll(h3) : 0);
-                        todo &= ~(h2 | h3);
-                    }
-                    if (todo) {
-                        // Keys the cache does not hold: each takes the place of the way with the smallest count when
-                        // it was met at least twice in this step or a way is still empty (single meetings are mostly
-                        // diagonals that do not repeat and must not push out ones that do).  Rows that share no
-                        // diagonals leave this loop at its first round.
-                        int rounds = 4;
-                        while (todo && rounds-- > 0) {
-                            const int leader = __ffsll((unsigned long long)todo) - 1;
-                            const int lkey = __builtin_amdgcn_readlane(key, leader);
-                            const uint64_t same = __builtin_amdgcn_sicmp(key, lkey, 32) & todo;   // todo holds valid lanes only
-                            const int mult = __popcll(same);
-                            const int n0 = __builtin_amdgcn_readlane(ccntA, ks), n1 = __builtin_amdgcn_readlane(ccntA, ks + SHORT_ROW);
-                            const int n2 = __builtin_amdgcn_readlane(ccntB, ks), n3 = __builtin_amdgcn_readlane(ccntB, ks + SHORT_ROW);
-                            int way = 0, nmin = n0;
-                            if (n1 < nmin) { way = 1; nmin = n1; }
-                            if (n2 < nmin) { way = 2; nmin = n2; }
-                            if (n3 < nmin) { way = 3; nmin = n3; }
-                            if (mult >= 2 || nmin == 0) {
-                                const int wl = ks + (way & 1) * SHORT_ROW;
-                                if (way < 2) {
-                                    if (lane == wl) {
-                                        if (ccntA) count_key(ckeyA, (uint32_t)ccntA, ht_key, ht_cnt, &ht_full, hist);
-                                        ckeyA = lkey; ccntA = mult;
-                                    }
-                                } else {
-                                    if (lane == wl) {
-                                        if (ccntB) count_key(ckeyB, (uint32_t)ccntB, ht_key, ht_cnt, &ht_full, hist);
-                                        ckeyB = lkey; ccntB = mult;
-                                    }
-                                }
-                                todo &= ~same;
-                            } else {
-                                break;   // a single meeting and no empty way: it and the rest go to the table below
-                            }
+            if constexpr (!DO_HIST) {
+                // validation only.  Lane masks are built from the compare instructions' own 64-bit results and
+                // combined with scalar operations.
+                for (int k = 0;; ++k) {
+                    const uint64_t actm = __builtin_amdgcn_sicmp(k, cnt, 40 /* signed < */);
+                    if (!actm) break;
+                    const int c = mine[k < cm1 ? k : cm1];   // lanes past their row end re-read their last entry (unused)
+                    const uint64_t okm = actm & __builtin_amdgcn_uicmp((unsigned)c, (unsigned)n, 36 /* unsigned < */) &
+                                         __builtin_amdgcn_sicmp(c, prev, 38 /* signed > */);
+                    errm |= actm & ~okm;
+                    prev = c;                                 // a lane past its row end never becomes active again in this chunk
+                }
+            } else {
+                if ((chunks++ & 31) == 0) tmpl_fail = 0;      // a wave that gave up on candidate lists tries again now and then
+                if (ncand == 0 && tmpl_fail < 2) {
+                    // the longest row of the chunk becomes the candidate list, if it is well-formed
+                    const int best = __builtin_amdgcn_readfirstlane(wave_max(cnt));
+                    if (best > 0) {
+                        const int L = __ffsll((unsigned long long)ballot64(cnt == best)) - 1;
+                        const int offL = __builtin_amdgcn_readlane((int)(mine - s_col), L);
+                        const int krowL = __builtin_amdgcn_readlane(krow, L);
+                        const int j = lane < best ? lane : best - 1;
+                        const int cj = s_col[offL + j];
+                        const int cp = s_col[offL + (j > 0 ? j - 1 : 0)];
+                        const bool okj = (unsigned)cj < (unsigned)n && (j == 0 || cj > cp);
+                        if (ballot64(!okj) == 0ull) {
+                            cand = lane < best ? cj + krowL : NONE;
+                            ccnt = 0;
+                            ncand = best;
                         }
-                        if ((todo >> lane) & 1ull) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
+                    }
+                }
+                // The lane's current entry as a key (NONE when the row is used up or malformed), checked as it is
+                // fetched: inside [0, n) and above its predecessor.
+                int e = 0;
+                int c = mine[0];
+                bool ok = cnt > 0 && (unsigned)c < (unsigned)n;
+                if (cnt > 0 && !ok) err = true;
+                int cur = ok ? c + krow : NONE;
+                prev = c;
+                auto advance = [&]() {
+                    ++e;
+                    const int cn = mine[e < cm1 ? e : cm1];
+                    const bool okn = e < cnt && (unsigned)cn < (unsigned)n && cn > prev;
+                    if (e < cnt && !okn) err = true;
+                    prev = cn;
+                    cur = okn ? cn + krow : NONE;
+                };
+                int nhit = 0, nmiss = 0;
+                const int nc = __builtin_amdgcn_readfirstlane(ncand);
+                for (int d = 0; d < nc; ++d) {
+                    const int target = __builtin_amdgcn_readlane(cand, d);
+                    uint64_t below = __builtin_amdgcn_sicmp(cur, target, 40 /* signed < */);
+                    while (below) {                            // entries on diagonals that are not in the list
+                        nmiss += (int)__popcll(below);
+                        if (cur < target) {
+                            count_key(cur, 1u, ht_key, ht_cnt, &ht_full, hist);
+                            advance();
+                        }
+                        below = __builtin_amdgcn_sicmp(cur, target, 40);
+                    }
+                    const uint64_t hit = __builtin_amdgcn_sicmp(cur, target, 32 /* == */);
+                    if (hit) {
+                        const int nh = (int)__popcll(hit);
+                        nhit += nh;
+                        ccnt += lane == d ? nh : 0;
+                        if (cur == target) advance();
+                    }
+                }
+                uint64_t left = __builtin_amdgcn_sicmp(cur, NONE, 33 /* != */);
+                while (left) {                                 // entries beyond the last candidate
+                    nmiss += (int)__popcll(left);
+                    if (cur != NONE) {
+                        count_key(cur, 1u, ht_key, ht_cnt, &ht_full, hist);
+                        advance();
+                    }
+                    left = __builtin_amdgcn_sicmp(cur, NONE, 33);
+                }
+                if (nc > 0) {
+                    if (nmiss * 4 > nhit + nmiss) {            // the list does not fit these rows: write it out, start over
+                        if (lane < ncand && ccnt) count_key(cand, (uint32_t)ccnt, ht_key, ht_cnt, &ht_full, hist);
+                        cand = NONE; ccnt = 0; ncand = 0;
+                        ++tmpl_fail;
+                    } else {
+                        tmpl_fail = 0;
                     }
                 }
             }
@@ -197,8 +222,7 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
         }
     }
     if (DO_HIST) {
-        if (ccntA) count_key(ckeyA, (uint32_t)ccntA, ht_key, ht_cnt, &ht_full, hist);
-        if (ccntB) count_key(ckeyB, (uint32_t)ccntB, ht_key, ht_cnt, &ht_full, hist);
+        if (lane < ncand && ccnt) count_key(cand, (uint32_t)ccnt, ht_key, ht_cnt, &ht_full, hist);
         __syncthreads();
         for (int i = threadIdx.x; i < HT_SIZE; i += TB) {
             const uint32_t c = ht_cnt[i];

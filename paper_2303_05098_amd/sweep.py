@@ -2,6 +2,7 @@
 matrices.
 
     python -m paper_2303_05098_amd.sweep run --first 0 --count 64 --out sweep_000.jsonl     (GPU)
+    python -m paper_2303_05098_amd.sweep features --first 0 --count 64 --out fe_000.jsonl     (GPU; feature time only)
     python -m paper_2303_05098_amd.sweep fit 'sweep_*.jsonl' --model paper_2303_05098_amd/models/mi355x_forest.bin
 
 ``run``: per matrix, features on the GPU (mo_features), then the run-first tuner (mo_tune, 1000 timed SpMVs per
@@ -59,14 +60,49 @@ def run(first: int, count: int, out: str, reps: int, n_hi: float) -> None:
             torch.cuda.empty_cache()
 
 
+def run_features(first: int, count: int, out: str, n_hi: float) -> None:
+    """Feature-extraction time only (after a change to the feature kernels): lines {"k", "t_fe_ms", "features"} that
+    `load` lays over the full records of the same matrices."""
+    import torch
+
+    from . import mo
+
+    with open(out, "a") as fh:
+        for k in range(first, first + count):
+            fam, m, n, rp, ci, v = synth.sweep_matrix(k, 1e3, n_hi)
+            a = mo.Csr(m, n, rp, ci, v)
+            mo.mo_features(a)
+            fe = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                feats, ints = mo.mo_features(a)
+                fe.append((time.perf_counter() - t0) * 1e3)
+            fh.write(json.dumps(dict(k=k, t_fe_ms=min(fe), features=[float(f) for f in feats])) + "\n")
+            fh.flush()
+            if k % 64 == 0:
+                print(f"[sweep features] k={k} {fam} m={m} t_fe={min(fe):.3f} ms", flush=True)
+            del a
+            torch.cuda.empty_cache()
+
+
 def load(paths) -> list:
-    recs = {}
+    """Records by matrix index; a later file wins.  Lines without timings (from `features`) only replace t_fe_ms, and
+    must carry the same feature vector as the record they update."""
+    recs, fe_only = {}, []
     for p in paths:
         for line in open(p):
             line = line.strip()
             if line:
                 r = json.loads(line)
-                recs[r["k"]] = r
+                if "ms_per_rep" in r:
+                    recs[r["k"]] = r
+                else:
+                    fe_only.append(r)
+    for r in fe_only:
+        if r["k"] in recs:
+            if recs[r["k"]]["features"] != r["features"]:
+                raise ValueError(f"matrix {r['k']}: feature vector differs between the record and its update")
+            recs[r["k"]]["t_fe_ms"] = r["t_fe_ms"]
     return [recs[k] for k in sorted(recs)]
 
 
@@ -172,6 +208,11 @@ def main(argv=None) -> int:
     r.add_argument("--out", required=True)
     r.add_argument("--reps", type=int, default=1000)
     r.add_argument("--n-hi", type=float, default=4e6)
+    q = sub.add_parser("features")
+    q.add_argument("--first", type=int, default=0)
+    q.add_argument("--count", type=int, default=256)
+    q.add_argument("--out", required=True)
+    q.add_argument("--n-hi", type=float, default=4e6)
     f = sub.add_parser("fit")
     f.add_argument("records", nargs="+")
     f.add_argument("--model", default=None)
@@ -183,6 +224,9 @@ def main(argv=None) -> int:
     args = ap.parse_args(argv)
     if args.cmd == "run":
         run(args.first, args.count, args.out, args.reps, args.n_hi)
+        return 0
+    if args.cmd == "features":
+        run_features(args.first, args.count, args.out, args.n_hi)
         return 0
     paths = [p for pat in args.records for p in sorted(glob.glob(pat))]
     recs = load(paths)
