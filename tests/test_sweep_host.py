@@ -94,3 +94,22 @@ def test_committed_model_is_the_tuned_forest_fitted_on_the_training_set(tmp_path
     loaded = mo.mo_model_load(committed)
     assert np.array_equal(mo.mo_predict(loaded, X), mo.mo_predict(model, X))
     assert fit.accuracy(y[test], mo.mo_predict(loaded, X[test])) == rep["forest"]["tuned"]["test"]["accuracy"]
+
+
+def test_feature_time_updates_lay_over_records(tmp_path):
+    """Lines written by `sweep features` replace t_fe_ms of the record with the same k, whatever the file order, and a
+    line whose feature vector differs from the record's is refused."""
+    full = dict(k=3, family="x", m=2, n=2, nnz=2, features=[2.0] * 10, t_fe_ms=1.0, ms_per_rep=[1.0] * 6, convert_ms=[0.1] * 6,
+                best=1, reps=1000)
+    other = dict(full, k=4, t_fe_ms=2.0)
+    a, b = tmp_path / "a.jsonl", tmp_path / "b.jsonl"
+    a.write_text(json.dumps(dict(k=3, t_fe_ms=0.25, features=[2.0] * 10)) + "\n" + json.dumps(dict(k=9, t_fe_ms=0.5, features=[1.0] * 10)) + "\n")
+    b.write_text(json.dumps(full) + "\n" + json.dumps(other) + "\n")
+    for order in ([a, b], [b, a]):
+        recs = sweep.load([str(p) for p in order])
+        assert [r["k"] for r in recs] == [3, 4] and [r["t_fe_ms"] for r in recs] == [0.25, 2.0]
+        assert recs[0]["ms_per_rep"] == [1.0] * 6
+    a.write_text(json.dumps(dict(k=3, t_fe_ms=0.25, features=[3.0] * 10)) + "\n")
+    import pytest
+    with pytest.raises(ValueError):
+        sweep.load([str(a), str(b)])
