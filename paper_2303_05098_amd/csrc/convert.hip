@@ -522,11 +522,13 @@ mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, i
     mo_matrix *h = b.h;
     h->csr_max_row = max_row;
     const double avg = m > 0 ? (double)nnz / (double)m : 0.0;
-    // lanes per row: the rows of one tile (about CSR_TILE / avg) should fit one pass of 256 / g rows
+    const int tile = nnz < CSR_SMALL_NNZ ? CSR_TILE_SMALL : CSR_TILE;
+    h->csr_tile = tile;
+    // lanes per row: the rows of one tile (about tile / avg) should fit one pass of 256 / g rows
     int g = 1;
-    while (g < 16 && avg > 10.0 * g) g <<= 1;
+    while (g < 16 && avg > (10.0 * tile / CSR_TILE) * g) g <<= 1;
     h->csr_group = g;
-    h->csr_tiles = csr_tile_count(nnz, CSR_TILE);
+    h->csr_tiles = csr_tile_count(nnz, tile);
     h->csr_split = max_row > CSR_TILE_SLACK ? 1 : 0;
     {
         h->csr_tile_rp = (int32_t *)b.own((size_t)(h->csr_tiles + 1) * 8);
@@ -535,7 +537,7 @@ mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, i
             h->csr_carry_val = b.own((size_t)h->csr_tiles * dtype_size(h->dtype));
         }
         if (b.failed) return MO_E_ALLOC;
-        MO_TRY(csr_build_tiles(row_ptr, m, nnz, h->csr_tiles, CSR_TILE, h->csr_tile_rp, b.s));
+        MO_TRY(csr_build_tiles(row_ptr, m, nnz, h->csr_tiles, tile, h->csr_tile_rp, b.s));
     }
     return MO_OK;
 }

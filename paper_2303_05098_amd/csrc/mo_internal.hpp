@@ -52,6 +52,8 @@ struct Scratch {
 
 // ---------------------------------------------------------------- handle
 constexpr int CSR_TILE = 2048;        // entries per CSR work tile
+constexpr int CSR_TILE_SMALL = 512;   // ... for parts of fewer than CSR_SMALL_NNZ entries, which 2048-entry tiles would
+constexpr int64_t CSR_SMALL_NNZ = 1 << 20;   // spread over too few blocks (measured cross-over: 1 - 2 M entries)
 constexpr int CSR_TILE_SLACK = 256;   // longest row the tiled CSR kernel accepts (LDS holds CSR_TILE + slack entries)
 constexpr int COO_B_THREADS = 256;    // threads per COO block; a tile is COO_B_THREADS * coo_strip entries
 constexpr int64_t COO_SMALL_NNZ = 4 * 1024 * 1024;   // below this many entries the COO part of HYB uses 2-entry strips
@@ -87,7 +89,8 @@ struct mo_matrix {
     const void *csr_val = nullptr;
     // launch data derived at conversion time (not part of the format)
     int64_t csr_max_row = 0;
-    int64_t csr_tiles = 0;            // tiles of CSR_TILE entries; csr_group lanes per row in the LDS reduction
+    int64_t csr_tiles = 0;            // tiles of csr_tile entries; csr_group lanes per row in the LDS reduction
+    int32_t csr_tile = mo::CSR_TILE;  // CSR_TILE or CSR_TILE_SMALL
     int32_t csr_group = 1;
     int32_t csr_split = 0;            // 1: tiles cut rows (any row length), carries in csr_carry_*
     int32_t *csr_carry_row = nullptr;
