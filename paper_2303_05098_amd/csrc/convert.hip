@@ -3,7 +3,7 @@
 // Every conversion is integer bookkeeping plus copies of the stored values, so the produced arrays are fully
 // determined by the input: offsets ascending, row entries in ascending column order, padding col = -1 / val = +0.
 // Rows are mapped one per lane, which makes the writes into the slot-major ELL slabs and the diagonal-major DIA
-// slabs coalesced; the tail of a row longer than SHORT_ROW entries is handled by the whole wave.
+// slabs coalesced; a row longer than SHORT_ROW entries is handled by the whole wave.
 #include "dev_common.hpp"
 #include "mo_internal.hpp"
 
@@ -16,32 +16,12 @@ namespace mo {
 constexpr int CB = 256;
 constexpr int SHORT_ROW = 32;
 
-// ------------------------------------------------------------------ generic row walker
-// Calls f(row, p, s) for every stored entry p of the rows owned by this wave (one row per lane), s = position of
-// the entry inside its row.  Entries s < SHORT_ROW lane-per-row; later entries with lanes over consecutive p.
-template <class F>
-__device__ __forceinline__ void walk_rows(bool rv, int64_t row, int64_t lo, int64_t hi, F f)
-{
-    const int64_t len = hi - lo;
-    const int sl = (int)(len < SHORT_ROW ? len : SHORT_ROW);
-    const int wmax = wave_max(rv ? sl : 0);
-    for (int k = 0; k < wmax; ++k)
-        if (rv && k < sl) f(row, lo + k, (int64_t)k);
-    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
-    const int lane = lane_id();
-    while (longmask) {
-        const int l = __ffsll((unsigned long long)longmask) - 1;
-        longmask &= longmask - 1;
-        const int64_t r = __shfl(row, l, WAVE);
-        const int64_t rlo = __shfl(lo, l, WAVE);
-        const int64_t rhi = __shfl(hi, l, WAVE);
-        for (int64_t q = rlo + SHORT_ROW + lane; q < rhi; q += WAVE) f(r, q, q - rlo);
-    }
-}
-
-// Same traversal, but the entries of the wave's rows (one contiguous run of the CSR arrays) are first streamed into
+// ------------------------------------------------------------------ row walker
+// Calls f(row, p, s, col, val, own) for every stored entry p of the rows owned by this wave (one row per lane), s =
+// position of the entry inside its row.
+// The entries of the wave's rows (one contiguous run of the CSR arrays) are first streamed into
 // the wave's own LDS region with coalesced loads, WCAP entries at a time, and the lanes then pick their rows' entries
-// out of LDS: f(row, p, s, col, val).  Lane-per-row reads straight from global memory touch one cache line per lane
+// out of LDS.  Lane-per-row reads straight from global memory touch one cache line per lane
 // and step; this way every line is read once.  Rows longer than SHORT_ROW are left to the cooperative loop, which
 // reads global memory with consecutive lanes anyway.  No block barrier: a wave's LDS accesses execute in order.
 constexpr int WCAP = 1024;
