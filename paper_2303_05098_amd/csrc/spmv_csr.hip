@@ -77,10 +77,15 @@ __global__ __launch_bounds__(CSR_B) void k_csr_tiled(const int32_t *__restrict__
         c[j] = 0; v[j] = (T)0;
         if (i < cnt) { c[j] = ld_stream(col_idx + p0 + i); v[j] = ld_stream(val + p0 + i); }
     }
+    // x is gathered for every slot, used or not (an unused slot holds column 0), so that the gathers of a thread are
+    // all in flight together: behind a per-slot condition each one waited for the one before it
+    T xv[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) xv[j] = x[c[j]];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = threadIdx.x + j * CSR_B;
-        if (i < cnt) ps[i] = v[j] * x[c[j]];
+        if (i < cnt) ps[i] = v[j] * xv[j];
     }
     __syncthreads();
     for (int64_t base = 0; base < nrows; base += RPB) {
@@ -154,10 +159,13 @@ __global__ __launch_bounds__(CSR_B) void k_csr_split(const int32_t *__restrict__
         c[j] = 0; v[j] = (T)0;
         if (i < cnt) { c[j] = ld_stream(col_idx + t0 + i); v[j] = ld_stream(val + t0 + i); }
     }
+    T xv[EPT];   // gathered for every slot, used or not (an unused slot holds column 0): all in flight together
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) xv[j] = x[c[j]];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         const int i = threadIdx.x + j * CSR_B;
-        if (i < cnt) ps[i] = v[j] * x[c[j]];
+        if (i < cnt) ps[i] = v[j] * xv[j];
     }
     if (threadIdx.x == 0) s_nlong = 0;
     __syncthreads();
