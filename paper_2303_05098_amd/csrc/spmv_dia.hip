@@ -26,9 +26,12 @@ __global__ __launch_bounds__(DIA_B) void k_dia(const int32_t *__restrict__ off, 
     T sum = (T)0;
     const T *v = val + row;
 #pragma unroll 4
-    for (int64_t k = 0; k < nd; ++k) {
+    for (int64_t k = 0; k < nd; ++k) {   // loads without conditions (x index clamped), so that the unrolled ones overlap
         const int64_t j = row + off[k];
-        if (j >= 0 && j < n) sum += ld_stream(v + k * ld) * x[j];
+        const bool in = j >= 0 && j < n;
+        const T a = ld_stream(v + k * ld);
+        const T xv = x[in ? j : 0];
+        sum += in ? a * xv : (T)0;
     }
     st_stream(y + row, sum);
 }
@@ -46,9 +49,12 @@ __global__ __launch_bounds__(DIA_B) void k_hdc_fused(const int32_t *__restrict__
     T sum = (T)0;
     const T *v = val + row;
 #pragma unroll 4
-    for (int64_t k = 0; k < nd; ++k) {
+    for (int64_t k = 0; k < nd; ++k) {   // loads without conditions (x index clamped), so that the unrolled ones overlap
         const int64_t j = row + off[k];
-        if (j >= 0 && j < n) sum += ld_stream(v + k * ld) * x[j];
+        const bool in = j >= 0 && j < n;
+        const T a = ld_stream(v + k * ld);
+        const T xv = x[in ? j : 0];
+        sum += in ? a * xv : (T)0;
     }
     for (int32_t p = lo; p < hi; ++p) sum += cval[p] * x[col_idx[p]];
     st_stream(y + row, sum);
