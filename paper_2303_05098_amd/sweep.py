@@ -153,7 +153,7 @@ def time_select(model, X, rounds: int = 20) -> float:
 
 
 def analyse(recs, tree_grid=None, forest_grid=None, reps_eq2: int = 1000, score: str = "balanced_accuracy",
-            tolerance: float = 0.005):
+            tolerance: float = 0.0):
     """The procedure of Section VII-C on the records: stratified 80 / 20 split, grid search with 5-fold CV on the
     training set for a decision tree and a random forest, refit of the winners on the whole training set, accuracy
     and balanced accuracy of baseline and tuned models on the test set; then speedups over CSR and the tuner cost
@@ -218,7 +218,7 @@ def main(argv=None) -> int:
     f.add_argument("--model", default=None)
     f.add_argument("--report", default=None)
     f.add_argument("--score", default="balanced_accuracy", choices=["accuracy", "balanced_accuracy"])
-    f.add_argument("--tolerance", type=float, default=0.005,
+    f.add_argument("--tolerance", type=float, default=0.0,
                    help="pick the cheapest model whose CV score is within this much of the best one")
     f.add_argument("--grid", default=None, help="JSON file {\"tree\": {...}, \"forest\": {...}} replacing the built-in grids")
     args = ap.parse_args(argv)
