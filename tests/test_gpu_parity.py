@@ -52,6 +52,11 @@ def small_cases():
     rp3 = np.zeros(m + 1, np.int64)
     np.cumsum(np.bincount(ti, minlength=m), out=rp3[1:])
     out.append(("bulge", m, n, rp3.astype(np.int32), tj.astype(np.int32), synth.uniform_pm1(14, 0, np.arange(tj.size))))
+    # 16 diagonals 1500 apart: their x windows do not fit the LDS budget of the staged DIA / HDC kernels, so the
+    # direct kernels run (without and with scattered entries, which become the CSR remainder of HDC)
+    spread = [1500 * k for k in range(-8, 8)]
+    out.append(("spread16", *synth.banded_scatter(20000, spread, 0, 100, 15)))
+    out.append(("spread16s", *synth.banded_scatter(20000, spread, 2, 100, 16)))
     return out
 
 
