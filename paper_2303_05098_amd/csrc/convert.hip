@@ -620,6 +620,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         h->coo_val = b.own(e * sizeof(T));
         int32_t *rp_copy = (int32_t *)b.own((size_t)(a.m + 1) * 4);
         setup_coo_tiles(b, sizeof(T));
+        h->coo_every_row = an.min_row >= 1;
         if (b.failed) return MO_E_ALLOC;
         MO_HIP(hipMemcpyAsync(rp_copy, a.row_ptr, (size_t)(a.m + 1) * 4, hipMemcpyDeviceToDevice, s));
         h->coo_rp = rp_copy;

@@ -90,6 +90,7 @@ struct mo_matrix {
     // launch data derived at conversion time (not part of the format)
     int64_t csr_max_row = 0;
     int64_t csr_tiles = 0;            // tiles of csr_tile entries; csr_group lanes per row in the LDS reduction
+    bool coo_every_row = false;       // MO_COO: every row holds an entry, so the SpMV writes all of y and needs no zero pass
     int32_t csr_tile = mo::CSR_TILE;  // CSR_TILE or CSR_TILE_SMALL
     int32_t csr_group = 1;
     int32_t csr_split = 0;            // 1: tiles cut rows (any row length), carries in csr_carry_*

@@ -6,6 +6,7 @@
 //   2. runs that cross strips are finished through a small LDS table by the thread that holds the head of the run;
 //   3. a run that crosses a tile boundary leaves its continuation in a per-tile carry slot, added by k_coo_fixup.
 // Exactly one thread of the whole grid writes y[row] in step 1/2, and one thread adds the carries in step 3.
+// y is zeroed first only when the matrix has rows without entries (known from the conversion's row statistics).
 #include "dev_common.hpp"
 #include "mo_internal.hpp"
 
@@ -184,7 +185,8 @@ static mo_status coo_launch(const mo_matrix &a, const T *x, T *y, bool accumulat
 template <typename T>
 static mo_status coo_typed(const mo_matrix &a, const void *x, void *y, bool accumulate, hipStream_t s)
 {
-    if (!accumulate) MO_TRY(zero_typed<T>(y, a.m, s));
+    // y[row] is stored by the one thread that holds the head of the row's run, so only rows without entries need zeros
+    if (!accumulate && !(a.fmt == MO_COO && a.coo_every_row)) MO_TRY(zero_typed<T>(y, a.m, s));
     if (a.nnz_coo <= 0) return MO_OK;
     if (a.coo_strip == 2) return coo_launch<T, 2>(a, (const T *)x, (T *)y, accumulate, s);
     return coo_launch<T, 4>(a, (const T *)x, (T *)y, accumulate, s);
