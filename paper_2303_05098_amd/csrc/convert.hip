@@ -561,8 +561,9 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         MO_HIP(hipMemcpyAsync(hoff.data(), h->dia_off, (size_t)nd * 4, hipMemcpyDeviceToHost, s));
         MO_HIP(hipStreamSynchronize(s));
         // 512 threads per block, one row per lane in fp64 and two in fp32 (8 bytes per lane and load either way):
-        // measured best of {256, 512} x {1, 2} on the stencil and band configurations.
-        const int block = 512, rows = sizeof(T) == 4 ? 2 : 1;
+        // measured best of {256, 512} x {1, 2} on the stencil and band configurations.  Matrices of fewer than 2^17
+        // rows get 256-thread blocks: twice as many, shorter blocks on a chip they cannot fill anyway.
+        const int block = a.m < 131072 ? 256 : 512, rows = sizeof(T) == 4 ? 2 : 1;
         std::vector<int32_t> xpos, cl;
         int64_t elems = 0;
         if (plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems)) {
