@@ -32,6 +32,9 @@ MEASURED_TRAFFIC = {
     # profiles/spmv_all_formats_banded_scatter_f64.md: the 1.17 M scattered entries gather one 128-byte line of x each
     (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 736.2e6, (4, "f64", "ELL"): 784.5e6, (4, "f64", "HYB"): 684.9e6,
     (4, "f64", "COO"): 835.6e6 + 5.9e6,
+    # profiles/spmv_all_formats_banded_scatter_f32.md
+    (4, "f32", "HDC"): 331.4e6, (4, "f32", "HYB"): 482.6e6, (4, "f32", "CSR"): 502.8e6, (4, "f32", "ELL"): 565.9e6,
+    (4, "f32", "COO"): 640.4e6 + 5.8e6,
     # profiles/spmv_all_formats_lognormal_f64.md: 16.8 M random gathers of x miss L2; bytes counted at the L2 boundary
     (3, "f64", "CSR"): 1333.9e6, (3, "f64", "HYB"): 659.5e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
 }
