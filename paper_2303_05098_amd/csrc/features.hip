@@ -48,12 +48,8 @@ struct RowPart {
 template <bool DO_HIST>
 __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   int64_t m, int64_t n, int64_t nnz, int64_t rows_per_block,
-                                                  uint32_t *__restrict__ hist, RowPart *__restrict__ part, Counters *reset)
+                                                  uint32_t *__restrict__ hist, RowPart *__restrict__ part)
 {
-    if (reset && blockIdx.x == 0 && threadIdx.x == 0) {   // for the diagonal count that follows on the same stream
-        reset->max_row = 0ull; reset->min_row = ~0ull; reset->sum_sq = 0ull; reset->n_diag = 0ull; reset->n_true = 0ull;
-        reset->err = 0u; reset->pad = 0u;
-    }
     __shared__ int ht_key[DO_HIST ? HT_SIZE : 1];
     __shared__ uint32_t ht_cnt[DO_HIST ? HT_SIZE : 1];
     __shared__ int ht_full;
@@ -268,7 +264,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
         hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr);
         MO_LAUNCH_CHECK();
         hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part, (Counters *)nullptr);
+                           rows_per_block, hist, part);
         MO_LAUNCH_CHECK();
         const int64_t mn = a.m < a.n ? a.m : a.n;
         hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
@@ -276,7 +272,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
         MO_LAUNCH_CHECK();
     } else {
         hipLaunchKernelGGL(k_traverse<false>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part, (Counters *)nullptr);
+                           rows_per_block, hist, part);
         MO_LAUNCH_CHECK();
     }
     struct { Counters c; char pad[256 - sizeof(Counters)]; RowPart part[TRAV_BLOCKS]; } h;
@@ -307,7 +303,8 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
 // allocator) and a pinned host block for the results, under these rules:
 //   * on entry the histogram part of the block is all zero: the counting kernel clears what it reads, so no fill
 //     kernel runs after the first call;
-//   * the traversal resets the diagonal counters itself;
+//   * both kernels leave their per-block results (row statistics, diagonal counts) directly in the pinned host block,
+//     which the host adds up after the synchronisation: no counters to reset and no copy command after the kernels;
 //   * `clean` is dropped before the first launch and set again only after the final synchronisation, so an error on
 //     the way makes the next call zero the block again;
 //   * one call at a time owns the block (try-lock); a concurrent call, or a failed allocation, takes the ordinary
@@ -315,8 +312,15 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
 // mo_set_allocator releases the block through the allocator it came from.
 namespace {
 
+struct DiagPart {
+    unsigned long long n_diag, n_true;
+};
+constexpr int DIAG_BLOCKS = 512;
+
+// Counts the non-empty and the true diagonals and clears the counters it reads; every block leaves its two counts in
+// dpart[blockIdx.x] (no atomics: the host adds the few hundred partial results).
 __global__ __launch_bounds__(FB) void k_diag_count_clear(uint32_t *__restrict__ hist, int64_t nd, unsigned long long thr_rhs,
-                                                          unsigned long long td_den, Counters *ctr)
+                                                          unsigned long long td_den, DiagPart *__restrict__ dpart)
 {
     unsigned long long c_nd = 0, c_td = 0;
     const int64_t stride = (int64_t)gridDim.x * FB;
@@ -334,19 +338,19 @@ __global__ __launch_bounds__(FB) void k_diag_count_clear(uint32_t *__restrict__ 
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int w = 1; w < FB / WAVE; ++w) { c_nd += s_nd[w]; c_td += s_td[w]; }
-        if (c_nd) atomicAdd(&ctr->n_diag, c_nd);
-        if (c_td) atomicAdd(&ctr->n_true, c_td);
+        dpart[blockIdx.x] = DiagPart{c_nd, c_td};
     }
 }
 
-constexpr size_t HEAD_BYTES = 256 + (size_t)TRAV_BLOCKS * sizeof(RowPart);
+// results of one call, written by the kernels straight into pinned host memory (no copy command after them)
+constexpr size_t HOST_BYTES = (size_t)TRAV_BLOCKS * sizeof(RowPart) + (size_t)DIAG_BLOCKS * sizeof(DiagPart);
 
 struct FeatureCache {
     std::mutex mu;
-    char *dev = nullptr;     // [Counters in 256 bytes | RowPart x TRAV_BLOCKS | histogram of hist_cap counters]
+    uint32_t *dev = nullptr;   // histogram of hist_cap counters
     int64_t hist_cap = 0;
     bool clean = false;
-    void *host = nullptr;    // pinned, HEAD_BYTES
+    void *host = nullptr;      // pinned: [RowPart x TRAV_BLOCKS | DiagPart x DIAG_BLOCKS]
     int device = -1;
 };
 FeatureCache g_fc;
@@ -365,7 +369,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     std::unique_lock<std::mutex> lk(g_fc.mu, std::try_to_lock);
     int dev_now = -1;
     bool usable = lk.owns_lock() && hipGetDevice(&dev_now) == hipSuccess;
-    if (usable && !g_fc.host && hipHostMalloc(&g_fc.host, HEAD_BYTES, hipHostMallocDefault) != hipSuccess) {
+    if (usable && !g_fc.host && hipHostMalloc(&g_fc.host, HOST_BYTES, hipHostMallocDefault) != hipSuccess) {
         g_fc.host = nullptr;
         usable = false;
     }
@@ -373,7 +377,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     if (usable && (g_fc.hist_cap < ndiag || g_fc.device != dev_now)) {
         if (g_fc.dev) dev_free(g_fc.dev, s);
         g_fc.hist_cap = ndiag + ndiag / 2;
-        g_fc.dev = (char *)dev_alloc(HEAD_BYTES + (size_t)g_fc.hist_cap * sizeof(uint32_t), s);
+        g_fc.dev = (uint32_t *)dev_alloc((size_t)g_fc.hist_cap * sizeof(uint32_t), s);
         g_fc.clean = false;
         g_fc.device = dev_now;
         if (!g_fc.dev) { g_fc.hist_cap = 0; usable = false; }
@@ -385,31 +389,29 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         out->hist = nullptr;   // gone with the scratch
         return MO_OK;
     }
-    Counters *ctr = (Counters *)g_fc.dev;
-    RowPart *part = (RowPart *)(g_fc.dev + 256);
-    uint32_t *hist = (uint32_t *)(g_fc.dev + HEAD_BYTES);
+    RowPart *part = (RowPart *)g_fc.host;
+    DiagPart *dpart = (DiagPart *)((char *)g_fc.host + (size_t)TRAV_BLOCKS * sizeof(RowPart));
+    uint32_t *hist = g_fc.dev;
     const bool was_clean = g_fc.clean;
     g_fc.clean = false;
     if (!was_clean) {
-        hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, ctr);
+        hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, 0u);
         MO_LAUNCH_CHECK();
     }
     int64_t rows_per_block = (a.m + TRAV_BLOCKS - 1) / TRAV_BLOCKS;
     rows_per_block = ((rows_per_block + TB - 1) / TB) * TB;
     const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;
     hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                       rows_per_block, hist, part, ctr);
+                       rows_per_block, hist, part);
     MO_LAUNCH_CHECK();
     const int64_t mn = a.m < a.n ? a.m : a.n;
-    hipLaunchKernelGGL(k_diag_count_clear, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
-                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
+    const int dblocks = grid_for(ndiag, FB * 4, DIAG_BLOCKS);
+    hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart);
     MO_LAUNCH_CHECK();
-    const size_t bytes = 256 + (size_t)row_blocks * sizeof(RowPart);
-    MO_HIP(hipMemcpyAsync(g_fc.host, g_fc.dev, bytes, hipMemcpyDeviceToHost, s));
-    MO_HIP(hipStreamSynchronize(s));
+    MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
     g_fc.clean = true;
-    const Counters *hc = (const Counters *)g_fc.host;
-    const RowPart *hp = (const RowPart *)((const char *)g_fc.host + 256);
+    const RowPart *hp = part;
     unsigned long long mx = 0ull, mnr = ~0ull, sq = 0ull, err = 0ull;
     for (int64_t b = 0; b < row_blocks; ++b) {
         mx = hp[b].max_row > mx ? hp[b].max_row : mx;
@@ -417,12 +419,14 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         sq += hp[b].sum_sq;
         err |= hp[b].err;
     }
+    unsigned long long n_diag = 0ull, n_true = 0ull;
+    for (int b = 0; b < dblocks; ++b) { n_diag += dpart[b].n_diag; n_true += dpart[b].n_true; }
     if (err) return MO_E_CSR_INVALID;
     out->max_row = (int64_t)mx;
     out->min_row = (int64_t)mnr;
     out->sum_sq = sq;
-    out->n_diag = (int64_t)hc->n_diag;
-    out->n_true = (int64_t)hc->n_true;
+    out->n_diag = (int64_t)n_diag;
+    out->n_true = (int64_t)n_true;
     out->hist = nullptr;
     return MO_OK;
 }
