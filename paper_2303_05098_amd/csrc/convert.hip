@@ -478,8 +478,13 @@ struct Builder {
     mo_matrix *h;
     hipStream_t s;
     bool failed = false;
+    std::vector<std::vector<int32_t>> keep;   // host arrays that asynchronous uploads still read: alive until the end
     Builder(hipStream_t st) : h(new (std::nothrow) mo_matrix()), s(st) { if (h) h->home = st; }
-    ~Builder() { if (h) release(); }
+    ~Builder()
+    {
+        if (!keep.empty()) (void)hipStreamSynchronize(s);   // a no-op after the conversion's final synchronisation
+        if (h) release();
+    }
     void *own(size_t bytes)
     {
         void *p = dev_alloc(bytes, s);
@@ -570,12 +575,15 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
             h->dia_xpos = (int32_t *)b.own(xpos.size() * 4);
             h->dia_clusters = (int32_t *)b.own(cl.size() * 4);
             if (b.failed) return MO_E_ALLOC;
-            MO_HIP(hipMemcpyAsync(h->dia_xpos, xpos.data(), xpos.size() * 4, hipMemcpyHostToDevice, s));
-            MO_HIP(hipMemcpyAsync(h->dia_clusters, cl.data(), cl.size() * 4, hipMemcpyHostToDevice, s));
-            MO_HIP(hipStreamSynchronize(s));   // the host vectors go out of scope
+            const size_t nx = xpos.size(), ncl = cl.size();
+            b.keep.push_back(std::move(xpos));   // the uploads complete by the conversion's final synchronisation
+            b.keep.push_back(std::move(cl));
+            const std::vector<int32_t> &kx = b.keep[b.keep.size() - 2], &kc = b.keep.back();
+            MO_HIP(hipMemcpyAsync(h->dia_xpos, kx.data(), nx * 4, hipMemcpyHostToDevice, s));
+            MO_HIP(hipMemcpyAsync(h->dia_clusters, kc.data(), ncl * 4, hipMemcpyHostToDevice, s));
             h->dia_block = block;
             h->dia_rows = rows;
-            h->dia_ncl = (int32_t)(cl.size() / 3);
+            h->dia_ncl = (int32_t)(ncl / 3);
             h->dia_lds_elems = elems;
         }
     }
