@@ -7,6 +7,7 @@
 #include "dev_common.hpp"
 #include "mo_internal.hpp"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <new>
@@ -134,25 +135,32 @@ __global__ __launch_bounds__(CB) void k_csr_to_coo(const int32_t *__restrict__ r
 }
 
 // ------------------------------------------------------------------ diagonal selection
-// flag[i] = 1 for every diagonal kept by the DIA part: all non-empty ones (DIA) or the true ones (HDC).
-__global__ __launch_bounds__(CB) void k_flag_diag(const uint32_t *__restrict__ hist, int64_t nd, int all_nonempty,
-                                                   unsigned long long thr_rhs, unsigned long long td_den, int32_t *__restrict__ flag)
+// Appends the offset of every diagonal kept by the DIA part - all non-empty ones (DIA) or the true ones (HDC) - to
+// off_out, in any order: there are few of them (at most max_fill times the mean row length), so the host sorts the
+// list, which it needs anyway for the launch plan of the SpMV kernel, and sends it back.
+__global__ __launch_bounds__(CB) void k_collect_diag(const uint32_t *__restrict__ hist, int64_t ndiag, int all_nonempty,
+                                                      unsigned long long thr_rhs, unsigned long long td_den, int64_t m,
+                                                      int32_t *__restrict__ count, int32_t *__restrict__ off_out, int32_t cap)
 {
-    const int64_t i = (int64_t)blockIdx.x * CB + threadIdx.x;
-    if (i >= nd) return;
-    const unsigned long long c = hist[i];
-    flag[i] = (c >= 1ull && (all_nonempty || c * td_den >= thr_rhs)) ? 1 : 0;
+    const int64_t stride = (int64_t)gridDim.x * CB;
+    for (int64_t i = (int64_t)blockIdx.x * CB + threadIdx.x; i < ndiag; i += stride) {
+        const unsigned long long c = hist[i];
+        if (c >= 1ull && (all_nonempty || c * td_den >= thr_rhs)) {
+            const int32_t p = atomicAdd(count, 1);
+            if (p < cap) off_out[p] = (int32_t)(i - (m - 1));
+        }
+    }
 }
 
-// pos[] = exclusive scan of flag[].  Writes the ascending offset list and turns pos into the slot map
-// (slot index of a kept diagonal, -1 otherwise), in place.
-__global__ __launch_bounds__(CB) void k_offsets_and_slots(const int32_t *__restrict__ flag, int32_t *__restrict__ pos, int64_t nd,
-                                                           int64_t m, int32_t *__restrict__ off)
+// Index of offset `off` in the ascending list dia_off[0, nd), or -1.
+__device__ __forceinline__ int find_slot(const int32_t *__restrict__ dia_off, int nd, int32_t off)
 {
-    const int64_t i = (int64_t)blockIdx.x * CB + threadIdx.x;
-    if (i >= nd) return;
-    if (flag[i]) off[pos[i]] = (int32_t)(i - (m - 1));
-    else pos[i] = -1;
+    int lo = 0, hi = nd;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (dia_off[mid] < off) lo = mid + 1; else hi = mid;
+    }
+    return (lo < nd && dia_off[lo] == off) ? lo : -1;
 }
 
 // DIA part of DIA / HDC.  A wave owns rw consecutive rows and stages their run of entries in LDS once.  Columns ascend
@@ -162,7 +170,8 @@ __global__ __launch_bounds__(CB) void k_offsets_and_slots(const int32_t *__restr
 // stores that cover rw consecutive rows of one diagonal; no zero-fill pass and no per-entry slot lookup are needed.
 // Entries that fall between kept diagonals (HDC) are skipped and counted into rest_cnt[row].
 // Rows that do not fit the staged window are merged straight from global memory; rows longer than SHORT_ROW are
-// handled by the whole wave through the slot map (zero the row's slots, wait for those stores, then scatter).
+// handled by the whole wave, each entry finding its slot by binary search in the offset list (zero the row's slots,
+// wait for those stores, then scatter).
 template <typename T, class ColAt, class ValAt>
 __device__ __forceinline__ int dia_merge_row(bool act, bool store, int cnt, int64_t row, const int32_t *__restrict__ dia_off, int nd,
                                              int64_t ld, T *__restrict__ dval, ColAt col_at, ValAt val_at)
@@ -190,7 +199,7 @@ __device__ __forceinline__ int dia_merge_row(bool act, bool store, int cnt, int6
 
 template <typename T>
 __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-                                                  const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
+                                                  const T *__restrict__ val, int64_t m,
                                                   const int32_t *__restrict__ dia_off, int nd, int64_t ld, T *__restrict__ dval,
                                                   int32_t *__restrict__ rest_cnt, int rw)
 {
@@ -232,7 +241,7 @@ __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row
             const int q = q0 + lane;
             int k = 0;
             if (q < rhi) {
-                k = slot[(int64_t)col_idx[q] - r + (m - 1)];
+                k = find_slot(dia_off, nd, (int32_t)((int64_t)col_idx[q] - r));
                 if (k >= 0) dval[(int64_t)k * ld + r] = val[q];
             }
             rest += (int)__popcll(ballot64(k < 0));
@@ -360,7 +369,7 @@ __device__ __forceinline__ void hdc_rest_row(bool act, int cnt, int need, int64_
 
 template <typename T>
 __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-                                                  const T *__restrict__ val, int64_t m, const int32_t *__restrict__ slot,
+                                                  const T *__restrict__ val, int64_t m,
                                                   const int32_t *__restrict__ dia_off, int nd, const int32_t *__restrict__ rest_ptr,
                                                   int32_t *__restrict__ rcol, T *__restrict__ rval, int rw)
 {
@@ -405,7 +414,7 @@ __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row
             int32_t c = 0;
             if (q < rhi) {
                 c = col_idx[q];
-                rest = slot[(int64_t)c - r + (m - 1)] < 0;
+                rest = find_slot(dia_off, nd, (int32_t)((int64_t)c - r)) < 0;
             }
             const uint64_t mask = ballot64(rest);
             if (rest) {
@@ -527,44 +536,45 @@ mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, i
     return MO_OK;
 }
 
-// Slot map for the DIA part: offsets (ascending) into h->dia_off, slot[] (m + n - 1 ints, scratch) for the fill.
+// DIA part: the kept offsets, ascending, into h->dia_off; the slab filled; the launch plan of the SpMV kernel.
 template <typename T>
 mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an, bool all_nonempty, int64_t nd,
-                         Builder &b, Scratch &scr, int32_t **slot_out, int32_t *rest_cnt = nullptr)
+                         Builder &b, Scratch &scr, int32_t *rest_cnt = nullptr)
 {
     hipStream_t s = b.s;
     const int64_t ndiag = a.m + a.n - 1;
-    int32_t *flag = (int32_t *)scr.get((size_t)ndiag * 4);
-    int32_t *pos = (int32_t *)scr.get((size_t)(ndiag + 1) * 4);
-    void *tmp = scr.get(scan_tmp_bytes(ndiag));
-    if (!flag || !pos || !tmp) return MO_E_ALLOC;
     mo_matrix *h = b.h;
     h->nd = nd;
     h->dia_off = (int32_t *)b.own((size_t)(nd > 0 ? nd : 1) * 4);
     h->dia_val = b.own((size_t)(nd > 0 ? nd : 1) * (size_t)h->ld * sizeof(T));
     if (b.failed) return MO_E_ALLOC;
-    const int64_t mn = a.m < a.n ? a.m : a.n;
-    hipLaunchKernelGGL(k_flag_diag, dim3(blocks_for(ndiag)), dim3(CB), 0, s, an.hist, ndiag, all_nonempty ? 1 : 0,
-                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, flag);
-    MO_LAUNCH_CHECK();
-    MO_TRY(exclusive_scan_i32(flag, pos, ndiag, tmp, s));
-    hipLaunchKernelGGL(k_offsets_and_slots, dim3(blocks_for(ndiag)), dim3(CB), 0, s, flag, pos, ndiag, a.m, h->dia_off);
-    MO_LAUNCH_CHECK();
     if (nd > 0) {
+        int32_t *count = (int32_t *)scr.get(256);
+        if (!count) return MO_E_ALLOC;
+        hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(CB), 0, s, count, (int64_t)1, 0);
+        MO_LAUNCH_CHECK();
+        const int64_t mn = a.m < a.n ? a.m : a.n;
+        hipLaunchKernelGGL(k_collect_diag, dim3(fill_grid(ndiag)), dim3(CB), 0, s, an.hist, ndiag, all_nonempty ? 1 : 0,
+                           (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, a.m, count,
+                           h->dia_off, (int32_t)nd);
+        MO_LAUNCH_CHECK();
+        b.keep.emplace_back((size_t)nd);
+        std::vector<int32_t> &hoff = b.keep.back();   // stays alive until the conversion's final synchronisation
+        MO_HIP(hipMemcpyAsync(hoff.data(), h->dia_off, (size_t)nd * 4, hipMemcpyDeviceToHost, s));
+        MO_HIP(hipStreamSynchronize(s));
+        std::sort(hoff.begin(), hoff.end());
+        MO_HIP(hipMemcpyAsync(h->dia_off, hoff.data(), (size_t)nd * 4, hipMemcpyHostToDevice, s));
         const int rw = rows_per_wave(a.m, a.nnz);
         hipLaunchKernelGGL(k_fill_dia<T>, dim3(wave_blocks_for(h->ld, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, (const T *)a.val, a.m,
-                           pos, h->dia_off, (int)nd, h->ld, (T *)h->dia_val, rest_cnt, rw);
+                           h->dia_off, (int)nd, h->ld, (T *)h->dia_val, rest_cnt, rw);
         MO_LAUNCH_CHECK();
     } else if (rest_cnt) {   // no diagonal is kept: every entry is remainder
         hipLaunchKernelGGL(k_surplus, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.m, (int64_t)0, rest_cnt);
         MO_LAUNCH_CHECK();
     }
-    *slot_out = pos;
-    // launch plan for the LDS-staged SpMV kernel: needs the offsets on the host
+    // launch plan for the LDS-staged SpMV kernel, from the offsets the host already holds
     if (nd > 0) {
-        std::vector<int32_t> hoff((size_t)nd);
-        MO_HIP(hipMemcpyAsync(hoff.data(), h->dia_off, (size_t)nd * 4, hipMemcpyDeviceToHost, s));
-        MO_HIP(hipStreamSynchronize(s));
+        const std::vector<int32_t> hoff = b.keep.back();
         // 512 threads per block, one row per lane in fp64 and two in fp32 (8 bytes per lane and load either way):
         // measured best of {256, 512} x {1, 2} on the stencil and band configurations.  Matrices of fewer than 2^17
         // rows get 256-thread blocks: twice as many, shorter blocks on a chip they cannot fill anyway.
@@ -642,8 +652,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
     }
     case MO_DIA: {
         if (!slab_feasible(an.n_diag, a.m, a.nnz, p)) return MO_E_FILL;
-        int32_t *slot = nullptr;
-        MO_TRY(build_dia_part<T>(a, p, an, true, an.n_diag, b, scr, &slot));
+        MO_TRY(build_dia_part<T>(a, p, an, true, an.n_diag, b, scr));
         break;
     }
     case MO_ELL:
@@ -703,12 +712,11 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         break;
     }
     case MO_HDC: {
-        int32_t *slot = nullptr;
         int32_t *cnt = (int32_t *)scr.get((size_t)a.m * 4);
         int32_t *rest_ptr = (int32_t *)b.own((size_t)(a.m + 1) * 4);
         void *tmp = scr.get(scan_tmp_bytes(a.m));
         if (b.failed || !cnt || !tmp) return MO_E_ALLOC;
-        MO_TRY(build_dia_part<T>(a, p, an, false, an.n_true, b, scr, &slot, cnt));   // also counts the remainder per row
+        MO_TRY(build_dia_part<T>(a, p, an, false, an.n_true, b, scr, cnt));   // also counts the remainder per row
         MO_TRY(exclusive_scan_i32(cnt, rest_ptr, a.m, tmp, s));
         int32_t total = 0;
         MO_HIP(hipMemcpyAsync(&total, rest_ptr + a.m, 4, hipMemcpyDeviceToHost, s));
@@ -723,7 +731,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
             MO_HIP(hipMemcpyAsync(rval, aval, (size_t)total * sizeof(T), hipMemcpyDeviceToDevice, s));
         } else if (total > 0) {
             const int rw = rows_per_wave(a.m, a.nnz);
-            hipLaunchKernelGGL(k_hdc_rest<T>, dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, slot,
+            hipLaunchKernelGGL(k_hdc_rest<T>, dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m,
                                h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw);
             MO_LAUNCH_CHECK();
         }
