@@ -367,17 +367,19 @@ __device__ __forceinline__ void hdc_rest_row(bool act, int cnt, int need, int64_
     }
 }
 
-template <typename T>
+// SPARSE: the remainder is a small share of the entries, so only the columns are staged and the few values that leave
+// are fetched one by one (staging every value would double the bytes this pass reads).
+template <typename T, bool SPARSE>
 __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   const T *__restrict__ val, int64_t m,
                                                   const int32_t *__restrict__ dia_off, int nd, const int32_t *__restrict__ rest_ptr,
                                                   int32_t *__restrict__ rcol, T *__restrict__ rval, int rw)
 {
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
-    __shared__ T s_val[(CB / WAVE) * WCAP];
+    __shared__ T s_val[SPARSE ? 1 : (CB / WAVE) * WCAP];
     const int lane = lane_id();
     int32_t *sc = s_col + (threadIdx.x / WAVE) * WCAP;
-    T *sv = s_val + (threadIdx.x / WAVE) * WCAP;
+    T *sv = s_val + (SPARSE ? 0 : (threadIdx.x / WAVE) * WCAP);
     const int64_t row = (xcd_block(blockIdx.x, gridDim.x) * (CB / WAVE) + threadIdx.x / WAVE) * rw + lane;
     const bool rv = lane < rw && row < m;
     const int lo = row_ptr[row < m ? row : m], hi = row_ptr[row + 1 < m ? row + 1 : m];   // empty run past the last row
@@ -389,12 +391,15 @@ __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row
     const int wb = __builtin_amdgcn_readfirstlane(lo);
     const int we = nvalid ? __builtin_amdgcn_readlane(hi, nvalid - 1) : wb;
     const int staged = we - wb < WCAP ? we - wb : WCAP;
-    if (staged > 0) stage_pair_to_lds(col_idx + wb, val + wb, sc, sv, staged, lane);
+    if (staged > 0) {
+        if constexpr (SPARSE) stage_to_lds(col_idx + wb, sc, staged, lane);
+        else stage_pair_to_lds(col_idx + wb, val + wb, sc, sv, staged, lane);
+    }
     const bool is_short = rv && len <= SHORT_ROW;
     const bool in_lds = is_short && hi - wb <= staged;
     const int off = in_lds ? lo - wb : 0;
     hdc_rest_row<T>(in_lds, len, need, row, base, dia_off, nd, rcol, rval,
-                    [&](int e) { return sc[off + e]; }, [&](int e) { return sv[off + e]; });
+                    [&](int e) { return sc[off + e]; }, [&](int e) { return SPARSE ? val[lo + e] : sv[off + e]; });
     const bool direct = is_short && !in_lds;
     if (ballot64(direct && need > 0) != 0ull)
         hdc_rest_row<T>(direct, len, need, row, base, dia_off, nd, rcol, rval,
@@ -731,7 +736,11 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
             MO_HIP(hipMemcpyAsync(rval, aval, (size_t)total * sizeof(T), hipMemcpyDeviceToDevice, s));
         } else if (total > 0) {
             const int rw = rows_per_wave(a.m, a.nnz);
-            hipLaunchKernelGGL(k_hdc_rest<T>, dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m,
+            if ((int64_t)total * 4 < a.nnz)
+                hipLaunchKernelGGL((k_hdc_rest<T, true>), dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m,
+                               h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw);
+            else
+                hipLaunchKernelGGL((k_hdc_rest<T, false>), dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m,
                                h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw);
             MO_LAUNCH_CHECK();
         }
