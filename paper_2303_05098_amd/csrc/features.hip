@@ -315,7 +315,7 @@ namespace {
 struct DiagPart {
     unsigned long long n_diag, n_true;
 };
-constexpr int DIAG_BLOCKS = 512;
+constexpr int DIAG_BLOCKS = 2048;
 
 // Counts the non-empty and the true diagonals and clears the counters it reads; every block leaves its two counts in
 // dpart[blockIdx.x] (no atomics: the host adds the few hundred partial results).
@@ -405,7 +405,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
                        rows_per_block, hist, part);
     MO_LAUNCH_CHECK();
     const int64_t mn = a.m < a.n ? a.m : a.n;
-    const int dblocks = grid_for(ndiag, FB * 4, DIAG_BLOCKS);
+    const int dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
     hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
                        (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart);
     MO_LAUNCH_CHECK();
