@@ -123,6 +123,29 @@ void mo_default_params(mo_params *out);
 mo_status mo_features(const mo_csr *a, const mo_params *params, double out[MO_NUM_FEATURES],
                       mo_feature_ints *ints_opt, void *stream);
 
+/* The host half of mo_features on its own (Table I): the ten doubles from the integer statistics, with the same
+ * correctly rounded operations, so that the result equals mo_features' bit for bit.  Pure host. */
+mo_status mo_features_finalize(const mo_feature_ints *ints, double out[MO_NUM_FEATURES]);
+
+/* mo_features for callers that cannot allocate or wait: code under HIP stream capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same kernels and same integers as mo_features, but the diagonal histogram and the per-block
+ * partial results live in a device array inside the library (one copy per GPU, about 16 MiB, held until the process
+ * ends) and the call neither allocates, frees nor synchronises: it enqueues four kernels on `stream` and returns.
+ *   out_dev : DEVICE-accessible memory owned by the caller (device memory or pinned host memory); when the enqueued
+ *             work has finished it holds the integer statistics and status = MO_OK or MO_E_CSR_INVALID (then the
+ *             integers mean nothing).  mo_features_finalize turns ints into the ten doubles.
+ *   limit   : m + n - 1 <= MO_STATIC_MAX_DIAGS, else MO_E_SHAPE and nothing is enqueued.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or threads)
+ * race and give wrong counts; calls in stream order are fine, each starts by clearing what it uses.  The first call
+ * on a device looks the array's address up (no allocation); make that call once outside any capture. */
+#define MO_STATIC_MAX_DIAGS 4194304
+typedef struct {
+    mo_feature_ints ints;
+    int32_t status; /* mo_status */
+    int32_t pad;
+} mo_feature_result;
+mo_status mo_features_static(const mo_csr *a, const mo_params *params, mo_feature_result *out_dev, void *stream);
+
 /* Build a handle holding `a` in format `fmt` (Section II-B).  The handle owns its arrays (installed allocator)
  * and does not alias the input, with one exception: an MO_CSR handle BORROWS row_ptr / col_idx / val, so those
  * must outlive it.  Validates the CSR precondition.  Synchronises `stream` (sizes are read back).

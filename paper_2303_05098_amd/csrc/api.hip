@@ -84,11 +84,24 @@ mo_status mo_features(const mo_csr *a, const mo_params *params, double out[MO_NU
     hipStream_t s = (hipStream_t)stream;
     Analysis an;
     MO_TRY(analyse_cached(*a, p, &an, s));
+    mo_feature_ints ints;
+    ints.m = a->m; ints.n = a->n; ints.nnz = a->nnz;
+    ints.max_row = an.max_row; ints.min_row = an.min_row;
+    ints.n_diag = an.n_diag; ints.n_true_diag = an.n_true;
+    ints.sum_sq_row = an.sum_sq;
+    if (ints_opt) *ints_opt = ints;
+    return mo_features_finalize(&ints, out);
+}
+
+mo_status mo_features_finalize(const mo_feature_ints *ints, double out[MO_NUM_FEATURES])
+{
+    if (!ints || !out) return MO_E_NULL;
+    if (ints->m < 1 || ints->n < 1 || ints->nnz < 0) return MO_E_SHAPE;
     // Table I, from exact integers.  M * sum(len^2) - NNZ^2 equals M^2 times the mean squared deviation of the row
     // lengths; every floating-point operation below is a single correctly rounded IEEE operation.
-    const unsigned __int128 num = (unsigned __int128)a->m * (unsigned __int128)an.sum_sq -
-                                  (unsigned __int128)a->nnz * (unsigned __int128)a->nnz;
-    const double md = (double)a->m, nd = (double)a->n, zd = (double)a->nnz;
+    const unsigned __int128 num = (unsigned __int128)ints->m * (unsigned __int128)ints->sum_sq_row -
+                                  (unsigned __int128)ints->nnz * (unsigned __int128)ints->nnz;
+    const double md = (double)ints->m, nd = (double)ints->n, zd = (double)ints->nnz;
     const double mm = md * md;
     const double var = (double)num / mm;
     out[0] = md;
@@ -97,18 +110,21 @@ mo_status mo_features(const mo_csr *a, const mo_params *params, double out[MO_NU
     out[3] = zd / md;
     const double mn = md * nd;
     out[4] = zd / mn;
-    out[5] = (double)an.max_row;
-    out[6] = (double)an.min_row;
+    out[5] = (double)ints->max_row;
+    out[6] = (double)ints->min_row;
     out[7] = std::sqrt(var);
-    out[8] = (double)an.n_diag;
-    out[9] = (double)an.n_true;
-    if (ints_opt) {
-        ints_opt->m = a->m; ints_opt->n = a->n; ints_opt->nnz = a->nnz;
-        ints_opt->max_row = an.max_row; ints_opt->min_row = an.min_row;
-        ints_opt->n_diag = an.n_diag; ints_opt->n_true_diag = an.n_true;
-        ints_opt->sum_sq_row = an.sum_sq;
-    }
+    out[8] = (double)ints->n_diag;
+    out[9] = (double)ints->n_true_diag;
     return MO_OK;
+}
+
+mo_status mo_features_static(const mo_csr *a, const mo_params *params, mo_feature_result *out_dev, void *stream)
+{
+    if (!out_dev) return MO_E_NULL;
+    MO_TRY(check_csr_args(a));
+    mo_params p;
+    MO_TRY(check_params(params, &p));
+    return features_static(*a, p, out_dev, (hipStream_t)stream);
 }
 
 mo_status mo_convert(const mo_csr *a, mo_format fmt, const mo_params *params, mo_matrix **out, void *stream)

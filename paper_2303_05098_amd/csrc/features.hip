@@ -431,4 +431,95 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     return MO_OK;
 }
 
+// ------------------------------------------------------------------ the call that allocates nothing
+// For callers that cannot allocate (stream capture, tight serving loops): the same two kernels as above, with the
+// diagonal histogram and the per-block partial results in a file-scope device array instead of allocator memory, and
+// a last one-block kernel that adds the partial results up on the device and writes the integers where the caller
+// wants them.  Every GPU holds its own copy of the array at its own address; the address is looked up once per device.
+namespace {
+
+constexpr int64_t STATIC_MAX_DIAGS = (int64_t)MO_STATIC_MAX_DIAGS;
+struct StaticScratch {
+    uint32_t hist[STATIC_MAX_DIAGS];
+    RowPart part[TRAV_BLOCKS];
+    DiagPart dpart[DIAG_BLOCKS];
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticScratch)];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mu;
+StaticScratch *g_static_ptr[MAX_DEVICES] = {};
+
+// One block: adds up the partial results of the two kernels before it, in index order.
+__global__ __launch_bounds__(FB) void k_static_finish(const RowPart *__restrict__ part, int row_blocks, const DiagPart *__restrict__ dpart,
+                                                       int dblocks, int64_t m, int64_t n, int64_t nnz, mo_feature_result *__restrict__ out)
+{
+    unsigned long long mx = 0ull, mn = ~0ull, sq = 0ull, err = 0ull, nd = 0ull, nt = 0ull;
+    for (int b = threadIdx.x; b < row_blocks; b += FB) {
+        const RowPart p = part[b];
+        mx = p.max_row > mx ? p.max_row : mx;
+        mn = p.min_row < mn ? p.min_row : mn;
+        sq += p.sum_sq;
+        err |= p.err;
+    }
+    for (int b = threadIdx.x; b < dblocks; b += FB) { nd += dpart[b].n_diag; nt += dpart[b].n_true; }
+    mx = wave_max(mx); mn = wave_min(mn); sq = wave_sum(sq); err = wave_max(err); nd = wave_sum(nd); nt = wave_sum(nt);
+    __shared__ unsigned long long s[6][FB / WAVE];
+    const int w = threadIdx.x / WAVE;
+    if (lane_id() == 0) { s[0][w] = mx; s[1][w] = mn; s[2][w] = sq; s[3][w] = err; s[4][w] = nd; s[5][w] = nt; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int q = 1; q < FB / WAVE; ++q) {
+            mx = s[0][q] > mx ? s[0][q] : mx;
+            mn = s[1][q] < mn ? s[1][q] : mn;
+            sq += s[2][q]; err |= s[3][q]; nd += s[4][q]; nt += s[5][q];
+        }
+        out->ints.m = m; out->ints.n = n; out->ints.nnz = nnz;
+        out->ints.max_row = (int64_t)mx; out->ints.min_row = (int64_t)mn;
+        out->ints.n_diag = (int64_t)nd; out->ints.n_true_diag = (int64_t)nt;
+        out->ints.sum_sq_row = sq;
+        out->status = err ? (int32_t)MO_E_CSR_INVALID : (int32_t)MO_OK;
+        out->pad = 0;
+    }
+}
+
+}  // namespace
+
+mo_status features_static(const mo_csr &a, const mo_params &p, mo_feature_result *out_dev, hipStream_t s)
+{
+    const int64_t ndiag = a.m + a.n - 1;
+    if (ndiag > STATIC_MAX_DIAGS) return MO_E_SHAPE;
+    int dev = -1;
+    MO_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return MO_E_DEVICE;
+    StaticScratch *sc = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_static_mu);
+        if (!g_static_ptr[dev]) {
+            void *ptr = nullptr;
+            MO_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            g_static_ptr[dev] = (StaticScratch *)ptr;
+        }
+        sc = g_static_ptr[dev];
+    }
+    if (!sc) return MO_E_DEVICE;
+    // the array keeps whatever the last call left (possibly one that was cut short): the counters start from zero
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, sc->hist, ndiag, 0u);
+    MO_LAUNCH_CHECK();
+    int64_t rows_per_block = (a.m + TRAV_BLOCKS - 1) / TRAV_BLOCKS;
+    rows_per_block = ((rows_per_block + TB - 1) / TB) * TB;
+    const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;
+    hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
+                       rows_per_block, sc->hist, sc->part);
+    MO_LAUNCH_CHECK();
+    const int64_t mn = a.m < a.n ? a.m : a.n;
+    const int dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
+    hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, sc->hist, ndiag,
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, sc->dpart);
+    MO_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_static_finish, dim3(1), dim3(FB), 0, s, sc->part, (int)row_blocks, sc->dpart, dblocks, a.m, a.n, a.nnz, out_dev);
+    MO_LAUNCH_CHECK();
+    return MO_OK;
+}
+
 }  // namespace mo

@@ -125,6 +125,8 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
 // The same numbers (histogram included in the counts, not handed out) with scratch that is kept between calls.
 mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hipStream_t s);
 void release_feature_cache();
+// The no-allocation variant: integers and status into caller memory, asynchronous.
+mo_status features_static(const mo_csr &a, const mo_params &p, mo_feature_result *out_dev, hipStream_t s);
 
 // ---------------------------------------------------------------- conversions (convert.hip)
 mo_status convert_impl(const mo_csr &a, mo_format fmt, const mo_params &p, const Analysis &an, mo_matrix **out, hipStream_t s);

@@ -476,25 +476,13 @@ mo_status mo_matrix_features(const mo_matrix *a, const mo_params *params, double
     unsigned long long nnz = 0;
     MO_TRY(a->dtype == MO_F32 ? features_any<float>(*a, p, &c, &nnz, (hipStream_t)stream)
                               : features_any<double>(*a, p, &c, &nnz, (hipStream_t)stream));
-    // same finalisation as mo_features (Table I), from exact integers
-    const unsigned __int128 num = (unsigned __int128)a->m * (unsigned __int128)c.sum_sq - (unsigned __int128)nnz * (unsigned __int128)nnz;
-    const double md = (double)a->m, nd = (double)a->n, zd = (double)nnz;
-    const double mm = md * md;
-    const double var = (double)num / mm;
-    out[0] = md; out[1] = nd; out[2] = zd;
-    out[3] = zd / md;
-    const double mn = md * nd;
-    out[4] = zd / mn;
-    out[5] = (double)c.max_row; out[6] = (double)c.min_row;
-    out[7] = std::sqrt(var);
-    out[8] = (double)c.n_diag; out[9] = (double)c.n_true;
-    if (ints_opt) {
-        ints_opt->m = a->m; ints_opt->n = a->n; ints_opt->nnz = (int64_t)nnz;
-        ints_opt->max_row = (int64_t)c.max_row; ints_opt->min_row = (int64_t)c.min_row;
-        ints_opt->n_diag = (int64_t)c.n_diag; ints_opt->n_true_diag = (int64_t)c.n_true;
-        ints_opt->sum_sq_row = c.sum_sq;
-    }
-    return MO_OK;
+    mo_feature_ints ints;
+    ints.m = a->m; ints.n = a->n; ints.nnz = (int64_t)nnz;
+    ints.max_row = (int64_t)c.max_row; ints.min_row = (int64_t)c.min_row;
+    ints.n_diag = (int64_t)c.n_diag; ints.n_true_diag = (int64_t)c.n_true;
+    ints.sum_sq_row = c.sum_sq;
+    if (ints_opt) *ints_opt = ints;
+    return mo_features_finalize(&ints, out);   // the same finalisation as mo_features (Table I)
 }
 
 }  // extern "C"

@@ -30,7 +30,7 @@ MO_F32, MO_F64 = 0, 1
 (MO_OK, MO_E_NULL, MO_E_SHAPE, MO_E_CSR_INVALID, MO_E_FORMAT, MO_E_DTYPE, MO_E_FILL, MO_E_ALLOC, MO_E_DEVICE,
  MO_E_MODEL, MO_E_PARAM, MO_E_IO) = range(12)
 
-EXPORTS = ("mo_default_params", "mo_features", "mo_convert", "mo_spmv", "mo_spmm", "mo_tune", "mo_tune_spmm", "mo_pick", "mo_model_load",
+EXPORTS = ("mo_default_params", "mo_features", "mo_features_finalize", "mo_features_static", "mo_convert", "mo_spmv", "mo_spmm", "mo_tune", "mo_tune_spmm", "mo_pick", "mo_model_load",
            "mo_model_free", "mo_model_info", "mo_select", "mo_default_fit_opts", "mo_model_fit", "mo_model_save", "mo_predict", "mo_mtx_read", "mo_host_free", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
            "mo_strerror", "mo_last_hip_error")
 
@@ -56,6 +56,10 @@ class mo_params(C.Structure):
 class mo_feature_ints(C.Structure):
     _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("nnz", C.c_int64), ("max_row", C.c_int64), ("min_row", C.c_int64),
                 ("n_diag", C.c_int64), ("n_true_diag", C.c_int64), ("sum_sq_row", C.c_uint64)]
+
+
+class mo_feature_result(C.Structure):
+    _fields_ = [("ints", mo_feature_ints), ("status", C.c_int32), ("pad", C.c_int32)]
 
 
 class mo_tune_opts(C.Structure):
@@ -85,6 +89,8 @@ lib.mo_last_hip_error.restype = C.c_int
 lib.mo_default_params.restype = None
 lib.mo_default_params.argtypes = [C.POINTER(mo_params)]
 lib.mo_features.argtypes = [C.POINTER(mo_csr), C.POINTER(mo_params), C.POINTER(C.c_double), C.POINTER(mo_feature_ints), C.c_void_p]
+lib.mo_features_finalize.argtypes = [C.POINTER(mo_feature_ints), C.POINTER(C.c_double)]
+lib.mo_features_static.argtypes = [C.POINTER(mo_csr), C.POINTER(mo_params), C.c_void_p, C.c_void_p]
 lib.mo_convert.argtypes = [C.POINTER(mo_csr), C.c_int, C.POINTER(mo_params), C.POINTER(C.c_void_p), C.c_void_p]
 lib.mo_switch.argtypes = [C.c_void_p, C.c_int, C.POINTER(mo_params), C.POINTER(C.c_void_p), C.c_void_p]
 lib.mo_matrix_features.argtypes = [C.c_void_p, C.POINTER(mo_params), C.POINTER(C.c_double), C.POINTER(mo_feature_ints), C.c_void_p]
@@ -247,6 +253,34 @@ def mo_features(a: Csr, params=None, stream=None):
     st = a.struct()
     _check(lib.mo_features(C.byref(st), _params(params), out, C.byref(ints), _stream_ptr(stream)), "mo_features")
     return np.array(list(out), dtype=np.float64), {k: int(getattr(ints, k)) for k, _ in mo_feature_ints._fields_}
+
+
+def mo_features_finalize(ints: dict) -> np.ndarray:
+    """The ten doubles of Table I from the integer statistics (host only)."""
+    st = mo_feature_ints(**{k: int(ints[k]) for k, _ in mo_feature_ints._fields_})
+    out = (C.c_double * 10)()
+    _check(lib.mo_features_finalize(C.byref(st), out), "mo_features_finalize")
+    return np.array(list(out), dtype=np.float64)
+
+
+STATIC_MAX_DIAGS = 4194304
+RESULT_BYTES = C.sizeof(mo_feature_result)
+
+
+def mo_features_static(a: Csr, out_dev: torch.Tensor, params=None, stream=None) -> None:
+    """Enqueue the feature kernels without allocating or synchronising; ``out_dev``: a CUDA uint8 tensor of at least
+    RESULT_BYTES bytes that receives a ``mo_feature_result``.  Decode it with ``decode_feature_result`` once the stream
+    has finished."""
+    if not (out_dev.is_cuda and out_dev.is_contiguous() and out_dev.dtype == torch.uint8 and out_dev.numel() >= RESULT_BYTES):
+        raise ValueError(f"out_dev must be a contiguous CUDA uint8 tensor of at least {RESULT_BYTES} bytes")
+    st = a.struct()
+    _check(lib.mo_features_static(C.byref(st), _params(params), out_dev.data_ptr(), _stream_ptr(stream)), "mo_features_static")
+
+
+def decode_feature_result(host_bytes) -> tuple:
+    """bytes of a mo_feature_result -> (status, ints dict)"""
+    r = mo_feature_result.from_buffer_copy(bytes(host_bytes)[:RESULT_BYTES])
+    return int(r.status), {k: int(getattr(r.ints, k)) for k, _ in mo_feature_ints._fields_}
 
 
 def mo_convert(a: Csr, fmt: int, params=None, stream=None) -> Matrix:
