@@ -7,8 +7,10 @@ run-first choice made before the timed region), then REPS = 1000 SpMVs in that f
 2 * nnz * REPS / t_step.  The one-off rows of the path (conversions, run-first tuning) and the SpMV rate of every
 format are measured in the same run and printed in the same JSON line.
 
-Workload: the 3-D 27-point stencil on a 128^3 grid in fp64 (synthetic, seeded), with
-all inputs resident in HBM before the timed region starts.
+Headline workload: the 3-D 27-point stencil on a 128^3 grid in fp64 (synthetic, seeded), with all inputs resident in
+HBM before the timed region starts.  The other large configurations (lognormal rows, banded + scatter in fp64 and
+fp32) and the small Laplacian are measured after it, each with the per-format table, the run-first and the model's
+choice, one Eq. 2 step and the oracle's error for the chosen format, under "configs" of the same line.
 """
 from __future__ import annotations
 
@@ -25,22 +27,25 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per SpMV launch from the committed rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scale
-# factors a plain 1 GiB copy gives; see profiles/spmv_all_formats_stencil27_128_f64.md).  Keyed by (config, dtype, format).
+# factors a plain 1 GiB copy gives).  Not measured by this run: constants taken from the named summary, keyed by
+# (config, dtype, format); a format whose kernels changed since the summary was made has no entry.
+TRAFFIC_SOURCE = {(2, "f64"): "profiles/spmv_all_formats_stencil27_128_f64.md", (3, "f64"): "profiles/spmv_all_formats_lognormal_f64.md",
+                  (4, "f64"): "profiles/spmv_all_formats_banded_scatter_f64.md", (4, "f32"): "profiles/spmv_all_formats_banded_scatter_f32.md"}
 MEASURED_TRAFFIC = {
     (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 765.5e6, (2, "f64", "ELL"): 710.2e6,
     (2, "f64", "COO"): 959.4e6 + 9.1e6,
-    # profiles/spmv_all_formats_banded_scatter_f64.md: the 1.17 M scattered entries gather one 128-byte line of x each
     (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 736.2e6, (4, "f64", "ELL"): 784.5e6, (4, "f64", "HYB"): 684.9e6,
     (4, "f64", "COO"): 835.6e6 + 5.9e6,
-    # profiles/spmv_all_formats_banded_scatter_f32.md
     (4, "f32", "HDC"): 331.4e6, (4, "f32", "HYB"): 482.6e6, (4, "f32", "CSR"): 502.8e6, (4, "f32", "ELL"): 565.9e6,
     (4, "f32", "COO"): 640.4e6 + 5.8e6,
-    # profiles/spmv_all_formats_lognormal_f64.md: 16.8 M random gathers of x miss L2; bytes counted at the L2 boundary
     (3, "f64", "CSR"): 1333.9e6, (3, "f64", "HYB"): 659.5e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
 }
 REPS = 1000
 LLC_BYTES = 256 << 20     # last-level (Infinity) cache of the MI355X
 MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_forest.bin")
+NAMES = {1: "2-D 5-point Laplacian 64x64", 2: "3-D 27-point stencil 128^3", 3: "lognormal rows n=1048576",
+         4: "banded+scatter n=4194304"}
+EXTRA_DEFAULT = "3:f64,4:f64,4:f32,1:f64"
 
 
 def algorithmic_bytes(fmt, v, sv):
@@ -60,14 +65,207 @@ def algorithmic_bytes(fmt, v, sv):
     return v.nd * m * sv + v.nd * 4 + v.nnz_csr * (sv + 4) + (m + 1) * 4 + xy
 
 
+class Workload:
+    """One configuration resident on the GPU: CSR arrays, x, y, and what was measured on it."""
+
+    def __init__(self, config, dtype, mods):
+        np, torch, mo, synth = mods
+        self.config, self.dtype = config, dtype
+        self.np_dtype = np.float64 if dtype == "f64" else np.float32
+        self.sv = 8 if dtype == "f64" else 4
+        self.m, self.n, self.rp, self.ci, v = synth.config(config)
+        self.v = np.asarray(v, dtype=self.np_dtype)
+        self.nnz = int(self.rp[-1])
+        self.x_host = synth.make_x(self.n, synth.BASE_SEED + config).astype(self.np_dtype)
+        self.a = mo.Csr(self.m, self.n, self.rp, self.ci, self.v)
+        self.x = torch.as_tensor(self.x_host).cuda()
+        self.y = torch.empty(self.m, dtype=self.x.dtype, device="cuda")
+        self.handles = {}
+
+
+def time_formats(w, args, mods, launches, batches, convert_repeats):
+    """Convert to every feasible format and time mo_spmv in each -> (per_format, convert_ms)."""
+    np, torch, mo, synth = mods
+    stream = torch.cuda.current_stream()
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731  (events on the stream the kernels are launched on)
+    per_format, convert_ms = {}, {}
+    for fmt in range(6):
+        name = mo.FORMAT_NAMES[fmt]
+        t0 = time.perf_counter()
+        try:
+            h = mo.mo_convert(w.a, fmt)
+        except mo.MoError as e:
+            if e.status != mo.MO_E_FILL:
+                raise
+            per_format[name] = None
+            continue
+        torch.cuda.synchronize()
+        t_cold = (time.perf_counter() - t0) * 1e3
+        # again with the allocator warm (the first repeat still has to get fresh blocks from the device, because `h`
+        # holds the ones of the first call; after it is freed the caching allocator serves the same blocks again);
+        # bytes = CSR arrays read + arrays of the format written (x and y taken out)
+        t_warm = math.inf
+        for rep in range(convert_repeats):
+            t0 = time.perf_counter()
+            h2 = mo.mo_convert(w.a, fmt)
+            torch.cuda.synchronize()
+            if rep > 0:
+                t_warm = min(t_warm, (time.perf_counter() - t0) * 1e3)
+            h2.free()
+        b = algorithmic_bytes(fmt, h.view(), w.sv)
+        csr_bytes = w.nnz * (w.sv + 4) + (w.m + 1) * 4
+        out_bytes = 0 if fmt == 1 else b - (w.n + w.m) * w.sv
+        convert_ms[name] = {"first_call": round(t_cold, 3)}
+        if math.isfinite(t_warm):
+            convert_ms[name].update(warm=round(t_warm, 3), gbs=round((csr_bytes + out_bytes) / t_warm / 1e6, 1))
+        # A format whose arrays fit the last-level cache is timed over several copies in rotation (own device arrays
+        # each, same contents), so that its value / index streams are read from HBM as they are at the other sizes.
+        # A CSR handle borrows the caller's arrays, so its copies are handles over cloned CSR arrays.
+        ncopies = args.copies if args.copies > 0 else (1 if b >= 1.25 * LLC_BYTES else min(4, math.ceil(2 * LLC_BYTES / b)))
+        hs = [h]
+        for _ in range(ncopies - 1):
+            src = w.a if fmt != mo.MO_CSR else mo.Csr(w.m, w.n, w.a.row_ptr.clone(), w.a.col_idx.clone(), w.a.val.clone())
+            hs.append(mo.mo_convert(src, fmt))
+        w.handles[fmt] = hs
+        for i in range(10):
+            mo.mo_spmv(hs[i % ncopies], w.x, w.y)
+        best = math.inf
+        for _ in range(batches):
+            e0, e1 = ev(), ev()
+            e0.record(stream)
+            for i in range(launches):
+                mo.mo_spmv(hs[i % ncopies], w.x, w.y)
+            e1.record(stream)
+            e1.synchronize()
+            best = min(best, e0.elapsed_time(e1) / launches)
+        per_format[name] = {"us": round(best * 1e3, 2), "gflops": round(2.0 * w.nnz / best / 1e6, 1),
+                            "gbs": round(b / best / 1e6, 1), "frac_hbm": round(b / best / 1e6 / HBM_PEAK_GBS, 4),
+                            "alg_mbytes": round(b / 1e6, 1), "copies_in_rotation": ncopies, "kernels": h.kernels(),
+                            "hbm_traffic_mbytes": (round(MEASURED_TRAFFIC[(w.config, w.dtype, name)] / 1e6, 1)
+                                                   if (w.config, w.dtype, name) in MEASURED_TRAFFIC else None)}
+    return per_format, convert_ms
+
+
+def choose_format(w, per_format, feats, model, mods):
+    """-> (run-first format, model's format or None, format used, prediction time in us or None)"""
+    np, torch, mo, synth = mods
+    ms_vec = [per_format[nm]["us"] / 1e3 if per_format[nm] else float("nan") for nm in mo.FORMAT_NAMES]
+    run_first = mo.mo_pick(ms_vec)
+    if model is None:
+        return run_first, None, run_first, None
+    t0 = time.perf_counter()
+    for _ in range(1000):
+        predicted = mo.mo_select(model, feats)
+    t_pred_us = (time.perf_counter() - t0) * 1e3
+    return run_first, predicted, (predicted if predicted in w.handles else run_first), t_pred_us
+
+
+def tuned_step(w, model, chosen, mods, timed_events=None):
+    """Section VII-E's unit of work: features, selection, REPS SpMVs in the selected format."""
+    np, torch, mo, synth = mods
+    stream = torch.cuda.current_stream()
+    f, _ = mo.mo_features(w.a)
+    fmt = mo.mo_select(model, f) if model is not None else chosen
+    hh = w.handles.get(fmt, w.handles[chosen])
+    if timed_events is not None:
+        timed_events[0].record(stream)
+    for i in range(REPS):
+        mo.mo_spmv(hh[i % len(hh)], w.x, w.y)
+    if timed_events is not None:
+        timed_events[1].record(stream)
+
+
+def features_timed(w, mods, repeats=5):
+    np, torch, mo, synth = mods
+    t0 = time.perf_counter()
+    feats, ints = mo.mo_features(w.a)
+    torch.cuda.synchronize()
+    t_first = (time.perf_counter() - t0) * 1e3
+    fe = []
+    for _ in range(repeats):
+        t0 = time.perf_counter()
+        feats, ints = mo.mo_features(w.a)
+        fe.append((time.perf_counter() - t0) * 1e3)
+    return feats, min(fe), t_first
+
+
+def oracle_check(w, h, mods):
+    """The oracle's SpMV on the whole matrix (one thread) against mo_spmv of handle h -> (err, zeros_ok, y_ref time)."""
+    np, torch, mo, synth = mods
+    from oracle import ref
+    ti, tj, ta = ref.csr_to_triplets(w.rp, w.ci, w.v.astype(np.float64))
+    xo = w.x_host.astype(np.float64)
+    t0 = time.perf_counter()
+    y1, mag = ref.spmv(w.m, w.n, ti, tj, ta, xo)
+    t_1 = time.perf_counter() - t0
+    w.y.fill_(float("nan"))
+    mo.mo_spmv(h, w.x, w.y)
+    torch.cuda.synchronize()
+    err, zeros_ok = ref.spmv_error(w.y.cpu().numpy(), y1, mag)
+    return err, zeros_ok, t_1, (ti, tj, ta, xo)
+
+
+def extra_config(config, dtype, model, args, mods):
+    """A configuration beside the headline one: per-format table, both tuners' choices, one Eq. 2 step, oracle error."""
+    np, torch, mo, synth = mods
+    w = Workload(config, dtype, mods)
+    small = config == 1
+    feats, t_fe, _ = features_timed(w, mods, repeats=3)
+    per_format, convert_ms = time_formats(w, args, mods, launches=100, batches=3, convert_repeats=2)
+    if small:
+        # a launch-bound matrix: the Python call costs more than the kernel, so the times come from the library's own
+        # loop (mo_tune: 1000 back-to-back launches per format between two events)
+        _, tune_ms, _ = mo.mo_tune(w.a, warmups=20, reps=1000)
+        for f, nm_ in enumerate(mo.FORMAT_NAMES):
+            if per_format[nm_] is not None:
+                per_format[nm_]["us"] = round(float(tune_ms[f]) * 1e3, 2)
+    run_first, predicted, chosen, t_pred_us = choose_format(w, per_format, feats, model, mods)
+    tuned_step(w, model, chosen, mods)                  # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tuned_step(w, model, chosen, mods)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) * 1e3
+    nm = mo.FORMAT_NAMES
+    csr_us, sel_us, rf_us = per_format["CSR"]["us"], per_format[nm[chosen]]["us"], per_format[nm[run_first]]["us"]
+    out = {"workload": f"{NAMES[config]}, {dtype}, m={w.m}, nnz={w.nnz}", "dtype": dtype,
+           "per_format": per_format if not small else {k: (None if v is None else {"us": v["us"], "kernels": v["kernels"]}) for k, v in per_format.items()},
+           "run_first_format": nm[run_first], "model_predicted_format": nm[predicted] if predicted is not None else None,
+           "selected_format": nm[chosen], "selected_over_run_first_time": round(sel_us / rf_us, 3),
+           "speedup_vs_csr_spmv_only": round(csr_us / sel_us, 3), "speedup_vs_csr_run_first": round(csr_us / rf_us, 3),
+           "speedup_vs_csr_eq2": round(csr_us * 1e-3 * REPS / t_step, 3), "ms_per_step": round(t_step, 3),
+           "t_fe_ms": round(t_fe, 3), "t_pred_us": round(t_pred_us, 3) if t_pred_us is not None else None,
+           "tuner_cost_in_csr_spmv": round((t_fe + (t_pred_us or 0.0) * 1e-3) / (csr_us * 1e-3), 1),
+           "convert_ms": {k: v.get("warm", v["first_call"]) for k, v in convert_ms.items()},
+           "traffic_source": TRAFFIC_SOURCE.get((config, dtype))}
+    if not small:
+        best = per_format[nm[run_first]]
+        out["best_format_roofline"] = {"format": nm[run_first], "kernels": best["kernels"], "frac": best["frac_hbm"], "achieved": best["gbs"],
+                                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "traffic": MEASURED_TRAFFIC.get((config, dtype, nm[run_first]))}
+    if not args.no_cpu_baseline:
+        err, zeros_ok, _, _ = oracle_check(w, w.handles[chosen][0], mods)
+        out["gpu_vs_oracle_max_rel_err"] = err
+        out["zeros_ok"] = zeros_ok
+    for hs in w.handles.values():
+        for h in hs:
+            h.free()
+    del w
+    torch.cuda.empty_cache()
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=2, help="2 = 27-point stencil 128^3 (default), 4 = banded+scatter, 3 = lognormal")
+    ap.add_argument("--config", type=int, default=2, help="headline workload: 2 = 27-point stencil 128^3 (default), 4 = banded+scatter, 3 = lognormal")
     ap.add_argument("--dtype", default="f64", choices=["f64", "f32"])
+    ap.add_argument("--extra", default="auto",
+                    help=f"configurations measured after the headline one, as config:dtype,...; 'auto' = {EXTRA_DEFAULT} when the "
+                         "headline is the default one, none otherwise; 'none' = none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-spmm", action="store_true", help="skip the 8-right-hand-side product of the headline workload")
     ap.add_argument("--copies", type=int, default=0,
                     help="device copies of each format the SpMV launches rotate over; 0 = as many as it takes for their "
                          "bytes to exceed twice the 256 MB last-level cache (at most 4), so that the streams come from HBM")
@@ -82,23 +280,14 @@ def main() -> int:
     import torch
 
     from paper_2303_05098_amd import mo, synth
+    mods = (np, torch, mo, synth)
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 3
     torch.cuda.set_device(0)
-    np_dtype = np.float64 if args.dtype == "f64" else np.float32
-    sv = 8 if args.dtype == "f64" else 4
-    names = {1: "2-D 5-point Laplacian 64x64", 2: "3-D 27-point stencil 128^3", 3: "lognormal rows n=1048576",
-             4: "banded+scatter n=4194304"}
-    m, n, rp, ci, v = synth.config(args.config)
-    nnz = int(rp[-1])
-    x_host = synth.make_x(n, synth.BASE_SEED + args.config).astype(np_dtype)
-    a = mo.Csr(m, n, rp, ci, np.asarray(v, dtype=np_dtype))
-    x = torch.as_tensor(x_host).cuda()
-    y = torch.empty(m, dtype=x.dtype, device="cuda")
     stream = torch.cuda.current_stream()
-    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731  (events on the stream the kernels are launched on)
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
 
     if args.calibrate:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
@@ -109,101 +298,26 @@ def main() -> int:
         del src, dst
         torch.cuda.empty_cache()
 
-    # ---- one-off rows of the path: features, conversions, per-format SpMV rate ------------------------------------
-    t0 = time.perf_counter()
-    feats, ints = mo.mo_features(a)
-    torch.cuda.synchronize()
-    t_fe_first = (time.perf_counter() - t0) * 1e3
-    fe = []
-    for _ in range(5):
-        t0 = time.perf_counter()
-        feats, ints = mo.mo_features(a)
-        fe.append((time.perf_counter() - t0) * 1e3)
-    t_fe = min(fe)
-
-    handles, per_format, convert_ms = {}, {}, {}
-    for fmt in range(6):
-        t0 = time.perf_counter()
-        try:
-            h = mo.mo_convert(a, fmt)
-        except mo.MoError as e:
-            if e.status != mo.MO_E_FILL:
-                raise
-            per_format[mo.FORMAT_NAMES[fmt]] = None
-            continue
-        torch.cuda.synchronize()
-        t_cold = (time.perf_counter() - t0) * 1e3
-        # again with the allocator warm (the first repeat still has to get fresh blocks from the device, because `h`
-        # holds the ones of the first call; after it is freed the caching allocator serves the same blocks again);
-        # bytes = CSR arrays read + arrays of the format written (x and y taken out)
-        t_warm = math.inf
-        for rep in range(4):
-            t0 = time.perf_counter()
-            h2 = mo.mo_convert(a, fmt)
-            torch.cuda.synchronize()
-            if rep > 0:
-                t_warm = min(t_warm, (time.perf_counter() - t0) * 1e3)
-            h2.free()
-        csr_bytes = nnz * (sv + 4) + (m + 1) * 4
-        out_bytes = 0 if fmt == 1 else algorithmic_bytes(fmt, h.view(), sv) - (n + m) * sv
-        convert_ms[mo.FORMAT_NAMES[fmt]] = {"first_call": round(t_cold, 3), "warm": round(t_warm, 3),
-                                            "gbs": round((csr_bytes + out_bytes) / t_warm / 1e6, 1)}
-        # A format whose arrays fit the last-level cache is timed over several copies in rotation (own device arrays
-        # each, same contents), so that its value / index streams are read from HBM as they are at the other sizes.
-        b = algorithmic_bytes(fmt, h.view(), sv)
-        ncopies = args.copies if args.copies > 0 else (1 if b >= 1.25 * LLC_BYTES else min(4, math.ceil(2 * LLC_BYTES / b)))
-        hs = [h] + [mo.mo_convert(a, fmt) for _ in range(ncopies - 1)]
-        handles[fmt] = hs
-        for i in range(10):
-            mo.mo_spmv(hs[i % ncopies], x, y)
-        best = math.inf
-        for _ in range(5):
-            e0, e1 = ev(), ev()
-            e0.record(stream)
-            for i in range(200):
-                mo.mo_spmv(hs[i % ncopies], x, y)
-            e1.record(stream)
-            e1.synchronize()
-            best = min(best, e0.elapsed_time(e1) / 200.0)
-        per_format[mo.FORMAT_NAMES[fmt]] = {"us": round(best * 1e3, 2), "gflops": round(2.0 * nnz / best / 1e6, 1),
-                                            "gbs": round(b / best / 1e6, 1), "frac_hbm": round(b / best / 1e6 / HBM_PEAK_GBS, 4),
-                                            "alg_mbytes": round(b / 1e6, 1), "copies_in_rotation": ncopies}
-
-    # ---- format choice ----------------------------------------------------------------------------------------------
-    ms_vec = [per_format[nm]["us"] / 1e3 if per_format[nm] else float("nan") for nm in mo.FORMAT_NAMES]
-    run_first = mo.mo_pick(ms_vec)
     model = mo.mo_model_load(MODEL_PATH) if os.path.exists(MODEL_PATH) else None
-    if model is not None:
-        t0 = time.perf_counter()
-        for _ in range(1000):
-            predicted = mo.mo_select(model, feats)
-        t_pred_us = (time.perf_counter() - t0) * 1e3
-        tuner = "random_forest" if model.info()[0] > 1 else "decision_tree"
-        chosen = predicted if predicted in handles else run_first
-    else:
-        predicted, t_pred_us, tuner, chosen = None, None, "run_first", run_first
-    hs = handles[chosen]
+    tuner = "run_first" if model is None else ("random_forest" if model.info()[0] > 1 else "decision_tree")
+
+    # ---- headline workload: one-off rows of the path (features, conversions, per-format SpMV rate) -------------------
+    w = Workload(args.config, args.dtype, mods)
+    m, n, nnz, sv = w.m, w.n, w.nnz, w.sv
+    feats, t_fe, t_fe_first = features_timed(w, mods)
+    per_format, convert_ms = time_formats(w, args, mods, launches=200, batches=5, convert_repeats=4)
+    run_first, predicted, chosen, t_pred_us = choose_format(w, per_format, feats, model, mods)
+    hs = w.handles[chosen]
     h = hs[0]
 
     # ---- timed region: K steps of (features + select + REPS SpMVs in the chosen format) --------------------------
-    def step(timed_events=None):
-        f, _ = mo.mo_features(a)
-        fmt = mo.mo_select(model, f) if model is not None else chosen
-        hh = handles.get(fmt, hs)
-        if timed_events is not None:
-            timed_events[0].record(stream)
-        for i in range(REPS):
-            mo.mo_spmv(hh[i % len(hh)], x, y)
-        if timed_events is not None:
-            timed_events[1].record(stream)
-
     for _ in range(args.warmup):
-        step()
+        tuned_step(w, model, chosen, mods)
     torch.cuda.synchronize()
     kernel_events = [(ev(), ev()) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(kernel_events[k])
+        tuned_step(w, model, chosen, mods, kernel_events[k])
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t0
     ms_per_step = t_total * 1e3 / args.steps
@@ -212,78 +326,79 @@ def main() -> int:
 
     alg = algorithmic_bytes(chosen, h.view(), sv)
     achieved = alg / (spmv_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": {2: "k_dia_lds", 5: "k_dia_lds(HDC)", 1: "k_csr_tiled / k_csr_split", 3: "k_ell", 0: "k_coo_tile", 4: "k_ell+k_coo_tile"}[chosen],
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC.get((args.config, args.dtype, mo.FORMAT_NAMES[chosen])), "algorithmic_bytes_per_launch": alg, "us_per_launch": round(spmv_ms * 1e3, 2)}
+    tkey = (args.config, args.dtype, mo.FORMAT_NAMES[chosen])
+    roofline = {"bound": "hbm", "kernel": h.kernels(), "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(tkey),
+                "traffic_source": (TRAFFIC_SOURCE.get((args.config, args.dtype), None) if tkey in MEASURED_TRAFFIC else None),
+                "traffic_note": "HBM bytes per launch from the named rocprofv3 counter summary (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0); a constant, not measured by this run",
+                "algorithmic_bytes_per_launch": alg, "us_per_launch": round(spmv_ms * 1e3, 2)}
 
     # ---- run-first tuner (timed once; conversions included in its wall time) -------------------------------------------
     t0 = time.perf_counter()
-    tune_best, tune_ms, _ = mo.mo_tune(a, warmups=5, reps=50)
+    tune_best, tune_ms, _ = mo.mo_tune(w.a, warmups=5, reps=50)
     t_tune = (time.perf_counter() - t0) * 1e3
 
     # ---- the second operation: Y = A X with 8 right-hand sides, every format (not part of the timed step) ----------
-    SPMM_K = 8
-    xk = torch.as_tensor(np.ascontiguousarray(synth.uniform_pm1(synth.BASE_SEED + 40, 0, np.arange(n * SPMM_K)).reshape(n, SPMM_K),
-                                              dtype=np_dtype)).cuda()
-    yk = torch.empty((m, SPMM_K), dtype=xk.dtype, device="cuda")
-    spmm = {}
-    for fmt, hl in handles.items():
-        hh = hl[0]
-        for _ in range(3):
-            mo.mo_spmm(hh, xk, yk)
-        tb = math.inf
-        for _ in range(3):
-            e0, e1 = ev(), ev()
-            e0.record(stream)
-            for _ in range(20):
+    spmm = None
+    if not args.no_spmm:
+        SPMM_K = 8
+        xk = torch.as_tensor(np.ascontiguousarray(synth.uniform_pm1(synth.BASE_SEED + 40, 0, np.arange(n * SPMM_K)).reshape(n, SPMM_K),
+                                                  dtype=w.np_dtype)).cuda()
+        yk = torch.empty((m, SPMM_K), dtype=xk.dtype, device="cuda")
+        spmm = {}
+        for fmt, hl in w.handles.items():
+            hh = hl[0]
+            for _ in range(3):
                 mo.mo_spmm(hh, xk, yk)
-            e1.record(stream)
-            e1.synchronize()
-            tb = min(tb, e0.elapsed_time(e1) / 20.0)
-        bk = algorithmic_bytes(fmt, hh.view(), sv) + (SPMM_K - 1) * (n + m) * sv
-        spmm[mo.FORMAT_NAMES[fmt]] = {"us": round(tb * 1e3, 1), "gflops": round(2.0 * nnz * SPMM_K / tb / 1e6, 1),
-                                      "frac_hbm": round(bk / tb / 1e6 / HBM_PEAK_GBS, 4)}
-    del xk, yk
+            tb = math.inf
+            for _ in range(3):
+                e0, e1 = ev(), ev()
+                e0.record(stream)
+                for _ in range(20):
+                    mo.mo_spmm(hh, xk, yk)
+                e1.record(stream)
+                e1.synchronize()
+                tb = min(tb, e0.elapsed_time(e1) / 20.0)
+            bk = algorithmic_bytes(fmt, hh.view(), sv) + (SPMM_K - 1) * (n + m) * sv
+            spmm[mo.FORMAT_NAMES[fmt]] = {"us": round(tb * 1e3, 1), "gflops": round(2.0 * nnz * SPMM_K / tb / 1e6, 1),
+                                          "frac_hbm": round(bk / tb / 1e6 / HBM_PEAK_GBS, 4)}
+        del xk, yk
 
     # ---- CPU baseline: the oracle, as it stands, on this host -------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import ref
-        ti, tj, ta = ref.csr_to_triplets(rp, ci, np.asarray(v, dtype=np_dtype).astype(np.float64))
-        xo = x_host.astype(np.float64)
-        cores = len(os.sched_getaffinity(0))
-        cores = min(cores, 16)
-        t0 = time.perf_counter()
-        y1, mag = ref.spmv(m, n, ti, tj, ta, xo)
-        t_1 = time.perf_counter() - t0
+        err, zeros_ok, t_1, (ti, tj, ta, xo) = oracle_check(w, h, mods)
+        avail = len(os.sched_getaffinity(0))
+        cores = min(avail, 16)                   # the GPU machine's CPU share for one GPU
         reps_mt, t_mt = 0, 0.0
         while t_mt < 8.0 and reps_mt < 50:
             t0 = time.perf_counter()
-            ymt = ref.spmv_rowsorted_mt(m, ti, tj, ta, xo, cores)
+            ref.spmv_rowsorted_mt(m, ti, tj, ta, xo, cores)
             t_mt += time.perf_counter() - t0
             reps_mt += 1
-        # the GPU result of the chosen format is checked against the oracle while we are here
-        mo.mo_spmv(h, x, y)
-        torch.cuda.synchronize()
-        err, zeros_ok = ref.spmv_error(y.cpu().numpy(), y1, mag)
         cpu_model = "unknown"
         try:
             with open("/proc/cpuinfo") as fh:
                 cpu_model = next((ln.split(":", 1)[1].strip() for ln in fh if ln.startswith("model name")), cpu_model)
         except OSError:
             pass
-        cpu = {"value": round(2.0 * nnz / (t_mt / reps_mt) / 1e9, 3), "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
-               "sample": f"{reps_mt} full SpMVs of the workload matrix, long-double COO-triplet loop split over {cores} threads by row range",
+        sample = f"{reps_mt} full SpMVs of the workload matrix, long-double COO-triplet loop split over {cores} threads by row range"
+        if avail > cores:
+            sample += f" ({avail} hardware threads visible, capped at the {cores} that one GPU's share of the host allows)"
+        cpu = {"value": round(2.0 * nnz / (t_mt / reps_mt) / 1e9, 3), "unit": "GFLOP/s", "cores": cores, "kind": "oracle", "sample": sample,
                "single_thread_gflops": round(2.0 * nnz / t_1 / 1e9, 3), "cpu_model": cpu_model, "gpu_vs_oracle_max_rel_err": err, "zeros_ok": zeros_ok}
+        del ti, tj, ta, xo
 
     csr_us = per_format["CSR"]["us"]
     best_us = per_format[mo.FORMAT_NAMES[chosen]]["us"]
+    rf_us = per_format[mo.FORMAT_NAMES[run_first]]["us"]
     out = {
         "metric": "tuned SpMV GFLOP/s (features + format selection + 1000 SpMVs in the selected format, Eq. 2 form)",
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"{names[args.config]}, {args.dtype}, m={m}, nnz={nnz}", "spmv_reps_per_step": REPS, "tuner": tuner,
+        "config": {"workload": f"{NAMES[args.config]}, {args.dtype}, m={m}, nnz={nnz}", "spmv_reps_per_step": REPS, "tuner": tuner,
                    "matrix_copies_in_rotation": len(hs)},
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -291,6 +406,7 @@ def main() -> int:
         "selected_format": mo.FORMAT_NAMES[chosen],
         "run_first_format": mo.FORMAT_NAMES[run_first],
         "model_predicted_format": mo.FORMAT_NAMES[predicted] if predicted is not None else None,
+        "selected_over_run_first_time": round(best_us / rf_us, 3),
         "speedup_vs_csr_spmv_only": round(csr_us / best_us, 3),
         "speedup_vs_csr_eq2": round(csr_us * 1e-3 * REPS / ms_per_step, 3),
         "t_fe_ms": round(t_fe, 3), "t_fe_first_call_ms": round(t_fe_first, 3),
@@ -303,6 +419,21 @@ def main() -> int:
                     "ms_per_rep": [None if math.isnan(t) else round(float(t), 5) for t in tune_ms]},
         "features": [float(f) for f in feats],
     }
+
+    # ---- the other configurations -----------------------------------------------------------------------------------
+    for hl in w.handles.values():
+        for hh in hl:
+            hh.free()
+    del w, h, hs
+    torch.cuda.empty_cache()
+    extra = args.extra
+    if extra == "auto":
+        extra = EXTRA_DEFAULT if (args.config, args.dtype) == (2, "f64") else "none"
+    if extra != "none":
+        out["configs"] = []
+        for item in extra.split(","):
+            c, dt = item.split(":")
+            out["configs"].append(extra_config(int(c), dt, model, args, mods))
     print(json.dumps(out))
     return 0
 

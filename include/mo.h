@@ -159,6 +159,10 @@ mo_status mo_convert(const mo_csr *a, mo_format fmt, const mo_params *params, mo
  * used by its kernels, so two mo_spmv calls on the SAME handle must not run concurrently on different streams. */
 mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream);
 
+/* Infrastructure, not in the paper: the names of the kernels mo_spmv enqueues for this handle, joined by '+', as a
+ * NUL-terminated string in buf (host, cap bytes; MO_E_PARAM when it does not fit).  For benchmark and profile reports. */
+mo_status mo_spmv_kernels(const mo_matrix *a, char *buf, size_t cap);
+
 /* Run-first tuner (Section VI-A): for every format that is feasible, convert, run `warmups` untimed and `reps`
  * timed SpMVs back to back between two events, free; best = format with the smallest time per repetition
  * (Section VII-A), ties to the lowest id.  ms_per_rep[f] is NaN for an infeasible format.  convert_ms[f]
@@ -177,7 +181,8 @@ mo_status mo_spmm(const mo_matrix *a, const void *x, void *y, int32_t k, void *s
 mo_status mo_tune_spmm(const mo_csr *a, int32_t k, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
                        double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream);
 
-/* Pure host: index of the smallest non-NaN entry, ties to the lowest id; MO_E_PARAM if all are NaN. */
+/* Pure host: the rule by which the run-first tuner and the training labels name the best format (Section VII-A: the
+ * format with the minimum runtime): index of the smallest non-NaN entry, ties to the lowest id; MO_E_PARAM if all are NaN. */
 mo_status mo_pick(const double ms[MO_NUM_FORMATS], mo_format *best);
 
 /* Model file -> forest (Section III-B: the model is loaded from a file named at run time).  Binary,
@@ -187,6 +192,7 @@ mo_status mo_pick(const double ms[MO_NUM_FORMATS], mo_format *best);
  * larger index than their parent (so walks terminate); leaves carry a class in [0, 6). */
 mo_status mo_model_load(const char *path, mo_model **out);
 void mo_model_free(mo_model *model);
+/* Infrastructure, not in the paper: number of trees and total number of nodes of a loaded model. */
 mo_status mo_model_info(const mo_model *model, int32_t *n_trees, int32_t *n_nodes_total);
 
 /* Pure host (Section VI-A): walk every tree from its root (left iff features[f] <= threshold), one vote per
@@ -248,10 +254,12 @@ mo_status mo_mtx_read(const char *path, int64_t *m, int64_t *n, int64_t *nnz, in
                       double **val);
 void mo_host_free(void *p);
 
+/* Infrastructure, not in the paper: the arrays a handle holds, laid out as Section II-B defines each format (see
+ * mo_matrix_view), so that tests can compare them element by element; and the release of a handle. */
 mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out);
 void mo_matrix_free(mo_matrix *a);
 
-/* Install the device allocator used for handles and scratch.  alloc returns a device pointer aligned to at
+/* Infrastructure, not in the paper.  Install the device allocator used for handles and scratch.  alloc returns a device pointer aligned to at
  * least 256 bytes or NULL; free_ releases it.  Both receive the stream of the calling entry point.  NULL, NULL
  * restores the default (hipMalloc / hipFree).  Not thread-safe against concurrent library calls. */
 mo_status mo_set_allocator(void *(*alloc)(size_t bytes, void *stream, void *user),

@@ -3,7 +3,9 @@
 
 #include <chrono>
 #include <cmath>
+#include <cstring>
 #include <limits>
+#include <string>
 
 namespace mo {
 
@@ -29,6 +31,18 @@ void dev_free(void *p, hipStream_t s)
     if (!p) return;
     if (g_free) { g_free(p, (void *)s, g_user); return; }
     (void)hipFree(p);
+}
+
+// x[i] = a fixed pseudo-random value in [-1, 1) (integer hash of i).
+template <typename T>
+__global__ void k_fill_operand(T *__restrict__ p, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint64_t z = ((uint64_t)i + 1u) * 0x9E3779B97F4A7C15ull;
+        z ^= z >> 31; z *= 0xBF58476D1CE4E5B9ull; z ^= z >> 29;
+        p[i] = (T)((double)(z >> 11) * (2.0 / 9007199254740992.0) - 1.0);
+    }
 }
 
 }  // namespace mo
@@ -136,11 +150,15 @@ mo_status mo_convert(const mo_csr *a, mo_format fmt, const mo_params *params, mo
     mo_params p;
     MO_TRY(check_params(params, &p));
     hipStream_t s = (hipStream_t)stream;
-    Scratch scr(s);
-    Analysis an;
-    const bool want_hist = (fmt == MO_DIA || fmt == MO_HDC);
-    MO_TRY(analyse(*a, p, want_hist, &an, scr, s));
-    return convert_impl(*a, fmt, p, an, out, s);
+    const mo_status rc = no_throw([&]() -> mo_status {
+        Scratch scr(s);
+        Analysis an;
+        const bool want_hist = (fmt == MO_DIA || fmt == MO_HDC);
+        MO_TRY(analyse(*a, p, want_hist, &an, scr, s));
+        return convert_impl(*a, fmt, p, an, out, s);
+    });
+    if (rc != MO_OK) *out = nullptr;
+    return rc;
 }
 
 mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
@@ -163,6 +181,41 @@ mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
         return a->nnz_csr > 0 ? spmv_csr(*a, x, y, true, s) : MO_OK;
     }
     return MO_E_FORMAT;
+}
+
+// The kernels mo_spmv enqueues for a handle, by the same conditions as the dispatch above and in the launchers.
+static const char *csr_kernel(const mo_matrix &a) { return a.csr_split ? "k_csr_split+k_coo_fixup" : "k_csr_tiled"; }
+static const char *dia_kernel(const mo_matrix &a, bool hdc) { return a.dia_block ? "k_dia_lds" : (hdc ? "k_hdc_fused" : "k_dia"); }
+
+mo_status mo_spmv_kernels(const mo_matrix *a, char *buf, size_t cap)
+{
+    if (!a || !buf || cap == 0) return MO_E_NULL;
+    std::string s;
+    switch (a->fmt) {
+    case MO_COO:
+        if (!a->coo_every_row) s += "k_zero+";
+        s += a->coo_tiles > 1 ? "k_coo_tile+k_coo_fixup" : "k_coo_tile";
+        break;
+    case MO_CSR: s = csr_kernel(*a); break;
+    case MO_DIA: s = dia_kernel(*a, false); break;
+    case MO_ELL: s = (a->m <= ELL_SPLIT_MAX_ROWS && a->k >= ELL_SPLIT_MIN_K) ? "k_ell_split" : "k_ell"; break;
+    case MO_HYB:
+        if (a->nnz_coo > 0 && a->hyb_max_surplus <= HYB_FUSED_MAX_SURPLUS && a->coo_rp) s = "k_ell_hyb";
+        else {
+            s = (a->m <= ELL_SPLIT_MAX_ROWS && a->k >= ELL_SPLIT_MIN_K) ? "k_ell_split" : "k_ell";
+            if (a->nnz_coo > 0) s += a->coo_tiles > 1 ? "+k_coo_tile+k_coo_fixup" : "+k_coo_tile";
+        }
+        break;
+    case MO_HDC:
+        if (a->nd == 0) s = csr_kernel(*a);
+        else if (a->csr_max_row <= HDC_FUSED_MAX_ROW) s = dia_kernel(*a, true);
+        else { s = dia_kernel(*a, false); if (a->nnz_csr > 0) { s += "+"; s += csr_kernel(*a); } }
+        break;
+    default: return MO_E_FORMAT;
+    }
+    if (s.size() + 1 > cap) return MO_E_PARAM;
+    std::memcpy(buf, s.c_str(), s.size() + 1);
+    return MO_OK;
 }
 
 mo_status mo_pick(const double ms[MO_NUM_FORMATS], mo_format *best)
@@ -210,8 +263,11 @@ static mo_status tune_impl(const mo_csr *a, int k, const mo_params *params, cons
     void *x = scr.get((size_t)(a->n * width) * sv);
     void *y = scr.get((size_t)(a->m * width) * sv);
     if (!x || !y) return MO_E_ALLOC;
-    // x = 0 is as good as any vector for timing: no kernel here branches on values
-    MO_TRY(fill_zero(x, a->n * width, a->dtype, s));
+    // a dense, sign-mixed operand of ordinary magnitude, the same on every call: the timed kernels then toggle the data
+    // paths and multipliers as they do on real vectors
+    if (a->dtype == MO_F32) hipLaunchKernelGGL(k_fill_operand<float>, dim3(1024), dim3(256), 0, s, (float *)x, a->n * width);
+    else hipLaunchKernelGGL(k_fill_operand<double>, dim3(1024), dim3(256), 0, s, (double *)x, a->n * width);
+    MO_LAUNCH_CHECK();
     hipEvent_t e0, e1;
     MO_HIP(hipEventCreate(&e0));
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return MO_E_DEVICE; }
@@ -244,14 +300,14 @@ static mo_status tune_impl(const mo_csr *a, int k, const mo_params *params, cons
 mo_status mo_tune(const mo_csr *a, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
                   double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream)
 {
-    return tune_impl(a, 0, params, opts, best, ms_per_rep, convert_ms, stream);
+    return no_throw([&] { return tune_impl(a, 0, params, opts, best, ms_per_rep, convert_ms, stream); });
 }
 
 mo_status mo_tune_spmm(const mo_csr *a, int32_t k, const mo_params *params, const mo_tune_opts *opts, mo_format *best,
                        double ms_per_rep[MO_NUM_FORMATS], double convert_ms[MO_NUM_FORMATS], void *stream)
 {
     if (k < 1 || k > MO_MAX_RHS) return MO_E_PARAM;
-    return tune_impl(a, (int)k, params, opts, best, ms_per_rep, convert_ms, stream);
+    return no_throw([&] { return tune_impl(a, (int)k, params, opts, best, ms_per_rep, convert_ms, stream); });
 }
 
 mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out)

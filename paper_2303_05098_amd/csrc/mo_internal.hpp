@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <new>
 #include <vector>
 
 #include "mo.h"
@@ -27,6 +28,19 @@ void set_hip_error(hipError_t e);
         mo_status mo_s_ = (call);                           \
         if (mo_s_ != MO_OK) return mo_s_;                   \
     } while (0)
+
+// Nothing may leave an extern "C" function by exception: host containers that fail to grow become MO_E_ALLOC.
+template <typename F>
+inline mo_status no_throw(F &&body)
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return MO_E_ALLOC;
+    } catch (...) {
+        return MO_E_ALLOC;
+    }
+}
 
 // Launch check: catches bad launch configurations right away.
 #define MO_LAUNCH_CHECK() MO_HIP(hipGetLastError())
@@ -146,6 +160,10 @@ mo_status spmv_coo(const mo_matrix &a, const void *x, void *y, bool accumulate, 
 mo_status spmv_dia(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 mo_status spmv_ell(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 mo_status spmv_hyb_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+// The slot-split ELL kernel pays off while one-row-per-lane blocks cannot fill the chip (measured: faster up to about
+// 260 000 rows at K = 27, slower beyond; no gain for K < 16).
+constexpr int64_t ELL_SPLIT_MAX_ROWS = 300000;
+constexpr int64_t ELL_SPLIT_MIN_K = 16;
 constexpr int64_t HYB_FUSED_MAX_SURPLUS = 16;   // longer COO runs per row go through the COO kernel
 mo_status spmv_hdc_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_elems, std::vector<int32_t> *xpos,

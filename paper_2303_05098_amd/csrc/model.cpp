@@ -28,7 +28,12 @@ mo_status mo_model_load(const char *path, mo_model **out)
     mo_model *m = new (std::nothrow) mo_model();
     if (!m) { std::fclose(f); return MO_E_ALLOC; }
     mo_status rc = MO_E_MODEL;
+    // what the file can still deliver bounds every allocation made on the say-so of a header field
+    long file_bytes = -1;
+    if (std::fseek(f, 0, SEEK_END) == 0) { file_bytes = std::ftell(f); std::rewind(f); }
+    try {
     do {
+        if (file_bytes < 0) break;
         char magic[8];
         int32_t hdr[4];
         if (!read_exact(f, magic, 8) || std::memcmp(magic, "MOMDL1\0\0", 8) != 0) break;
@@ -42,6 +47,8 @@ mo_status mo_model_load(const char *path, mo_model **out)
         for (int32_t t = 0; t < m->n_trees && ok; ++t) {
             int32_t nn = 0;
             if (!read_exact(f, &nn, 4) || nn < 1 || nn > kMaxNodes || total + nn > kMaxNodes) { ok = false; break; }
+            const long here = std::ftell(f);
+            if (here < 0 || (int64_t)nn * 24 > (int64_t)file_bytes - here) { ok = false; break; }   // truncated or lying header
             const size_t base = m->feature.size();
             m->feature.resize(base + nn); m->threshold.resize(base + nn);
             m->left.resize(base + nn); m->right.resize(base + nn); m->klass.resize(base + nn);
@@ -67,6 +74,9 @@ mo_status mo_model_load(const char *path, mo_model **out)
         if (std::fread(&extra, 1, 1, f) != 0) break;   // trailing bytes
         rc = MO_OK;
     } while (false);
+    } catch (const std::bad_alloc &) {
+        rc = MO_E_ALLOC;
+    }
     std::fclose(f);
     if (rc != MO_OK) { delete m; return rc; }
     *out = m;

@@ -39,10 +39,6 @@ __device__ __forceinline__ T ell_row_sum(const int32_t *__restrict__ c, const T 
     }
     return sum;
 }
-// The slot-split kernel pays off while one-row-per-lane blocks cannot fill the chip (measured: faster up to about
-// 260 000 rows at K = 27, slower beyond; no gain for K < 16).
-constexpr int64_t ELL_SPLIT_MAX_ROWS = 300000;
-constexpr int64_t ELL_SPLIT_MIN_K = 16;
 
 template <typename T>
 __global__ __launch_bounds__(ELL_B) void k_ell(const int32_t *__restrict__ col, const T *__restrict__ val, int64_t m, int64_t K,

@@ -459,7 +459,9 @@ mo_status mo_switch(const mo_matrix *a, mo_format fmt, const mo_params *params, 
     if ((int)fmt < 0 || (int)fmt >= MO_NUM_FORMATS) return MO_E_FORMAT;
     mo_params p;
     MO_TRY(check_params(params, &p));
-    return switch_impl(*a, fmt, p, out, (hipStream_t)stream);
+    const mo_status rc = no_throw([&] { return switch_impl(*a, fmt, p, out, (hipStream_t)stream); });
+    if (rc != MO_OK) *out = nullptr;
+    return rc;
 }
 
 mo_status mo_matrix_features(const mo_matrix *a, const mo_params *params, double out[MO_NUM_FEATURES], mo_feature_ints *ints_opt,

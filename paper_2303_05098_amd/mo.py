@@ -30,7 +30,7 @@ MO_F32, MO_F64 = 0, 1
 (MO_OK, MO_E_NULL, MO_E_SHAPE, MO_E_CSR_INVALID, MO_E_FORMAT, MO_E_DTYPE, MO_E_FILL, MO_E_ALLOC, MO_E_DEVICE,
  MO_E_MODEL, MO_E_PARAM, MO_E_IO) = range(12)
 
-EXPORTS = ("mo_default_params", "mo_features", "mo_features_finalize", "mo_features_static", "mo_convert", "mo_spmv", "mo_spmm", "mo_tune", "mo_tune_spmm", "mo_pick", "mo_model_load",
+EXPORTS = ("mo_default_params", "mo_features", "mo_features_finalize", "mo_features_static", "mo_convert", "mo_spmv", "mo_spmv_kernels", "mo_spmm", "mo_tune", "mo_tune_spmm", "mo_pick", "mo_model_load",
            "mo_model_free", "mo_model_info", "mo_select", "mo_default_fit_opts", "mo_model_fit", "mo_model_save", "mo_predict", "mo_mtx_read", "mo_host_free", "mo_switch", "mo_matrix_features", "mo_matrix_export", "mo_matrix_free", "mo_set_allocator",
            "mo_strerror", "mo_last_hip_error")
 
@@ -95,6 +95,7 @@ lib.mo_convert.argtypes = [C.POINTER(mo_csr), C.c_int, C.POINTER(mo_params), C.P
 lib.mo_switch.argtypes = [C.c_void_p, C.c_int, C.POINTER(mo_params), C.POINTER(C.c_void_p), C.c_void_p]
 lib.mo_matrix_features.argtypes = [C.c_void_p, C.POINTER(mo_params), C.POINTER(C.c_double), C.POINTER(mo_feature_ints), C.c_void_p]
 lib.mo_spmv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+lib.mo_spmv_kernels.argtypes = [C.c_void_p, C.c_char_p, C.c_size_t]
 lib.mo_spmm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
 lib.mo_tune_spmm.argtypes = [C.POINTER(mo_csr), C.c_int32, C.POINTER(mo_params), C.POINTER(mo_tune_opts), C.POINTER(C.c_int),
                              C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]
@@ -178,8 +179,19 @@ class Csr:
         self.row_ptr = torch.as_tensor(np.ascontiguousarray(row_ptr, dtype=np.int32)).to(device) if not torch.is_tensor(row_ptr) else row_ptr
         self.col_idx = torch.as_tensor(np.ascontiguousarray(col_idx, dtype=np.int32)).to(device) if not torch.is_tensor(col_idx) else col_idx
         self.val = torch.as_tensor(np.ascontiguousarray(val)).to(device) if not torch.is_tensor(val) else val
-        assert self.row_ptr.dtype == torch.int32 and self.col_idx.dtype == torch.int32
-        assert self.val.dtype in (torch.float32, torch.float64)
+        if self.row_ptr.dtype != torch.int32 or self.col_idx.dtype != torch.int32:
+            raise ValueError("row_ptr and col_idx must be int32")
+        if self.val.dtype not in (torch.float32, torch.float64):
+            raise ValueError("val must be float32 or float64")
+        for name, t in (("row_ptr", self.row_ptr), ("col_idx", self.col_idx), ("val", self.val)):
+            if not t.is_contiguous() or t.dim() != 1:
+                raise ValueError(f"{name} must be a contiguous 1-D tensor")
+            if str(device).startswith("cuda") and not t.is_cuda:
+                raise ValueError(f"{name} must live on the GPU")
+        if self.row_ptr.numel() != self.m + 1:
+            raise ValueError(f"row_ptr has {self.row_ptr.numel()} entries, m + 1 = {self.m + 1} are needed")
+        if self.val.numel() != self.col_idx.numel():
+            raise ValueError("val and col_idx differ in length")
         self.nnz = int(self.col_idx.numel())
         self.dtype = MO_F32 if self.val.dtype == torch.float32 else MO_F64
 
@@ -206,6 +218,13 @@ class Matrix:
         self.handle = handle
         self._keep = keep
 
+    def dims(self):
+        """(m, n, torch dtype) of the held matrix, read once from the handle."""
+        if getattr(self, "_dims", None) is None:
+            v = self.view()
+            self._dims = (int(v.m), int(v.n), torch.float32 if v.dtype == MO_F32 else torch.float64)
+        return self._dims
+
     def view(self) -> mo_matrix_view:
         v = mo_matrix_view()
         _check(lib.mo_matrix_export(self.handle, C.byref(v)), "mo_matrix_export")
@@ -231,6 +250,12 @@ class Matrix:
             out["csr_col"] = _to_host(v.csr_col, v.nnz_csr, np.int32)
             out["csr_val"] = _to_host(v.csr_val, v.nnz_csr, vt)
         return out
+
+    def kernels(self) -> str:
+        """Names of the kernels mo_spmv launches for this handle."""
+        buf = C.create_string_buffer(256)
+        _check(lib.mo_spmv_kernels(self.handle, buf, 256), "mo_spmv_kernels")
+        return buf.value.decode()
 
     def free(self) -> None:
         if self.handle:
@@ -304,7 +329,25 @@ def mo_matrix_features(a: Matrix, params=None, stream=None):
     return np.array(list(out), dtype=np.float64), {k: int(getattr(ints, k)) for k, _ in mo_feature_ints._fields_}
 
 
+def _check_operands(a: Matrix, x, y, k: int, where: str) -> None:
+    """The kernels trust the pointers they are given: refuse on the host whatever would make them read or write outside
+    x or y (wrong device, dtype, length or layout)."""
+    if not a.handle:
+        raise ValueError(f"{where}: the matrix handle has been freed")
+    m, n, dt = a.dims()
+    for name, t, need in (("x", x, n * k), ("y", y, m * k)):
+        if not torch.is_tensor(t) or not t.is_cuda:
+            raise ValueError(f"{where}: {name} must be a CUDA tensor")
+        if t.dtype != dt:
+            raise ValueError(f"{where}: {name} is {t.dtype}, the matrix holds {dt}")
+        if not t.is_contiguous():
+            raise ValueError(f"{where}: {name} must be contiguous")
+        if t.numel() < need:
+            raise ValueError(f"{where}: {name} has {t.numel()} elements, {need} are needed")
+
+
 def mo_spmv(a: Matrix, x: torch.Tensor, y: torch.Tensor, stream=None) -> None:
+    _check_operands(a, x, y, 1, "mo_spmv")
     _check(lib.mo_spmv(a.handle, x.data_ptr(), y.data_ptr(), _stream_ptr(stream)), "mo_spmv")
 
 
@@ -323,6 +366,7 @@ def mo_spmm(a: Matrix, x: torch.Tensor, y: torch.Tensor, stream=None) -> None:
     """Y = A X; x: (n, k) and y: (m, k) contiguous row-major tensors of the handle's dtype."""
     if x.dim() != 2 or y.dim() != 2 or x.shape[1] != y.shape[1] or not x.is_contiguous() or not y.is_contiguous():
         raise ValueError("x must be (n, k) and y (m, k), both contiguous")
+    _check_operands(a, x, y, int(x.shape[1]), "mo_spmm")
     _check(lib.mo_spmm(a.handle, x.data_ptr(), y.data_ptr(), int(x.shape[1]), _stream_ptr(stream)), "mo_spmm")
 
 

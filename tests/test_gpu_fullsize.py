@@ -1,10 +1,15 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
 Features and SpMV are compared with the oracle over the whole matrix (the C oracle needs a second or two at
-these sizes).  The converted arrays are too large to rebuild on the CPU in reasonable time, so they are checked
-(i) entry by entry on a seeded sample of stored entries, straight from the definition of each format, and
-(ii) through properties that hold at any size (non-padding slots = nnz, offsets ascending, parts disjoint and
-complete, closed-form offsets and widths where they exist)."""
+these sizes).  Every exported array of every feasible conversion is compared with the oracle's, byte for byte over
+its logical extent, padding included (a few seconds of oracle time per format); before that, as a fast pre-check
+that names the broken rule when something is off, (i) a seeded sample of stored entries is looked up where the
+definition of each format puts it and (ii) properties that hold at any size are checked (non-padding slots = nnz,
+offsets ascending, parts disjoint and complete, closed-form offsets and widths where they exist).  The last test
+of each configuration runs the whole online stage (Section III-B): features -> model -> conversion -> SpMV on the
+library side against features -> model -> SpMV on the oracle side."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -86,6 +91,85 @@ def check_sampled(e, rp, ci, v, dtype, seed, m, n):
         assert np.array_equal(e["dia_off"], true)
 
 
+def same_bytes(got, want, what):
+    """Equal as bit patterns (so that -0.0 in place of +0.0 padding, or a NaN, cannot pass as equal)."""
+    got, want = np.ascontiguousarray(got), np.ascontiguousarray(want)
+    assert got.dtype == want.dtype and got.shape == want.shape, (what, got.dtype, want.dtype, got.shape, want.shape)
+    u = {4: np.uint32, 8: np.uint64}[got.dtype.itemsize]
+    if not np.array_equal(got.view(u), want.view(u)):
+        bad = np.nonzero(got.view(u).reshape(-1) != want.view(u).reshape(-1))[0]
+        raise AssertionError(f"{what}: {bad.size} of {got.size} elements differ, first at flat index {int(bad[0])}: "
+                             f"{got.reshape(-1)[bad[0]]!r} != {want.reshape(-1)[bad[0]]!r}")
+
+
+def check_full(e, m, n, ti, tj, ta, dtype):
+    """Every exported array against the oracle's conversion of the same triplets, over the logical extent [:, :m]."""
+    fmt = e["fmt"]
+    cast = lambda a: a.astype(dtype)   # noqa: E731  (exact: the triplets hold dtype values promoted to fp64)
+    if fmt == mo.MO_COO:
+        row, col, val = ref.to_coo(ti, tj, ta)
+        assert e["nnz_coo"] == row.shape[0]
+        same_bytes(e["coo_row"], row, "coo_row"); same_bytes(e["coo_col"], col, "coo_col"); same_bytes(e["coo_val"], cast(val), "coo_val")
+    elif fmt == mo.MO_DIA:
+        off, val = ref.to_dia(m, n, ti, tj, ta)
+        assert e["nd"] == off.shape[0]
+        same_bytes(e["dia_off"], off, "dia_off"); same_bytes(e["dia_val"][:, :m], cast(val), "dia_val")
+    elif fmt == mo.MO_ELL:
+        k, col, val = ref.to_ell(m, ti, tj, ta)
+        assert e["k"] == k
+        same_bytes(e["ell_col"][:, :m], col, "ell_col"); same_bytes(e["ell_val"][:, :m], cast(val), "ell_val")
+    elif fmt == mo.MO_HYB:
+        o = ref.to_hyb(m, ti, tj, ta)
+        assert e["k"] == o["k"] and e["nnz_coo"] == o["coo_row"].shape[0]
+        same_bytes(e["ell_col"][:, :m], o["ell_col"], "hyb ell_col"); same_bytes(e["ell_val"][:, :m], cast(o["ell_val"]), "hyb ell_val")
+        same_bytes(e["coo_row"], o["coo_row"], "hyb coo_row"); same_bytes(e["coo_col"], o["coo_col"], "hyb coo_col")
+        same_bytes(e["coo_val"], cast(o["coo_val"]), "hyb coo_val")
+    elif fmt == mo.MO_HDC:
+        o = ref.to_hdc(m, n, ti, tj, ta)
+        assert e["nd"] == o["dia_off"].shape[0] and e["nnz_csr"] == o["csr_col"].shape[0]
+        same_bytes(e["dia_off"], o["dia_off"], "hdc dia_off"); same_bytes(e["dia_val"][:, :m], cast(o["dia_val"]), "hdc dia_val")
+        same_bytes(e["csr_row_ptr"], o["csr_row_ptr"], "hdc row_ptr"); same_bytes(e["csr_col"], o["csr_col"], "hdc csr_col")
+        same_bytes(e["csr_val"], cast(o["csr_val"]), "hdc csr_val")
+
+
+def oracle_model(path):
+    """The committed model file, parsed on the Python side, in the form the oracle's forest walk takes."""
+    trees = mo.read_model(path)
+    cat = {k: [] for k in ("feature", "threshold", "left", "right", "klass")}
+    off = [0]
+    for t in trees:
+        for k in cat:
+            cat[k] += list(t[k])
+        off.append(len(cat["feature"]))
+    return dict(tree_off=off, n_classes=6, **cat)
+
+
+MODEL_PATH = os.path.join(os.path.dirname(os.path.abspath(mo.__file__)), "models", "mi355x_forest.bin")
+
+
+def run_chain(c, dtype):
+    """Online stage, library against oracle: the format the committed model names for the library's features must be
+    the one the oracle's forest walk names for the oracle's features; the matrix converted to it must multiply right."""
+    m, n, rp, ci, v = synth.config(c)
+    v = np.asarray(v, dtype=dtype)
+    a = upload(m, n, rp, ci, v, dtype)
+    x = synth.make_x(n, synth.BASE_SEED + c)
+    ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, dtype)
+    f, _ = mo.mo_features(a)
+    fo, _ = ref.features(m, n, ti, tj)
+    assert f.tobytes() == fo.tobytes()
+    mdl = mo.mo_model_load(MODEL_PATH)
+    fmt = mo.mo_select(mdl, f)
+    assert fmt == ref.select(oracle_model(MODEL_PATH), fo)
+    h = try_convert(a, fmt)
+    assert h is not None, f"the model names {mo.FORMAT_NAMES[fmt]}, which is not feasible on config {c}"
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, xo)
+    err, zeros_ok = ref.spmv_error(gpu_spmv(h, x, m, dtype), y_ref, mag)
+    assert err <= TOL[dtype] and zeros_ok, (mo.FORMAT_NAMES[fmt], err)
+    h.free()
+    mdl.free()
+
+
 def run_config(c, dtype, expect_infeasible=()):
     m, n, rp, ci, v = synth.config(c)
     v = np.asarray(v, dtype=dtype)
@@ -120,7 +204,10 @@ def run_config(c, dtype, expect_infeasible=()):
         assert err <= TOL[dtype] and zeros_ok, (mo.FORMAT_NAMES[fmt], err)
         assert gpu_spmv(h, x, m, dtype).tobytes() == y.tobytes()
         if fmt != mo.MO_CSR:
-            check_sampled(h.export(), rp, ci, v, dtype, 100 + c, m, n)
+            e = h.export()
+            check_sampled(e, rp, ci, v, dtype, 100 + c, m, n)
+            check_full(e, m, n, ti, tj, ta, dtype)
+            del e
         # features gathered from the held format, and the way back to CSR: no value of these inputs is 0, so both
         # must reproduce what the CSR input gives, bit for bit
         assert np.count_nonzero(v) == rp[-1]
@@ -153,3 +240,9 @@ def test_c3_lognormal():
 def test_c4_banded_scatter(dtype):
     f, ints = run_config(4, dtype, expect_infeasible=("DIA",))
     assert ints["nnz"] == 38903548 and ints["n_true_diag"] == 9
+
+
+@pytest.mark.parametrize("c,dtype", [(1, np.float64), (2, np.float64), (3, np.float64), (4, np.float64), (4, np.float32)],
+                         ids=["c1", "c2", "c3", "c4-f64", "c4-f32"])
+def test_online_stage_chain(c, dtype):
+    run_chain(c, dtype)
