@@ -185,6 +185,11 @@ mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
 
 // The kernels mo_spmv enqueues for a handle, by the same conditions as the dispatch above and in the launchers.
 static const char *csr_kernel(const mo_matrix &a) { return a.csr_split ? "k_csr_split+k_coo_fixup" : "k_csr_tiled"; }
+static const char *ell_kernel(const mo_matrix &a)
+{
+    if (a.m <= ELL_SPLIT_MAX_ROWS && a.k >= ELL_SPLIT_MIN_K) return "k_ell_split";
+    return ell_uses_windows(a) ? "k_ell_win" : "k_ell";
+}
 static const char *dia_kernel(const mo_matrix &a, bool hdc) { return a.dia_block ? "k_dia_lds" : (hdc ? "k_hdc_fused" : "k_dia"); }
 
 mo_status mo_spmv_kernels(const mo_matrix *a, char *buf, size_t cap)
@@ -198,11 +203,11 @@ mo_status mo_spmv_kernels(const mo_matrix *a, char *buf, size_t cap)
         break;
     case MO_CSR: s = csr_kernel(*a); break;
     case MO_DIA: s = dia_kernel(*a, false); break;
-    case MO_ELL: s = (a->m <= ELL_SPLIT_MAX_ROWS && a->k >= ELL_SPLIT_MIN_K) ? "k_ell_split" : "k_ell"; break;
+    case MO_ELL: s = ell_kernel(*a); break;
     case MO_HYB:
-        if (a->nnz_coo > 0 && a->hyb_max_surplus <= HYB_FUSED_MAX_SURPLUS && a->coo_rp) s = "k_ell_hyb";
+        if (a->nnz_coo > 0 && a->hyb_max_surplus <= HYB_FUSED_MAX_SURPLUS && a->coo_rp) s = ell_uses_windows(*a) ? "k_ell_win(hyb)" : "k_ell_hyb";
         else {
-            s = (a->m <= ELL_SPLIT_MAX_ROWS && a->k >= ELL_SPLIT_MIN_K) ? "k_ell_split" : "k_ell";
+            s = ell_kernel(*a);
             if (a->nnz_coo > 0) s += a->coo_tiles > 1 ? "+k_coo_tile+k_coo_fixup" : "+k_coo_tile";
         }
         break;

@@ -66,12 +66,25 @@ struct Scratch {
 
 // ---------------------------------------------------------------- handle
 constexpr int CSR_TILE = 2048;        // entries per CSR work tile
+constexpr int CSR_TILE_LARGE = 4096;  // ... of the row-owning kernel in fp32, or when rows average 16 entries or more
 constexpr int CSR_TILE_SMALL = 512;   // ... for parts of fewer than CSR_SMALL_NNZ entries, which 2048-entry tiles would
 constexpr int64_t CSR_SMALL_NNZ = 1 << 20;   // spread over too few blocks (measured cross-over: 1 - 2 M entries)
-constexpr int CSR_TILE_SLACK = 256;   // longest row the tiled CSR kernel accepts (LDS holds CSR_TILE + slack entries)
+constexpr int CSR_MAX_ROW = 256;      // longest row the row-owning tiled CSR kernel accepts
+constexpr int CSR_TILE_SLACK = 512;   // entries a tile may hold beyond its nominal size: the rows it owns run to the end of
+                                      // the last of them, and its first row is rounded up to a multiple of row_align rows
+constexpr int CSR_HEAD = 32;          // a tile's stream starts on a multiple of this many entries (a 128-byte line of columns)
 constexpr int COO_B_THREADS = 256;    // threads per COO block; a tile is COO_B_THREADS * coo_strip entries
 constexpr int64_t COO_SMALL_NNZ = 4 * 1024 * 1024;   // below this many entries the COO part of HYB uses 2-entry strips
 
+
+// Windows of x that cover the matrix's heavily populated diagonals (launch data, see xplan.hip): group c covers the
+// offsets col - row in [lo[c], lo[c] + span[c]).  ncl = 0: no such structure was found, x is gathered.
+constexpr int XP_MAX_CL = 8;
+struct XPlan {
+    int32_t ncl = 0;
+    int32_t lo[XP_MAX_CL] = {};
+    int32_t span[XP_MAX_CL] = {};
+};
 
 }  // namespace mo
 
@@ -105,7 +118,7 @@ struct mo_matrix {
     int64_t csr_max_row = 0;
     int64_t csr_tiles = 0;            // tiles of csr_tile entries; csr_group lanes per row in the LDS reduction
     bool coo_every_row = false;       // MO_COO: every row holds an entry, so the SpMV writes all of y and needs no zero pass
-    int32_t csr_tile = mo::CSR_TILE;  // CSR_TILE or CSR_TILE_SMALL
+    int32_t csr_tile = mo::CSR_TILE;  // CSR_TILE, CSR_TILE_LARGE or CSR_TILE_SMALL
     int32_t csr_group = 1;
     int32_t csr_split = 0;            // 1: tiles cut rows (any row length), carries in csr_carry_*
     int32_t *csr_carry_row = nullptr;
@@ -118,6 +131,7 @@ struct mo_matrix {
     int32_t coo_strip = 4;            // entries per thread of the COO kernel (4 or 2)
     int32_t *coo_carry_row = nullptr; // one per COO tile
     void *coo_carry_val = nullptr;
+    mo::XPlan xplan;                  // x windows for the kernels that gather x by column index
     // everything this handle owns
     std::vector<void *> owned;
     hipStream_t home = nullptr;
@@ -149,6 +163,10 @@ mo_status check_params(const mo_params *in, mo_params *out);
 // exact integer feasibility of a DIA / ELL slab
 bool slab_feasible(int64_t width, int64_t m, int64_t nnz, const mo_params &p);
 
+// ---------------------------------------------------------------- x window plan (xplan.hip)
+// Samples the (validated) CSR arrays and groups the heavily populated diagonals.  Synchronises the stream.
+mo_status plan_x_windows(const int32_t *row_ptr, const int32_t *col_idx, int64_t m, int64_t nnz, XPlan *out, hipStream_t s);
+
 // ---------------------------------------------------------------- scans (scan.hip)
 // out[i] = sum_{j<i} in[j] for i in [0, n]; out has n + 1 entries (out[n] = total).  tmp: >= scan_tmp_bytes(n).
 size_t scan_tmp_bytes(int64_t n);
@@ -160,6 +178,7 @@ mo_status spmv_coo(const mo_matrix &a, const void *x, void *y, bool accumulate, 
 mo_status spmv_dia(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 mo_status spmv_ell(const mo_matrix &a, const void *x, void *y, hipStream_t s);
 mo_status spmv_hyb_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s);
+bool ell_uses_windows(const mo_matrix &a);   // one-row-per-lane ELL / fused HYB kernel with x served from LDS windows
 // The slot-split ELL kernel pays off while one-row-per-lane blocks cannot fill the chip (measured: faster up to about
 // 260 000 rows at K = 27, slower beyond; no gain for K < 16).
 constexpr int64_t ELL_SPLIT_MAX_ROWS = 300000;
@@ -177,7 +196,8 @@ mo_status spmm(const mo_matrix &a, const void *x, void *y, int k, hipStream_t s)
 int64_t csr_tile_count(int64_t nnz, int tile_size);
 // y[row] += carries of every chain of consecutive tiles with the same carry row (shared by the COO and CSR kernels)
 mo_status carry_fixup(const int32_t *carry_row, const void *carry_val, int64_t tiles, void *y, mo_dtype dt, hipStream_t s);
-mo_status csr_build_tiles(const int32_t *row_ptr, int64_t m, int64_t nnz, int64_t ntiles, int tile_size, int32_t *tile_rp, hipStream_t s);
+mo_status csr_build_tiles(const int32_t *row_ptr, int64_t m, int64_t nnz, int64_t ntiles, int tile_size, int row_align, int32_t *tile_rp,
+                          hipStream_t s);
 
 inline size_t dtype_size(mo_dtype d) { return d == MO_F32 ? 4 : 8; }
 

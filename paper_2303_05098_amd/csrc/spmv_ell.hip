@@ -8,28 +8,43 @@ namespace mo {
 
 constexpr int ELL_B = 256;
 constexpr int ELL_U = 8;   // slots fetched together
+constexpr int ELL_WIN_B = 512;                      // rows per block of the kernel with x windows
+constexpr int64_t ELL_WIN_LDS_BYTES = 40 * 1024;    // LDS budget of its windows
 
 // sum += A(row, slots s, s + step, ...) * x over the slots [s0, s1) of one row.  The loads of ELL_U slots are issued
 // together and unconditionally (a padded slot reads x[0] twice and is masked out of the sum), so that no load waits
-// for a branch on the one before it.  The order of the additions is the slot order.
+// for a branch on the one before it, and the column indices of the next ELL_U slots are requested before the values
+// and x entries of the current ones are waited for: loads return in order of issue, so that wait leaves the next
+// columns in flight and a group of slots costs one memory round trip instead of two.  The order of the additions is
+// the slot order.
 template <typename T>
 __device__ __forceinline__ T ell_row_sum(const int32_t *__restrict__ c, const T *__restrict__ v, int64_t ld, int64_t s0, int64_t s1,
                                          int64_t step, const T *__restrict__ x)
 {
     T sum = (T)0;
     int64_t s = s0;
-    for (; s + (ELL_U - 1) * step < s1; s += ELL_U * step) {
-        int32_t j[ELL_U];
-        T a[ELL_U], xv[ELL_U];
+    if (s + (ELL_U - 1) * step < s1) {
+        int32_t jn[ELL_U];
 #pragma unroll
-        for (int u = 0; u < ELL_U; ++u) j[u] = ld_stream(c + (s + u * step) * ld);
+        for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (s + u * step) * ld);
+        for (; s + (ELL_U - 1) * step < s1; s += ELL_U * step) {
+            int32_t j[ELL_U];
+            T a[ELL_U], xv[ELL_U];
 #pragma unroll
-        for (int u = 0; u < ELL_U; ++u) {   // a padded slot reads x[0] in place of its value: no slab traffic for padding
-            a[u] = ld_stream(j[u] >= 0 ? v + (s + u * step) * ld : x);
-            xv[u] = x[j[u] >= 0 ? j[u] : 0];
+            for (int u = 0; u < ELL_U; ++u) j[u] = jn[u];
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) {   // a padded slot reads x[0] in place of its value: no slab traffic for padding
+                a[u] = ld_stream(j[u] >= 0 ? v + (s + u * step) * ld : x);
+                xv[u] = x[j[u] >= 0 ? j[u] : 0];
+            }
+            const int64_t sn = s + ELL_U * step;
+            if (sn + (ELL_U - 1) * step < s1) {   // uniform: s1 and step are kernel arguments
+#pragma unroll
+                for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (sn + u * step) * ld);
+            }
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) sum += j[u] >= 0 ? a[u] * xv[u] : (T)0;
         }
-#pragma unroll
-        for (int u = 0; u < ELL_U; ++u) sum += j[u] >= 0 ? a[u] * xv[u] : (T)0;
     }
     for (; s < s1; s += step) {
         const int32_t j = ld_stream(c + s * ld);
@@ -39,7 +54,6 @@ __device__ __forceinline__ T ell_row_sum(const int32_t *__restrict__ c, const T 
     }
     return sum;
 }
-
 template <typename T>
 __global__ __launch_bounds__(ELL_B) void k_ell(const int32_t *__restrict__ col, const T *__restrict__ val, int64_t m, int64_t K,
                                                 int64_t ld, const T *__restrict__ x, T *__restrict__ y)
@@ -48,6 +62,124 @@ __global__ __launch_bounds__(ELL_B) void k_ell(const int32_t *__restrict__ col, 
     const int64_t row = lb * ELL_B + threadIdx.x;
     if (row >= m) return;
     st_stream(y + row, ell_row_sum<T>(col + row, val + row, ld, 0, K, 1, x));
+}
+
+// One row per lane with x served from LDS windows (matrices with a window plan: most entries on a few groups of
+// diagonals).  The rows [row0, row0 + B) of a block read x almost only inside x[row0 + lo_q, row0 + B - 1 + lo_q +
+// span_q) for the groups q of the plan; the block fetches those windows once, coalesced, and every entry then finds
+// its x value by comparing its column with the window bounds, which are the same for all lanes (scalar registers).
+// An entry outside every window is gathered from global memory.  Measured on the 27-point stencil: the x gathers of
+// k_ell cost 19 of its 129 us although consecutive lanes read consecutive x entries (every slot is one more memory
+// instruction per wave; with x from a fixed LDS table the kernel ran in 110 us); the windows replace 27 gathers per row
+// by 5 staged x entries per row, and the lookup costs part of that again: 123 us with 512-row blocks, 127 with 256.
+// HYB: the row's lane also adds its run of the COO part (see k_ell_hyb).
+template <typename T, int B, bool HYB>
+__global__ __launch_bounds__(B) void k_ell_win(const int32_t *__restrict__ col, const T *__restrict__ val, int64_t m, int64_t n, int64_t K,
+                                               int64_t ld, const int32_t *__restrict__ coo_rp, const int32_t *__restrict__ ccol,
+                                               const T *__restrict__ cval, const T *__restrict__ x, T *__restrict__ y, const XPlan xp)
+{
+    extern __shared__ __align__(16) unsigned char s_raw[];
+    T *xs = reinterpret_cast<T *>(s_raw);
+    const int64_t lb = xcd_block(blockIdx.x, gridDim.x);
+    const int64_t row0 = lb * B;
+    const int64_t row = row0 + threadIdx.x;
+    const bool rv = row < m;
+    const int64_t rr = rv ? row : m - 1;   // lanes past the end walk the last row and store nothing
+    const int32_t *c = col + rr;
+    const T *v = val + rr;
+    // the first group of column indices is requested before the windows, so that both are on their way together
+    int32_t jn[ELL_U];
+    const bool any_full = ELL_U <= K;
+    if (any_full) {
+#pragma unroll
+        for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + u * ld);
+    }
+    {
+        int base = 0;
+        for (int q = 0; q < xp.ncl; ++q) {
+            const int len = xp.span[q] + B - 1;
+            const int64_t first = row0 + xp.lo[q];
+            for (int i = threadIdx.x; i < len; i += B) {
+                const int64_t j = first + i;
+                xs[base + i] = (j >= 0 && j < n) ? x[j] : (T)0;
+            }
+            base += len;
+        }
+    }
+    __syncthreads();
+    // window bounds of this block: the same for all lanes (scalar registers)
+    int shift[XP_MAX_CL], wlen[XP_MAX_CL], wbase[XP_MAX_CL];
+    {
+        int base = 0;
+#pragma unroll
+        for (int q = 0; q < XP_MAX_CL; ++q) {
+            const bool on = q < xp.ncl;
+            wlen[q] = on ? xp.span[q] + B - 1 : 0;               // an unused group matches nothing
+            shift[q] = on ? (int)row0 + xp.lo[q] : 0;            // row0 + lo fits 32 bits: |lo| < m + n < 2^31
+            wbase[q] = base;
+            base += wlen[q];
+        }
+    }
+    T sum = (T)0;
+    int64_t s = 0;
+    if (any_full) {
+        for (; s + ELL_U <= K; s += ELL_U) {
+            int32_t j[ELL_U];
+            T a[ELL_U], xv[ELL_U];
+            int pos[ELL_U];
+            bool hit[ELL_U];
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) { j[u] = jn[u]; pos[u] = 0; hit[u] = false; }
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) a[u] = ld_stream(j[u] >= 0 ? v + (s + u) * ld : x);   // padding: no slab traffic
+            for (int q = 0; q < xp.ncl; ++q) {                    // uniform trip count
+                const int sh = shift[q], ln = wlen[q], bs = wbase[q];
+#pragma unroll
+                for (int u = 0; u < ELL_U; ++u) {
+                    const unsigned idx = (unsigned)(j[u] - sh);
+                    const bool in = idx < (unsigned)ln;
+                    pos[u] = in ? bs + (int)idx : pos[u];
+                    hit[u] = hit[u] || in;
+                }
+            }
+            bool all = true;
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) all = all && (hit[u] || j[u] < 0);
+            if (!all) {
+#pragma unroll
+                for (int u = 0; u < ELL_U; ++u) xv[u] = x[(j[u] >= 0 && !hit[u]) ? j[u] : 0];
+            }
+            if (s + 2 * ELL_U <= K) {
+#pragma unroll
+                for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (s + ELL_U + u) * ld);
+            }
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) {
+                const T xl = xs[pos[u]];
+                const T xu = hit[u] ? xl : (all ? (T)0 : xv[u]);
+                sum += j[u] >= 0 ? a[u] * xu : (T)0;
+            }
+        }
+    }
+    for (; s < K; ++s) {
+        const int32_t j = ld_stream(c + s * ld);
+        const T a = ld_stream(j >= 0 ? v + s * ld : x);
+        int pos = 0;
+        bool hit = false;
+        for (int q = 0; q < xp.ncl; ++q) {
+            const unsigned idx = (unsigned)(j - shift[q]);
+            const bool in = idx < (unsigned)wlen[q];
+            pos = in ? wbase[q] + (int)idx : pos;
+            hit = hit || in;
+        }
+        const T xu = hit ? xs[pos] : x[j >= 0 ? j : 0];
+        sum += j >= 0 ? a * xu : (T)0;
+    }
+    if (HYB) {
+        const int32_t p0 = coo_rp[rr], p1 = coo_rp[rr + 1];
+        for (int32_t p = p0; p < p1; ++p) sum += cval[p] * x[ccol[p]];
+    }
+    if (rv) st_stream(y + row, sum);
 }
 
 // Small matrices: one row per lane leaves most of the chip idle and makes every lane walk all K slots in sequence.
@@ -90,9 +222,35 @@ __global__ __launch_bounds__(ELL_B) void k_ell_hyb(const int32_t *__restrict__ c
     st_stream(y + row, sum);
 }
 
+// LDS bytes of the windows for blocks of B rows, or 0 when the plan does not pay: no plan, windows beyond the budget,
+// or more staged x entries than a third of the entries a block multiplies (then the gathers are the cheaper way).
+template <typename T>
+static size_t ell_window_bytes(const mo_matrix &a, int B)
+{
+    if (a.xplan.ncl <= 0 || a.m <= ELL_SPLIT_MAX_ROWS) return 0;   // 512-row blocks leave a small matrix on too few CUs
+    int64_t elems = 0;
+    for (int q = 0; q < a.xplan.ncl; ++q) elems += (int64_t)a.xplan.span[q] + B - 1;
+    if (elems * (int64_t)sizeof(T) > ELL_WIN_LDS_BYTES) return 0;
+    const double per_block = (double)B * ((double)a.nnz / (double)a.m);
+    if ((double)elems * 3.0 > per_block) return 0;
+    return (size_t)elems * sizeof(T);
+}
+
+template <typename T, bool HYB>
+static mo_status ell_win_launch(const mo_matrix &a, const void *x, void *y, size_t lds, hipStream_t s)
+{
+    constexpr int B = ELL_WIN_B;
+    const unsigned grid = (unsigned)((a.m + B - 1) / B);
+    hipLaunchKernelGGL((k_ell_win<T, B, HYB>), dim3(grid), dim3(B), lds, s, a.ell_col, (const T *)a.ell_val, a.m, a.n, a.k, a.ld, a.coo_rp,
+                       a.coo_col, (const T *)a.coo_val, (const T *)x, (T *)y, a.xplan);
+    MO_LAUNCH_CHECK();
+    return MO_OK;
+}
+
 template <typename T>
 static mo_status hyb_fused_typed(const mo_matrix &a, const void *x, void *y, hipStream_t s)
 {
+    if (const size_t lds = ell_window_bytes<T>(a, ELL_WIN_B)) return ell_win_launch<T, true>(a, x, y, lds, s);
     const unsigned grid = (unsigned)((a.m + ELL_B - 1) / ELL_B);
     hipLaunchKernelGGL(k_ell_hyb<T>, dim3(grid), dim3(ELL_B), 0, s, a.ell_col, (const T *)a.ell_val, a.m, a.k, a.ld, a.coo_rp, a.coo_col,
                        (const T *)a.coo_val, (const T *)x, (T *)y);
@@ -109,10 +267,16 @@ static mo_status ell_typed(const mo_matrix &a, const void *x, void *y, hipStream
         MO_LAUNCH_CHECK();
         return MO_OK;
     }
+    if (const size_t lds = ell_window_bytes<T>(a, ELL_WIN_B)) return ell_win_launch<T, false>(a, x, y, lds, s);
     const unsigned grid = (unsigned)((a.m + ELL_B - 1) / ELL_B);
     hipLaunchKernelGGL(k_ell<T>, dim3(grid), dim3(ELL_B), 0, s, a.ell_col, (const T *)a.ell_val, a.m, a.k, a.ld, (const T *)x, (T *)y);
     MO_LAUNCH_CHECK();
     return MO_OK;
+}
+
+bool ell_uses_windows(const mo_matrix &a)
+{
+    return (a.dtype == MO_F32 ? ell_window_bytes<float>(a, ELL_WIN_B) : ell_window_bytes<double>(a, ELL_WIN_B)) > 0;
 }
 
 mo_status spmv_hyb_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s)

@@ -315,3 +315,29 @@ def test_features_scratch_is_reused_safely():
         for stream in (None, other):
             f, ints = mo.mo_features(a, stream=stream)
             assert f.tobytes() == fo.tobytes() and ints == io, (name, stream)
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32], ids=["f64", "f32"])
+def test_window_kernels_with_entries_outside_the_windows(dtype):
+    """Matrices large enough for the kernels that serve x from LDS windows (ELL, fused HYB): a band of 15 diagonals plus
+    two far ones, with 4 % scattered entries that fall outside every window (gathered from memory inside the same
+    kernel), windows that reach past both ends of x, and a row count that is not a multiple of the block size."""
+    m = 400003
+    offs = list(range(-7, 8)) + [-30011, 25013]
+    m, n, rp, ci, v = synth.banded_scatter(m, offs, 4, 100, 91)
+    v = np.asarray(v, dtype=dtype)
+    a = upload(m, n, rp, ci, v, dtype)
+    x = synth.make_x(n, 92)
+    ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, dtype)
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, xo)
+    seen = set()
+    for fmt in (mo.MO_ELL, mo.MO_HYB, mo.MO_CSR):
+        h = try_convert(a, fmt, {"max_fill": 64})
+        assert h is not None
+        seen.add(h.kernels())
+        y = gpu_spmv(h, x, m, dtype)
+        err, zeros_ok = ref.spmv_error(y, y_ref, mag)
+        assert err <= TOL[dtype] and zeros_ok, (mo.FORMAT_NAMES[fmt], err)
+        assert gpu_spmv(h, x, m, dtype).tobytes() == y.tobytes()
+        h.free()
+    assert any("k_ell_win" in k for k in seen), seen
