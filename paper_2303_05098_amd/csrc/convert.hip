@@ -620,9 +620,11 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
 void setup_coo_tiles(Builder &b, size_t sv)
 {
     mo_matrix *h = b.h;
-    // Short strips only pay off for the scattered COO part of a HYB matrix, whose SpMV read-modify-writes y: measured
-    // 148 vs 165 us on the banded+scatter matrix; a plain COO matrix is faster with longer strips at any size.
-    h->coo_strip = (h->fmt == MO_HYB && h->nnz_coo < COO_SMALL_NNZ) ? 2 : 4;
+    // Entries per thread: 8 for large parts (2048-entry tiles: 157 against 163 us on the 27-point stencil, 129 against
+    // 132 us on the band matrix), 4 below COO_SMALL_NNZ entries (more blocks for a chip that a small part cannot fill), 2
+    // for the small scattered COO part of a HYB matrix, whose SpMV read-modify-writes y (measured 148 vs 165 us on the
+    // banded+scatter matrix).
+    h->coo_strip = h->nnz_coo >= COO_SMALL_NNZ ? 8 : (h->fmt == MO_HYB ? 2 : 4);
     const int64_t tile = (int64_t)COO_B_THREADS * h->coo_strip;
     h->coo_tiles = (h->nnz_coo + tile - 1) / tile;
     const int64_t t = h->coo_tiles > 0 ? h->coo_tiles : 1;

@@ -74,7 +74,7 @@ constexpr int CSR_TILE_SLACK = 512;   // entries a tile may hold beyond its nomi
                                       // the last of them, and its first row is rounded up to a multiple of row_align rows
 constexpr int CSR_HEAD = 32;          // a tile's stream starts on a multiple of this many entries (a 128-byte line of columns)
 constexpr int COO_B_THREADS = 256;    // threads per COO block; a tile is COO_B_THREADS * coo_strip entries
-constexpr int64_t COO_SMALL_NNZ = 4 * 1024 * 1024;   // below this many entries the COO part of HYB uses 2-entry strips
+constexpr int64_t COO_SMALL_NNZ = 4 * 1024 * 1024;   // from this many entries on a COO part uses 8-entry strips (below: 4, or 2 inside HYB)
 
 
 // Windows of x that cover the matrix's heavily populated diagonals (launch data, see xplan.hip): group c covers the
@@ -128,7 +128,7 @@ struct mo_matrix {
                                       // of the multi-vector product; not part of the format)
     int64_t hyb_max_surplus = 0;      // HYB: longest row minus the ELL width (entries of one row in the COO part)
     int64_t coo_tiles = 0;
-    int32_t coo_strip = 4;            // entries per thread of the COO kernel (4 or 2)
+    int32_t coo_strip = 4;            // entries per thread of the COO kernel (8, 4 or 2)
     int32_t *coo_carry_row = nullptr; // one per COO tile
     void *coo_carry_val = nullptr;
     mo::XPlan xplan;                  // x windows for the kernels that gather x by column index

@@ -13,9 +13,7 @@
 namespace mo {
 
 constexpr int COO_B = 256;
-// Entries per thread: 4 in general (one 16-byte load of rows and of columns per lane, contiguous across the wave;
-// measured 9 % faster than 8 per thread, whose loads touch every cache line twice), 2 for the small scattered COO
-// part of a HYB matrix (twice as many threads to hide the x gathers and the y read-modify-writes behind).
+// Entries per thread (COO_STRIP): 8, 4 or 2, chosen at conversion time from the size of the part.
 
 template <typename T>
 __global__ void k_zero(T *__restrict__ p, int64_t n)
@@ -43,41 +41,46 @@ __global__ __launch_bounds__(COO_B) void k_coo_tile(const int32_t *__restrict__ 
     const int64_t tile = xcd_block(blockIdx.x, gridDim.x);
     const int64_t base = tile * TILE;
     const int t = threadIdx.x;
-    const int64_t p0 = base + (int64_t)t * COO_STRIP;
 
-    int r[COO_STRIP];
-    T pr[COO_STRIP];
-    if (p0 + COO_STRIP <= nnz) {
-        using V2 = typename Vec2<T>::type;
-        int c[COO_STRIP];
-        V2 v[COO_STRIP / 2];
-        if constexpr (COO_STRIP == 4) {
-            const int4 ra = *reinterpret_cast<const int4 *>(row + p0);
-            const int4 ca = *reinterpret_cast<const int4 *>(col + p0);
-            r[0] = ra.x; r[1] = ra.y; r[2] = ra.z; r[3] = ra.w;
-            c[0] = ca.x; c[1] = ca.y; c[2] = ca.z; c[3] = ca.w;
-        } else {
-            static_assert(COO_STRIP == 2, "strip loads are written for 4 or 2 entries per thread");
-            const int2 ra = *reinterpret_cast<const int2 *>(row + p0);
-            const int2 ca = *reinterpret_cast<const int2 *>(col + p0);
-            r[0] = ra.x; r[1] = ra.y;
-            c[0] = ca.x; c[1] = ca.y;
+    // Entries are fetched with consecutive lanes on consecutive entries (entry base + t + q * 256 in load q), so that a
+    // wave's x gathers cover 64 neighbouring entries - a few rows, whose columns share cache lines - and not every
+    // fourth entry of 256; the products and row indices then change hands through LDS, after which every thread owns
+    // COO_STRIP consecutive entries.  (With 16-byte loads of 4 consecutive entries per lane the gathers of one
+    // instruction spread over four times as many rows: 125 against 107 us for this stream-and-gather step on the
+    // 27-point stencil's pattern.)
+    __shared__ int s_row[TILE];
+    __shared__ T s_prod[TILE];
+    {
+        int rr[COO_STRIP], cc[COO_STRIP];
+        T vv[COO_STRIP], xx[COO_STRIP];
+        const int64_t left = nnz - base;                       // > 0
+        const int lim = (int)(left < TILE ? left : TILE);      // entries of this tile
+#pragma unroll
+        for (int q = 0; q < COO_STRIP; ++q) {                  // unconditional loads, index clamped into the tile
+            const int i = t + q * COO_B;
+            const int64_t p = base + (i < lim ? i : lim - 1);
+            rr[q] = ld_stream(row + p);
+            cc[q] = ld_stream(col + p);
         }
-#pragma unroll
-        for (int q = 0; q < COO_STRIP / 2; ++q) v[q] = *reinterpret_cast<const V2 *>(val + p0 + 2 * q);
-        T xv[COO_STRIP];
-#pragma unroll
-        for (int q = 0; q < COO_STRIP; ++q) xv[q] = x[c[q]];
-#pragma unroll
-        for (int q = 0; q < COO_STRIP / 2; ++q) { pr[2 * q] = v[q].x * xv[2 * q]; pr[2 * q + 1] = v[q].y * xv[2 * q + 1]; }
-    } else {
 #pragma unroll
         for (int q = 0; q < COO_STRIP; ++q) {
-            const int64_t p = p0 + q;
-            if (p < nnz) { r[q] = row[p]; pr[q] = val[p] * x[col[p]]; }
-            else { r[q] = -1; pr[q] = (T)0; }
+            const int i = t + q * COO_B;
+            vv[q] = ld_stream(val + base + (i < lim ? i : lim - 1));
+        }
+#pragma unroll
+        for (int q = 0; q < COO_STRIP; ++q) xx[q] = x[cc[q]];
+#pragma unroll
+        for (int q = 0; q < COO_STRIP; ++q) {
+            const int i = t + q * COO_B;
+            s_row[i] = i < lim ? rr[q] : -1;
+            s_prod[i] = i < lim ? vv[q] * xx[q] : (T)0;
         }
     }
+    __syncthreads();
+    int r[COO_STRIP];
+    T pr[COO_STRIP];
+#pragma unroll
+    for (int q = 0; q < COO_STRIP; ++q) { r[q] = s_row[t * COO_STRIP + q]; pr[q] = s_prod[t * COO_STRIP + q]; }
 
     // runs inside the strip
     int cur = r[0];
@@ -189,6 +192,7 @@ static mo_status coo_typed(const mo_matrix &a, const void *x, void *y, bool accu
     if (!accumulate && !(a.fmt == MO_COO && a.coo_every_row)) MO_TRY(zero_typed<T>(y, a.m, s));
     if (a.nnz_coo <= 0) return MO_OK;
     if (a.coo_strip == 2) return coo_launch<T, 2>(a, (const T *)x, (T *)y, accumulate, s);
+    if (a.coo_strip == 8) return coo_launch<T, 8>(a, (const T *)x, (T *)y, accumulate, s);
     return coo_launch<T, 4>(a, (const T *)x, (T *)y, accumulate, s);
 }
 
