@@ -167,7 +167,12 @@ mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
     hipStream_t s = (hipStream_t)stream;
     switch (a->fmt) {
     case MO_COO: return spmv_coo(*a, x, y, false, s);
-    case MO_CSR: return spmv_csr(*a, x, y, false, s);
+    case MO_CSR:
+        if (a->csr_half[0]) {
+            MO_TRY(spmv_csr(*a->csr_half[0], x, y, false, s));
+            return spmv_csr(*a->csr_half[1], x, y, true, s);
+        }
+        return spmv_csr(*a, x, y, false, s);
     case MO_DIA: return spmv_dia(*a, x, y, s);
     case MO_ELL: return spmv_ell(*a, x, y, s);
     case MO_HYB:
@@ -201,7 +206,10 @@ mo_status mo_spmv_kernels(const mo_matrix *a, char *buf, size_t cap)
         if (!a->coo_every_row) s += "k_zero+";
         s += a->coo_tiles > 1 ? "k_coo_tile+k_coo_fixup" : "k_coo_tile";
         break;
-    case MO_CSR: s = csr_kernel(*a); break;
+    case MO_CSR:
+        if (a->csr_half[0]) { s = std::string(csr_kernel(*a->csr_half[0])) + "+" + csr_kernel(*a->csr_half[1]) + "(column halves)"; break; }
+        s = csr_kernel(*a);
+        break;
     case MO_DIA: s = dia_kernel(*a, false); break;
     case MO_ELL: s = ell_kernel(*a); break;
     case MO_HYB:
@@ -335,6 +343,7 @@ mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out)
 void mo_matrix_free(mo_matrix *a)
 {
     if (!a) return;
+    for (mo_matrix *half : a->csr_half) mo_matrix_free(half);
     for (void *p : a->owned) dev_free(p, a->home);
     delete a;
 }

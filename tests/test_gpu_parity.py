@@ -341,3 +341,26 @@ def test_window_kernels_with_entries_outside_the_windows(dtype):
         assert gpu_spmv(h, x, m, dtype).tobytes() == y.tobytes()
         h.free()
     assert any("k_ell_win" in k for k in seen), seen
+
+
+def test_csr_column_halves_fp32():
+    """Scattered columns and an x of 5.6 MB in fp32: the CSR handle multiplies in two passes over column halves (the
+    fp64 case of that path is the lognormal configuration at full size)."""
+    m, n, rp, ci, v = synth.uniform_rows(1400000, 4, 93)
+    v = np.asarray(v, dtype=np.float32)
+    a = upload(m, n, rp, ci, v, np.float32)
+    x = synth.make_x(n, 94)
+    ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, np.float32)
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, xo)
+    h = mo.mo_convert(a, mo.MO_CSR)
+    assert "column halves" in h.kernels()
+    y = gpu_spmv(h, x, m, np.float32)
+    err, zeros_ok = ref.spmv_error(y, y_ref, mag)
+    assert err <= TOL[np.float32] and zeros_ok, err
+    assert gpu_spmv(h, x, m, np.float32).tobytes() == y.tobytes()
+    e = h.export()                                # the handle still exports the caller's CSR arrays
+    assert np.array_equal(e["csr_row_ptr"], rp) and np.array_equal(e["csr_col"], ci) and e["csr_val"].tobytes() == v.tobytes()
+    f, ints = mo.mo_matrix_features(h)
+    fo, io = ref.features(m, n, ti, tj)
+    assert f.tobytes() == fo.tobytes() and ints == io
+    h.free()
