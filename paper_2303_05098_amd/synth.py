@@ -252,9 +252,50 @@ def config(c: int, scale: float = 1.0):
 FAMILIES = ("laplace2d", "stencil27", "lognormal", "banded_scatter", "uniform_rows")
 
 
+SWEEP_BASE = 2048          # matrices 0 .. 2047: the five families in rotation
+SWEEP_EXTRA = 512          # matrices 2048 .. 2559: clustered bands and scaled copies of the four benchmark configurations
+
+
+def _sweep_extra(k: int, n_lo: float, n_hi: float):
+    """Matrices beyond the five rotating families.  Even k: a band whose diagonals come in clusters (a centre cluster
+    and one to three pairs at +-d, every cluster 1, 3 or 5 diagonals wide, d a power of two times a small odd number),
+    the shape of benchmark configuration 4, with 0 - 10 % scattered entries.  Odd k: benchmark configuration
+    1 + (k >> 1) mod 4 at a size drawn log-uniformly (the first four odd k: at its own size)."""
+    seed = BASE_SEED + 1000 + k
+    n_t = math.exp(math.log(n_lo) + scalar01(seed, 40, 0) * (math.log(n_hi) - math.log(n_lo)))
+    j = k - SWEEP_BASE
+    if j % 2 == 1:
+        c = 1 + (j >> 1) % 4
+        native = {1: 4096.0, 2: 2097152.0, 3: 1048576.0, 4: 4194304.0}[c]
+        if (j >> 1) < 4:
+            scale = 1.0
+        elif c == 1:
+            scale = n_t ** 0.5 / 64.0
+        elif c == 2:
+            scale = n_t ** (1.0 / 3.0) / 128.0
+        else:
+            scale = min(n_t, native) / native
+        return ("config%d_scaled" % c,) + config(c, scale)
+    m = max(64, int(round(n_t)))
+    pairs = 1 + int(scalar01(seed, 47, 0) * 3)                  # 1..3 pairs of off-centre clusters
+    offs = []
+    half = int(scalar01(seed, 48, 0) * 3)                        # centre cluster: 1, 3 or 5 wide
+    offs += list(range(-half, half + 1))
+    for q in range(pairs):
+        d = (1 << (5 + int(scalar01(seed, 49, q) * 9))) * (1 + 2 * int(scalar01(seed, 50, q) * 2))   # 32 .. 8192, times 1 or 3
+        w = int(scalar01(seed, 51, q) * 3)
+        for o in range(-w, w + 1):
+            offs += [d + o, -d + o]
+    offs = [o for o in sorted(set(offs)) if abs(o) < m]
+    pct = int(scalar01(seed, 45, 0) * 11)                        # 0..10 % scatter
+    return ("banded_clustered",) + banded_scatter(m, offs, pct, 100, seed)
+
+
 def sweep_matrix(k: int, n_lo: float = 1e3, n_hi: float = 4e6):
-    """Matrix k of the tuner sweep: family = k mod 5, target n log-uniform in
-    [n_lo, n_hi].  Returns (family_name, m, n, row_ptr, col_idx, val)."""
+    """Matrix k of the tuner sweep: for k < SWEEP_BASE family = k mod 5, target n log-uniform in [n_lo, n_hi]; beyond
+    that see _sweep_extra.  Returns (family_name, m, n, row_ptr, col_idx, val)."""
+    if k >= SWEEP_BASE:
+        return _sweep_extra(k, n_lo, n_hi)
     seed = BASE_SEED + 1000 + k
     fam = FAMILIES[k % 5]
     n_t = math.exp(math.log(n_lo) + scalar01(seed, 40, 0) * (math.log(n_hi) - math.log(n_lo)))
