@@ -45,5 +45,16 @@ def build(jobs: int = 8) -> str:
     return LIB
 
 
+def build_microbench() -> str:
+    """The stand-alone memory-system measurements (csrc/microbench.hip) as a program of their own."""
+    exe = os.path.join(HERE, "mo_microbench")
+    cmd = [HIPCC, "-O3", "-std=c++17"] + DEVICE + [os.path.join(CSRC, "microbench.hip"), "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on microbench.hip:\n{r.stderr}")
+    return exe
+
+
 if __name__ == "__main__":
     print(build())
+    print(build_microbench())

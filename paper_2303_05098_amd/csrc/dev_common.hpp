@@ -71,18 +71,18 @@ __device__ __forceinline__ void st_stream(T *p, T v) { __builtin_nontemporal_sto
 // issued before the first one is consumed (registers in between), so a wave keeps STAGE_BATCH cache lines per lane
 // group in flight instead of paying one memory latency per 64 elements.
 constexpr int STAGE_BATCH = 8;
-template <typename T>
+template <typename T, int BATCH = STAGE_BATCH>
 __device__ __forceinline__ void stage_to_lds(const T *__restrict__ g, T *s, int count, int lane)
 {
-    for (int i0 = 0; i0 < count; i0 += WAVE * STAGE_BATCH) {
-        T r[STAGE_BATCH];
+    for (int i0 = 0; i0 < count; i0 += WAVE * BATCH) {
+        T r[BATCH];
 #pragma unroll
-        for (int u = 0; u < STAGE_BATCH; ++u) {   // unconditional loads (index clamped into the run) so that none waits for another
+        for (int u = 0; u < BATCH; ++u) {   // unconditional loads (index clamped into the run) so that none waits for another
             const int i = i0 + u * WAVE + lane;
             r[u] = ld_stream(g + (i < count ? i : count - 1));
         }
 #pragma unroll
-        for (int u = 0; u < STAGE_BATCH; ++u) {
+        for (int u = 0; u < BATCH; ++u) {
             const int i = i0 + u * WAVE + lane;
             if (i < count) s[i] = r[u];
         }

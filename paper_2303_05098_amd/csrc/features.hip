@@ -35,8 +35,12 @@ namespace mo {
 static_assert(SHORT_ROW <= WAVE, "one candidate diagonal per lane");
 
 constexpr int TB = 512;           // threads per block of the traversal: 8 waves share one hash table
-constexpr int TCAP = 2 * FCAP;    // entries a wave stages at a time: 64 rows of SHORT_ROW entries, so that the rows of a
-                                  // wave are walked in one go whenever they are all short
+constexpr int TCAP = 1920;        // entries a wave stages at a time: 64 rows of up to 30 entries are walked in one go.  Not
+                                  // 2048 (64 rows of SHORT_ROW entries): with the hash table that made 82 120 bytes of LDS per
+                                  // block, 200 bytes too many for two blocks per CU, and the kernel ran with 8 waves per CU
+static_assert((TB / WAVE) * TCAP * 4 + HT_SIZE * 8 + 1024 <= 80 * 1024, "two traversal blocks must fit one CU's 160 KB of LDS");
+constexpr int TSTAGE = 16;        // column loads a lane has in flight while a chunk is staged: two round trips to memory per
+                                  // full chunk (8: four round trips, with the few waves this kernel runs each one shows)
 constexpr int TRAV_BLOCKS = 512;  // at most this many blocks: every block ends with one atomic per distinct
                                   // diagonal it met, and same-address atomics are served one after the other
 
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
             const int last = first + nrun - 1;
             const int end = __builtin_amdgcn_readlane(hi, last);
             const int total = end - start;   // 0 .. TCAP
-            if (total > 0) stage_to_lds(col_idx + start, s_col, total, lane);
+            if (total > 0) stage_to_lds<int32_t, TSTAGE>(col_idx + start, s_col, total, lane);
             const bool mine_now = is_short && lane >= first && lane <= last && hi <= end;
             const int cnt = mine_now ? len : 0;   // <= SHORT_ROW
             const int32_t *mine = s_col + (mine_now ? lo - start : 0);

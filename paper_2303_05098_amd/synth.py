@@ -292,9 +292,9 @@ def _sweep_extra(k: int, n_lo: float, n_hi: float):
 
 
 def sweep_matrix(k: int, n_lo: float = 1e3, n_hi: float = 4e6):
-    """Matrix k of the tuner sweep: for k < SWEEP_BASE family = k mod 5, target n log-uniform in [n_lo, n_hi]; beyond
-    that see _sweep_extra.  Returns (family_name, m, n, row_ptr, col_idx, val)."""
-    if k >= SWEEP_BASE:
+    """Matrix k of the tuner sweep: family = k mod 5, target n log-uniform in [n_lo, n_hi], except for the SWEEP_EXTRA
+    indices from SWEEP_BASE on (see _sweep_extra).  Returns (family_name, m, n, row_ptr, col_idx, val)."""
+    if SWEEP_BASE <= k < SWEEP_BASE + SWEEP_EXTRA:
         return _sweep_extra(k, n_lo, n_hi)
     seed = BASE_SEED + 1000 + k
     fam = FAMILIES[k % 5]

@@ -199,3 +199,27 @@ def test_argument_checks_need_no_gpu():
     i64 = C.c_int64()
     assert mo.lib.mo_mtx_read(None, C.byref(i64), C.byref(i64), C.byref(i64), C.byref(h), C.byref(h), C.byref(h)) == mo.MO_E_NULL
     mo.lib.mo_host_free(None)
+
+
+def test_features_finalize_matches_the_oracle():
+    """The host half of mo_features on its own (Table I): from the oracle's integer counts it must give the oracle's
+    ten doubles bit for bit, on matrices with empty rows, rectangular shapes and a large closed-form case."""
+    cases = [synth.config(1), synth.random_csr(300, 1000, 0.02, 5, 0.3), synth.random_csr(1000, 130, 0.05, 6, 0.1),
+             synth.config(3, 1 / 64), synth.config(2, 0.1)]
+    for m, n, rp, ci, v in cases:
+        ti, tj, _ = ref.csr_to_triplets(rp, ci, v)
+        fo, io = ref.features(m, n, ti, tj)
+        f = mo.mo_features_finalize(io)
+        assert f.tobytes() == fo.tobytes()
+    # 128^3 stencil from its closed-form integers (no matrix needed)
+    g = 128
+    nnz = (3 * g - 2) ** 3
+    counts = {27: (g - 2) ** 3, 18: 6 * (g - 2) ** 2, 12: 12 * (g - 2), 8: 8}
+    ints = dict(m=g ** 3, n=g ** 3, nnz=nnz, max_row=27, min_row=8, n_diag=27, n_true_diag=27,
+                sum_sq_row=sum(k * k * c for k, c in counts.items()))
+    f = mo.mo_features_finalize(ints)
+    assert f[3] == nnz / g ** 3 and abs(f[7] - 1.9148405) < 1e-6 and f[8] == 27.0
+    bad = dict(ints, m=0)
+    with pytest.raises(mo.MoError) as e:
+        mo.mo_features_finalize(bad)
+    assert e.value.status == mo.MO_E_SHAPE

@@ -113,3 +113,39 @@ def test_feature_time_updates_lay_over_records(tmp_path):
     import pytest
     with pytest.raises(ValueError):
         sweep.load([str(a), str(b)])
+
+
+def test_labels_with_tolerance():
+    """The training label is the lowest id among the formats within the tolerance of the fastest; infeasible formats
+    never win; tolerance 0 is mo_pick."""
+    ms = np.array([[4.0, 2.0, 1.0, np.nan, 3.0, 1.01],       # DIA and HDC within 2 %: DIA (lower id)
+                   [1.0, 2.0, np.nan, np.nan, 0.99, 8.0],     # HYB fastest, COO within 2 %: COO
+                   [np.nan, 5.0, np.nan, np.nan, np.nan, 5.0],  # exact tie CSR / HDC: CSR
+                   [3.0, 2.0, 1.0, 1.5, 1.021, 1.03]])        # nothing within 2 % of DIA but DIA
+    assert sweep.labels_with_tolerance(ms, 0.02).tolist() == [2, 0, 1, 2]
+    strict = sweep.labels_with_tolerance(ms, 0.0)
+    assert strict.tolist() == [mo.mo_pick(row) for row in ms] == [2, 4, 1, 2]
+    # never slower than (1 + tol) times the fastest
+    t = np.where(np.isnan(ms), np.inf, ms)
+    lab = sweep.labels_with_tolerance(ms, 0.02)
+    assert np.all(t[np.arange(4), lab] <= 1.02 * t.min(axis=1))
+
+
+def test_extra_sweep_matrices():
+    """Indices 2048 .. 2559: clustered bands on even indices, the benchmark configurations on odd ones (the first four at
+    their own size); every other index keeps the five rotating families."""
+    from paper_2303_05098_amd import synth
+    fam, m, n, rp, ci, v = synth.sweep_matrix(2052, 1e3, 2e4)
+    assert fam == "banded_clustered" and m == n
+    d = np.unique(ci.astype(np.int64) - np.repeat(np.arange(m), np.diff(rp)))
+    cnt = np.bincount(ci.astype(np.int64) - np.repeat(np.arange(m), np.diff(rp)) + m - 1, minlength=2 * m - 1)
+    full = np.nonzero(cnt * 2 >= m)[0] - (m - 1)                 # the band: diagonals populated over more than half their length
+    assert 0 in full and np.array_equal(full, -full[::-1])       # symmetric clusters around the main diagonal
+    assert d.size >= full.size
+    assert synth.sweep_matrix(2049)[0] == "config1_scaled" and synth.sweep_matrix(2049)[1] == 4096
+    fam, m = synth.sweep_matrix(2065, 1e3, 2e4)[:2]
+    assert fam == "config1_scaled" and m != 4096
+    assert synth.sweep_matrix(2560, 1e3, 2e4)[0] == synth.FAMILIES[2560 % 5]
+    assert synth.sweep_matrix(5003, 1e3, 2e4)[0] == synth.FAMILIES[5003 % 5]
+    a, b = synth.sweep_matrix(2052, 1e3, 2e4), synth.sweep_matrix(2052, 1e3, 2e4)
+    assert all(np.array_equal(x, y) for x, y in zip(a[3:], b[3:]))
