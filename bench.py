@@ -32,13 +32,16 @@ HBM_PEAK_GBS = 8000.0
 TRAFFIC_SOURCE = {(2, "f64"): "profiles/spmv_all_formats_stencil27_128_f64.md", (3, "f64"): "profiles/spmv_all_formats_lognormal_f64.md",
                   (4, "f64"): "profiles/spmv_all_formats_banded_scatter_f64.md", (4, "f32"): "profiles/spmv_all_formats_banded_scatter_f32.md"}
 MEASURED_TRAFFIC = {
-    (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 765.5e6, (2, "f64", "ELL"): 710.2e6,
-    (2, "f64", "COO"): 959.4e6 + 9.1e6,
-    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 736.2e6, (4, "f64", "ELL"): 784.5e6, (4, "f64", "HYB"): 684.9e6,
-    (4, "f64", "COO"): 835.6e6 + 5.9e6,
-    (4, "f32", "HDC"): 331.4e6, (4, "f32", "HYB"): 482.6e6, (4, "f32", "CSR"): 502.8e6, (4, "f32", "ELL"): 565.9e6,
-    (4, "f32", "COO"): 640.4e6 + 5.8e6,
-    (3, "f64", "CSR"): 1333.9e6, (3, "f64", "HYB"): 659.5e6 + 722.1e6, (3, "f64", "COO"): 1524.7e6 + 8.4e6,
+    (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 715.1e6, (2, "f64", "ELL"): 710.3e6,
+    (2, "f64", "HYB"): 710.3e6, (2, "f64", "COO"): 930.7e6 + 4.5e6,
+    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 688.7e6, (4, "f64", "ELL"): 784.4e6, (4, "f64", "HYB"): 684.9e6,
+    (4, "f64", "COO"): 827.5e6 + 3.0e6,
+    (4, "f32", "HDC"): 331.4e6, (4, "f32", "HYB"): 482.4e6, (4, "f32", "CSR"): 483.5e6, (4, "f32", "ELL"): 565.9e6,
+    (4, "f32", "COO"): 624.3e6 + 2.9e6,
+    # lognormal rows: bytes counted at the L2 boundary (x gathers that miss L2 move a 128-byte line each); CSR = two passes
+    # over column halves, HDC (no true diagonal) = the one-pass CSR kernel
+    (3, "f64", "CSR"): 220.3e6 + 232.6e6 + 1.8e6, (3, "f64", "HDC"): 1333.7e6 + 0.9e6, (3, "f64", "HYB"): 658.8e6 + 659.8e6 + 0.9e6,
+    (3, "f64", "COO"): 8.4e6 + 1410.5e6 + 0.9e6,
 }
 REPS = 1000
 LLC_BYTES = 256 << 20     # last-level (Infinity) cache of the MI355X

@@ -15,15 +15,24 @@ def records():
     return sweep.load([os.path.join(MODELS, "mi355x_sweep.jsonl")])
 
 
+def report():
+    return json.load(open(os.path.join(MODELS, "mi355x_sweep_report.json")))
+
+
 def arrays(recs):
+    """Features and training labels as `sweep fit` forms them: label = lowest id within the reported tolerance of the
+    fastest format."""
     X = np.array([r["features"] for r in recs], dtype=np.float64)
-    y = np.array([r["best"] for r in recs], dtype=np.int64)
+    ms = np.array([[np.nan if t is None else t for t in r["ms_per_rep"]] for r in recs], dtype=np.float64)
+    y = sweep.labels_with_tolerance(ms, report()["label_tolerance"])
     return X, y
 
 
 def test_committed_records():
     recs = records()
-    assert len(recs) == 2048 and [r["k"] for r in recs] == list(range(2048))
+    assert len(recs) == 2560 and [r["k"] for r in recs] == list(range(2560))
+    assert sum(r["family"] == "banded_clustered" for r in recs) == 256
+    assert [r["family"] for r in recs if r["k"] in sweep.NAMED_CONFIG_RECORDS] == ["config%d_scaled" % c for c in (1, 2, 3, 4)]
     for r in recs:
         ms = [math.nan if t is None else t for t in r["ms_per_rep"]]
         assert r["best"] == mo.mo_pick(ms)                      # label = argmin of the timings (Section VII-A)
@@ -36,9 +45,12 @@ def test_committed_report_is_what_the_records_give():
     X, y = arrays(recs)
     rep = json.load(open(os.path.join(MODELS, "mi355x_sweep_report.json")))
     test = fit.train_test_split(y)
-    assert (rep["n"], rep["n_train"], rep["n_test"]) == (2048, int((~test).sum()), int(test.sum()))
+    assert (rep["n"], rep["n_train"], rep["n_test"]) == (2560, int((~test).sum()), int(test.sum()))
     assert abs(rep["n_test"] / rep["n"] - 0.2) < 0.005
-    assert sum(rep["class_histogram"].values()) == 2048
+    assert sum(rep["class_histogram"].values()) == 2560
+    assert rep["class_histogram"] == {sweep.FORMATS[c]: int((y == c).sum()) for c in range(6)}
+    strict = np.array([r["best"] for r in recs])
+    assert rep["labels_changed_by_tolerance"] == int((y != strict).sum())
     for kind, base in (("tree", fit.BASELINE_TREE), ("forest", fit.BASELINE_FOREST)):
         assert rep[kind]["baseline"]["test"]["opts"] == base
         for which in ("baseline", "tuned"):
