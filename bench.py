@@ -39,7 +39,7 @@ MEASURED_TRAFFIC = {
     (4, "f32", "HDC"): 331.4e6, (4, "f32", "HYB"): 482.4e6, (4, "f32", "CSR"): 483.5e6, (4, "f32", "ELL"): 565.9e6,
     (4, "f32", "COO"): 624.3e6 + 2.9e6,
     # lognormal rows: bytes counted at the L2 boundary (x gathers that miss L2 move a 128-byte line each); CSR = two passes
-    # over column halves, HDC (no true diagonal) = the one-pass CSR kernel
+    # over column slices, HDC (no true diagonal) = the one-pass CSR kernel
     (3, "f64", "CSR"): 220.3e6 + 232.6e6 + 1.8e6, (3, "f64", "HDC"): 1333.7e6 + 0.9e6, (3, "f64", "HYB"): 658.8e6 + 659.8e6 + 0.9e6,
     (3, "f64", "COO"): 8.4e6 + 1410.5e6 + 0.9e6,
 }

@@ -168,9 +168,9 @@ mo_status mo_spmv(const mo_matrix *a, const void *x, void *y, void *stream)
     switch (a->fmt) {
     case MO_COO: return spmv_coo(*a, x, y, false, s);
     case MO_CSR:
-        if (a->csr_half[0]) {
-            MO_TRY(spmv_csr(*a->csr_half[0], x, y, false, s));
-            return spmv_csr(*a->csr_half[1], x, y, true, s);
+        if (!a->csr_slices.empty()) {
+            for (size_t q = 0; q < a->csr_slices.size(); ++q) MO_TRY(spmv_csr(*a->csr_slices[q], x, y, q > 0, s));
+            return MO_OK;
         }
         return spmv_csr(*a, x, y, false, s);
     case MO_DIA: return spmv_dia(*a, x, y, s);
@@ -207,7 +207,10 @@ mo_status mo_spmv_kernels(const mo_matrix *a, char *buf, size_t cap)
         s += a->coo_tiles > 1 ? "k_coo_tile+k_coo_fixup" : "k_coo_tile";
         break;
     case MO_CSR:
-        if (a->csr_half[0]) { s = std::string(csr_kernel(*a->csr_half[0])) + "+" + csr_kernel(*a->csr_half[1]) + "(column halves)"; break; }
+        if (!a->csr_slices.empty()) {
+            s = std::to_string(a->csr_slices.size()) + " column slices x (" + csr_kernel(*a->csr_slices[0]) + ")";
+            break;
+        }
         s = csr_kernel(*a);
         break;
     case MO_DIA: s = dia_kernel(*a, false); break;
@@ -343,7 +346,7 @@ mo_status mo_matrix_export(const mo_matrix *a, mo_matrix_view *out)
 void mo_matrix_free(mo_matrix *a)
 {
     if (!a) return;
-    for (mo_matrix *half : a->csr_half) mo_matrix_free(half);
+    for (mo_matrix *part : a->csr_slices) mo_matrix_free(part);
     for (void *p : a->owned) dev_free(p, a->home);
     delete a;
 }

@@ -508,7 +508,7 @@ struct Builder {
     }
     void release()
     {
-        for (mo_matrix *half : h->csr_half) mo_matrix_free(half);
+        for (mo_matrix *part : h->csr_slices) mo_matrix_free(part);
         for (void *p : h->owned) dev_free(p, s);
         delete h;
         h = nullptr;
@@ -554,84 +554,81 @@ mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, i
     return MO_OK;
 }
 
-// ------------------------------------------------------------------ column halves of a CSR matrix
-// Columns ascend inside a row and rows follow each other, so the entries with col < boundary, taken in storage
-// order, are the CSR arrays of the left half of the matrix, and the others those of the right half: a stable
-// partition of the entry array.  flag -> exclusive scan -> scatter; the row pointers of the halves are the scanned
-// flags read at the row starts.
-__global__ __launch_bounds__(CB) void k_half_flags(const int32_t *__restrict__ col_idx, int64_t nnz, int32_t boundary, int32_t *__restrict__ flag)
-{
-    const int64_t stride = (int64_t)gridDim.x * CB;
-    for (int64_t p = (int64_t)blockIdx.x * CB + threadIdx.x; p < nnz; p += stride) flag[p] = ld_stream(col_idx + p) < boundary ? 1 : 0;
-}
-
-template <typename T>
-__global__ __launch_bounds__(CB) void k_half_scatter(const int32_t *__restrict__ col_idx, const T *__restrict__ val, int64_t nnz, int32_t boundary,
-                                                      const int32_t *__restrict__ left_before, int32_t *__restrict__ col0, T *__restrict__ val0,
-                                                      int32_t *__restrict__ col1, T *__restrict__ val1)
+// ------------------------------------------------------------------ column slices of a CSR matrix
+// Columns ascend inside a row and rows follow each other, so the entries with lo <= col < hi, taken in storage order,
+// are the CSR arrays of that column slice of the matrix: a stable selection from the entry array.  Per slice: flag ->
+// exclusive scan -> scatter; the row pointers of the slice are the scanned flags read at the row starts.
+__global__ __launch_bounds__(CB) void k_slice_flags(const int32_t *__restrict__ col_idx, int64_t nnz, int32_t lo, int32_t hi, int32_t *__restrict__ flag)
 {
     const int64_t stride = (int64_t)gridDim.x * CB;
     for (int64_t p = (int64_t)blockIdx.x * CB + threadIdx.x; p < nnz; p += stride) {
         const int32_t c = ld_stream(col_idx + p);
-        const T v = ld_stream(val + p);
-        const int64_t lb = left_before[p];
-        if (c < boundary) { col0[lb] = c; val0[lb] = v; }
-        else { col1[p - lb] = c; val1[p - lb] = v; }
+        flag[p] = (c >= lo && c < hi) ? 1 : 0;
     }
 }
 
-__global__ __launch_bounds__(CB) void k_half_row_ptr(const int32_t *__restrict__ row_ptr, int64_t m, const int32_t *__restrict__ left_before,
-                                                      int32_t *__restrict__ rp0, int32_t *__restrict__ rp1)
+template <typename T>
+__global__ __launch_bounds__(CB) void k_slice_scatter(const int32_t *__restrict__ col_idx, const T *__restrict__ val, int64_t nnz, int32_t lo,
+                                                       int32_t hi, const int32_t *__restrict__ before, int32_t *__restrict__ col_s,
+                                                       T *__restrict__ val_s)
+{
+    const int64_t stride = (int64_t)gridDim.x * CB;
+    for (int64_t p = (int64_t)blockIdx.x * CB + threadIdx.x; p < nnz; p += stride) {
+        const int32_t c = ld_stream(col_idx + p);
+        if (c >= lo && c < hi) {
+            const int32_t d = before[p];
+            col_s[d] = c;
+            val_s[d] = ld_stream(val + p);
+        }
+    }
+}
+
+__global__ __launch_bounds__(CB) void k_slice_row_ptr(const int32_t *__restrict__ row_ptr, int64_t m, const int32_t *__restrict__ before,
+                                                       int32_t *__restrict__ rp_s)
 {
     const int64_t r = (int64_t)blockIdx.x * CB + threadIdx.x;
     if (r > m) return;
-    const int32_t p = row_ptr[r];
-    const int32_t l = left_before[p];   // left_before has nnz + 1 entries
-    rp0[r] = l;
-    rp1[r] = p - l;
+    rp_s[r] = before[row_ptr[r]];   // `before` has nnz + 1 entries
 }
 
 mo_status plan_csr(Builder &b, const int32_t *row_ptr, int64_t m, int64_t nnz, int64_t max_row);
 
 template <typename T>
-mo_status build_csr_halves(const mo_csr &a, int64_t max_row, Builder &parent, Scratch &scr)
+mo_status build_csr_slices(const mo_csr &a, int nslices, int64_t max_row, Builder &parent, Scratch &scr)
 {
     hipStream_t s = parent.s;
-    const int32_t boundary = (int32_t)((a.n + 1) / 2);
     int32_t *flag = (int32_t *)scr.get((size_t)a.nnz * 4);
-    int32_t *left_before = (int32_t *)scr.get((size_t)(a.nnz + 1) * 4);
+    int32_t *before = (int32_t *)scr.get((size_t)(a.nnz + 1) * 4);
     void *tmp = scr.get(scan_tmp_bytes(a.nnz));
-    if (!flag || !left_before || !tmp) return MO_E_ALLOC;
+    if (!flag || !before || !tmp) return MO_E_ALLOC;
     const unsigned g = fill_grid(a.nnz);
-    hipLaunchKernelGGL(k_half_flags, dim3(g), dim3(CB), 0, s, a.col_idx, a.nnz, boundary, flag);
-    MO_LAUNCH_CHECK();
-    MO_TRY(exclusive_scan_i32(flag, left_before, a.nnz, tmp, s));
-    int32_t left = 0;
-    MO_HIP(hipMemcpyAsync(&left, left_before + a.nnz, 4, hipMemcpyDeviceToHost, s));
-    MO_HIP(hipStreamSynchronize(s));
-    const int64_t cnt[2] = {left, a.nnz - left};
-    Builder part[2] = {Builder(s), Builder(s)};
-    int32_t *rp[2], *col[2];
-    T *val[2];
-    for (int q = 0; q < 2; ++q) {
-        if (!part[q].h) return MO_E_ALLOC;
-        mo_matrix *h = part[q].h;
-        h->fmt = MO_CSR; h->dtype = a.dtype; h->m = a.m; h->n = a.n; h->nnz = cnt[q]; h->nnz_csr = cnt[q];
+    const int64_t width = (a.n + nslices - 1) / nslices;
+    for (int q = 0; q < nslices; ++q) {
+        const int32_t lo = (int32_t)(q * width), hi = (int32_t)((q + 1) * width < a.n ? (q + 1) * width : a.n);
+        hipLaunchKernelGGL(k_slice_flags, dim3(g), dim3(CB), 0, s, a.col_idx, a.nnz, lo, hi, flag);
+        MO_LAUNCH_CHECK();
+        MO_TRY(exclusive_scan_i32(flag, before, a.nnz, tmp, s));
+        int32_t cnt = 0;
+        MO_HIP(hipMemcpyAsync(&cnt, before + a.nnz, 4, hipMemcpyDeviceToHost, s));
+        MO_HIP(hipStreamSynchronize(s));
+        Builder part(s);
+        if (!part.h) return MO_E_ALLOC;
+        mo_matrix *h = part.h;
+        h->fmt = MO_CSR; h->dtype = a.dtype; h->m = a.m; h->n = a.n; h->nnz = cnt; h->nnz_csr = cnt;
         h->ld = (a.m + 63) & ~(int64_t)63;
-        rp[q] = (int32_t *)part[q].own((size_t)(a.m + 1) * 4);
-        col[q] = (int32_t *)part[q].own((size_t)(cnt[q] > 0 ? cnt[q] : 1) * 4);
-        val[q] = (T *)part[q].own((size_t)(cnt[q] > 0 ? cnt[q] : 1) * sizeof(T));
-        if (part[q].failed) return MO_E_ALLOC;
-        h->csr_row_ptr = rp[q]; h->csr_col = col[q]; h->csr_val = val[q];
+        int32_t *rp = (int32_t *)part.own((size_t)(a.m + 1) * 4);
+        int32_t *col = (int32_t *)part.own((size_t)(cnt > 0 ? cnt : 1) * 4);
+        T *val = (T *)part.own((size_t)(cnt > 0 ? cnt : 1) * sizeof(T));
+        if (part.failed) return MO_E_ALLOC;
+        h->csr_row_ptr = rp; h->csr_col = col; h->csr_val = val;
+        hipLaunchKernelGGL(k_slice_scatter<T>, dim3(g), dim3(CB), 0, s, a.col_idx, (const T *)a.val, a.nnz, lo, hi, before, col, val);
+        MO_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_slice_row_ptr, dim3(blocks_for(a.m + 1)), dim3(CB), 0, s, a.row_ptr, a.m, before, rp);
+        MO_LAUNCH_CHECK();
+        MO_TRY(plan_csr(part, rp, a.m, cnt, max_row));
+        MO_HIP(hipStreamSynchronize(s));   // `flag` and `before` are rewritten for the next slice
+        parent.h->csr_slices.push_back(part.take());
     }
-    hipLaunchKernelGGL(k_half_scatter<T>, dim3(g), dim3(CB), 0, s, a.col_idx, (const T *)a.val, a.nnz, boundary, left_before, col[0], val[0],
-                       col[1], val[1]);
-    MO_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_half_row_ptr, dim3(blocks_for(a.m + 1)), dim3(CB), 0, s, a.row_ptr, a.m, left_before, rp[0], rp[1]);
-    MO_LAUNCH_CHECK();
-    for (int q = 0; q < 2; ++q) MO_TRY(plan_csr(part[q], rp[q], a.m, cnt[q], max_row));
-    MO_HIP(hipStreamSynchronize(s));
-    for (int q = 0; q < 2; ++q) parent.h->csr_half[q] = part[q].take();
     return MO_OK;
 }
 
@@ -731,15 +728,19 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         h->csr_row_ptr = a.row_ptr; h->csr_col = a.col_idx; h->csr_val = a.val; h->nnz_csr = a.nnz;
         MO_TRY(plan_csr(b, a.row_ptr, a.m, a.nnz, an.max_row));
         MO_TRY(plan_x_windows(a.row_ptr, a.col_idx, a.m, a.nnz, &h->xplan, s));
-        // Scattered columns (no populated diagonals) and an x that one XCD's L2 cannot hold, though half of it fits: the
-        // gathers of such a matrix miss L2 half of the time and every miss moves a 128-byte line.  Two passes over
-        // column halves keep each pass's part of x in L2: 185 -> 135 us on the lognormal configuration (two launches
-        // over the halves; four quarters: 147 us, eight: 171 us, as the per-pass row pointers and y traffic grow).
+        // Scattered columns (no populated diagonals) and an x that one XCD's L2 cannot hold: the gathers of such a
+        // matrix miss L2 most of the time and every miss moves a 128-byte line.  Passes over column slices of at most
+        // 5 MB keep each pass's part of x in L2.  Measured (separate launches per slice): lognormal configuration, x =
+        // 8 MB: 185 us in one pass, 135 in two, 147 in four, 171 in eight (the per-pass row pointers and y traffic
+        // grow); 3.8 M rows, 106 M entries, x = 31 MB: 1725 us in one pass, 1082 in four, 819 in eight, 982 in
+        // sixteen; 1.6 M rows of 54 entries, x = 12.5 MB: 1071 us in one pass, 553 in four, 580 in eight.
         {
             const int64_t xb = a.n * (int64_t)sizeof(T);
-            if (h->xplan.ncl == 0 && xb >= CSR_HALF_MIN_X_BYTES && xb <= CSR_HALF_MAX_X_BYTES && a.nnz >= CSR_HALF_MIN_NNZ &&
-                a.nnz >= 4 * a.m)
-                MO_TRY(build_csr_halves<T>(a, an.max_row, b, scr));
+            if (h->xplan.ncl == 0 && xb >= CSR_SLICE_MIN_X_BYTES && a.nnz >= CSR_SLICE_MIN_NNZ && a.nnz >= 4 * a.m) {
+                int nslices = 2;
+                while (nslices < CSR_MAX_SLICES && xb > (int64_t)nslices * CSR_SLICE_X_BYTES) nslices <<= 1;
+                MO_TRY(build_csr_slices<T>(a, nslices, an.max_row, b, scr));
+            }
         }
         break;
     }

@@ -131,10 +131,10 @@ struct mo_matrix {
     int32_t coo_strip = 4;            // entries per thread of the COO kernel (8, 4 or 2)
     int32_t *coo_carry_row = nullptr; // one per COO tile
     void *coo_carry_val = nullptr;
-    // MO_CSR on a matrix with scattered columns whose x exceeds one XCD's L2: the entries again, regrouped into two
-    // column halves (each a CSR matrix of its own over all rows: launch data, not part of the format).  y = A0 x, then
-    // y += A1 x: each pass gathers from half of x, which stays in L2.
-    mo_matrix *csr_half[2] = {nullptr, nullptr};
+    // MO_CSR on a matrix with scattered columns whose x exceeds one XCD's L2: the entries again, regrouped into 2, 4 or 8
+    // column slices (each a CSR matrix of its own over all rows: launch data, not part of the format).  y = A_0 x, then
+    // y += A_s x for the others: each pass gathers from one slice of x, which stays in L2.
+    std::vector<mo_matrix *> csr_slices;
     mo::XPlan xplan;                  // x windows for the kernels that gather x by column index
     // everything this handle owns
     std::vector<void *> owned;
@@ -192,9 +192,11 @@ mo_status spmv_hdc_fused(const mo_matrix &a, const void *x, void *y, hipStream_t
 bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_elems, std::vector<int32_t> *xpos,
                        std::vector<int32_t> *clusters, int64_t *total_elems);
 constexpr int64_t DIA_LDS_BYTES = 48 * 1024;  // LDS budget for staged x windows per block
-// column halves of a CSR handle: x larger than one XCD's L2 (4 MB) but with halves that fit one
-constexpr int64_t CSR_HALF_MIN_X_BYTES = 5 * 1024 * 1024, CSR_HALF_MAX_X_BYTES = 10 * 1024 * 1024;
-constexpr int64_t CSR_HALF_MIN_NNZ = 1 << 22;
+// column slices of a CSR handle: from an x of this size on (one XCD's L2 is 4 MB), so many that a slice is at most
+// CSR_SLICE_X_BYTES, at most CSR_MAX_SLICES; only for matrices of at least CSR_SLICE_MIN_NNZ entries
+constexpr int64_t CSR_SLICE_MIN_X_BYTES = 5 * 1024 * 1024, CSR_SLICE_X_BYTES = 5 * 1024 * 1024;
+constexpr int CSR_MAX_SLICES = 8;
+constexpr int64_t CSR_SLICE_MIN_NNZ = 1 << 22;
 constexpr int64_t HDC_FUSED_MAX_ROW = 64;   // longest row for which HDC runs as one fused kernel
 mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s);
 
