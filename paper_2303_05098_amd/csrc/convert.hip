@@ -736,7 +736,11 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         // sixteen; 1.6 M rows of 54 entries, x = 12.5 MB: 1071 us in one pass, 553 in four, 580 in eight.
         {
             const int64_t xb = a.n * (int64_t)sizeof(T);
-            if (h->xplan.ncl == 0 && xb >= CSR_SLICE_MIN_X_BYTES && a.nnz >= CSR_SLICE_MIN_NNZ && a.nnz >= 4 * a.m) {
+            // every pass re-reads the row pointers and y: worth it only when the rows are long enough for the size of
+            // x (over the sweep's 189 scattered matrices above 5 MB of x the passes win from about 64 MB x entries per
+            // row on, by up to 2.3x, and lose up to 13 % below)
+            const bool long_rows = (__int128)a.nnz * (__int128)xb >= (__int128)CSR_SLICE_MIN_WORK * (__int128)a.m;
+            if (h->xplan.ncl == 0 && xb >= CSR_SLICE_MIN_X_BYTES && a.nnz >= CSR_SLICE_MIN_NNZ && long_rows) {
                 int nslices = 2;
                 while (nslices < CSR_MAX_SLICES && xb > (int64_t)nslices * CSR_SLICE_X_BYTES) nslices <<= 1;
                 MO_TRY(build_csr_slices<T>(a, nslices, an.max_row, b, scr));

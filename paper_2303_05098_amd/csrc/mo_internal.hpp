@@ -193,10 +193,12 @@ bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_e
                        std::vector<int32_t> *clusters, int64_t *total_elems);
 constexpr int64_t DIA_LDS_BYTES = 48 * 1024;  // LDS budget for staged x windows per block
 // column slices of a CSR handle: from an x of this size on (one XCD's L2 is 4 MB), so many that a slice is at most
-// CSR_SLICE_X_BYTES, at most CSR_MAX_SLICES; only for matrices of at least CSR_SLICE_MIN_NNZ entries
+// CSR_SLICE_X_BYTES, at most CSR_MAX_SLICES; only for matrices of at least CSR_SLICE_MIN_NNZ entries whose rows are
+// long enough (CSR_SLICE_MIN_WORK)
 constexpr int64_t CSR_SLICE_MIN_X_BYTES = 5 * 1024 * 1024, CSR_SLICE_X_BYTES = 5 * 1024 * 1024;
 constexpr int CSR_MAX_SLICES = 8;
 constexpr int64_t CSR_SLICE_MIN_NNZ = 1 << 22;
+constexpr int64_t CSR_SLICE_MIN_WORK = (int64_t)64 << 20;   // mean entries per row x bytes of x
 constexpr int64_t HDC_FUSED_MAX_ROW = 64;   // longest row for which HDC runs as one fused kernel
 mo_status fill_zero(void *p, int64_t n_elems, mo_dtype dt, hipStream_t s);
 

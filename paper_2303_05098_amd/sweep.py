@@ -32,13 +32,13 @@ FORMATS = ("COO", "CSR", "DIA", "ELL", "HYB", "HDC")
 NAMED_CONFIG_RECORDS = tuple(synth.SWEEP_BASE + 2 * i + 1 for i in range(4))   # configurations 1 .. 4 at full size
 
 
-def run(first: int, count: int, out: str, reps: int, n_hi: float) -> None:
+def run(first: int, count: int, out: str, reps: int, n_hi: float, ks=None) -> None:
     import torch
 
     from . import mo
 
     with open(out, "a") as fh:
-        for k in range(first, first + count):
+        for k in (ks if ks is not None else range(first, first + count)):
             t0 = time.perf_counter()
             fam, m, n, rp, ci, v = synth.sweep_matrix(k, 1e3, n_hi)
             t_gen = time.perf_counter() - t0
@@ -244,6 +244,7 @@ def main(argv=None) -> int:
     r.add_argument("--out", required=True)
     r.add_argument("--reps", type=int, default=1000)
     r.add_argument("--n-hi", type=float, default=4e6)
+    r.add_argument("--ks", default=None, help="comma-separated matrix indices to run instead of --first / --count (re-runs of single records)")
     q = sub.add_parser("features")
     q.add_argument("--first", type=int, default=0)
     q.add_argument("--count", type=int, default=256)
@@ -261,7 +262,7 @@ def main(argv=None) -> int:
     f.add_argument("--grid", default=None, help="JSON file {\"tree\": {...}, \"forest\": {...}} replacing the built-in grids")
     args = ap.parse_args(argv)
     if args.cmd == "run":
-        run(args.first, args.count, args.out, args.reps, args.n_hi)
+        run(args.first, args.count, args.out, args.reps, args.n_hi, [int(t) for t in args.ks.split(",")] if args.ks else None)
         return 0
     if args.cmd == "features":
         run_features(args.first, args.count, args.out, args.n_hi)
