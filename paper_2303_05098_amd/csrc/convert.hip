@@ -692,6 +692,32 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
             h->dia_ncl = (int32_t)(ncl / 3);
             h->dia_lds_elems = elems;
         }
+        // the same for the multi-vector product: blocks of SPMM_ROWS rows; kept when a 16-byte piece per row of X fits
+        std::vector<int32_t> mxpos, mcl;
+        int64_t melems = 0;
+        if (plan_dia_clusters(hoff, SPMM_ROWS, SPMM_WIN_BYTES / 16, &mxpos, &mcl, &melems)) {
+            // Every window is at least SPMM_ROWS long, so a run of SPMM_ROWS staged rows lies in at most two windows.
+            const int64_t nrun = (melems + SPMM_ROWS - 1) / SPMM_ROWS;
+            std::vector<int32_t> mmap((size_t)nrun * 3);
+            for (int64_t u = 0; u < nrun; ++u) {
+                size_t q = 0;   // window that holds staged row u * SPMM_ROWS
+                while (q + 5 < mcl.size() && (int64_t)mcl[q + 5] <= u * SPMM_ROWS) q += 3;
+                const bool more = q + 5 < mcl.size();
+                mmap[3 * u] = more ? mcl[q + 5] : (int32_t)melems;
+                mmap[3 * u + 1] = mcl[q] - mcl[q + 2];
+                mmap[3 * u + 2] = more ? mcl[q + 3] - mcl[q + 5] : 0;
+            }
+            h->mm_xpos = (int32_t *)b.own(mxpos.size() * 4);
+            h->mm_map = (int32_t *)b.own(mmap.size() * 4);
+            if (b.failed) return MO_E_ALLOC;
+            const size_t nx = mxpos.size(), ns = mmap.size();
+            b.keep.push_back(std::move(mxpos));
+            b.keep.push_back(std::move(mmap));
+            const std::vector<int32_t> &kx = b.keep[b.keep.size() - 2], &ks = b.keep.back();
+            MO_HIP(hipMemcpyAsync(h->mm_xpos, kx.data(), nx * 4, hipMemcpyHostToDevice, s));
+            MO_HIP(hipMemcpyAsync(h->mm_map, ks.data(), ns * 4, hipMemcpyHostToDevice, s));
+            h->mm_lds_elems = melems;
+        }
     }
     return MO_OK;
 }

@@ -13,6 +13,10 @@
 //      floats) streamed one row per lane with x taken from the row's own neighbourhood, y written, and 1 167 106
 //      random gathers of x (one per row for 28 % of the rows), with and without the gathers: what the scattered
 //      remainder costs any kernel on this memory system, each gather moving a 128-byte line.
+//   6. the rate at which cache-resident data reaches registers, by bytes per lane and load (4, 8, 16) and by where the
+//      data sits (a 2 KB region per block: the CU's L1; 31 regions of 64 KB shared by all blocks, a CU's blocks on
+//      different ones: the XCD's L2): what bounds a kernel that fetches a row of a dense operand per matrix entry (the multi-vector
+//      product) once the matrix stream itself is no longer the limit.
 // Every kernel is timed with events over 20 launches after 3 warm-ups; sizes are printed with the results.
 #include <hip/hip_runtime.h>
 
@@ -206,6 +210,38 @@ static void run_slabs(const char *name)
     CK(hipFree(val)); CK(hipFree(x)); CK(hipFree(y)); CK(hipFree(gcol));
 }
 
+// ------------------------------------------------------------------ 6. cache-resident data into registers
+// Block b reads `region` elements starting at region number (b / 8) mod nregion, 256 consecutive elements per step, round
+// and round.  Blocks b .. b + 7 go to the 8 XCDs, so every XCD sees every region (nregion regions have to fit its L2),
+// and nregion is odd so that the blocks that share a CU (b / 8 apart by multiples of the CUs per XCD) read different ones.
+template <typename VT>
+__global__ __launch_bounds__(256) void k_fill_regs(const VT *__restrict__ p, unsigned region, unsigned nregion, int steps, double *out)
+{
+    const VT *base = p + (size_t)((blockIdx.x / 8) % nregion) * region;
+    float s = 0.f;
+    for (int it = 0; it < steps; it += 8) {
+        VT v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = base[(unsigned)((it + u) * 256 + threadIdx.x) & (region - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            for (unsigned w = 0; w < sizeof(VT) / 4; ++w) s += reinterpret_cast<const float *>(&v[u])[w];   // every loaded word is used
+    }
+    if (s == 1.2345f) out[0] = s;   // never true for the zero-filled input: keeps the loads alive
+}
+
+template <typename VT>
+static void run_fill_regs(const char *what, const void *table, double *out)
+{
+    const unsigned grid = 256 * 8 * 4;
+    const int steps = 512;
+    const double bytes = (double)grid * steps * 256 * sizeof(VT);
+    float ms = time_ms([&] { k_fill_regs<VT><<<grid, 256>>>((const VT *)table, 2048 / sizeof(VT), grid / 8, steps, out); }, 5);
+    std::printf("6 %s per lane, 2 KB per block (L1)                    : %8.1f us  %7.1f GB/s\n", what, ms * 1e3, bytes / ms / 1e6);
+    ms = time_ms([&] { k_fill_regs<VT><<<grid, 256>>>((const VT *)table, 65536 / sizeof(VT), 31, steps, out); }, 5);
+    std::printf("6 %s per lane, 64 KB per block, 31 such regions (L2): %8.1f us  %7.1f GB/s\n", what, ms * 1e3, bytes / ms / 1e6);
+}
+
 int main()
 {
     double *out;
@@ -284,6 +320,15 @@ int main()
     }
     run_slabs<double>("fp64");
     run_slabs<float>("fp32");
+    {
+        void *table;
+        CK(hipMalloc(&table, (size_t)4 << 20));   // 1024 regions of 2 KB or 31 of 64 KB
+        CK(hipMemset(table, 0, (size_t)4 << 20));
+        run_fill_regs<float>(" 4 bytes", table, out);
+        run_fill_regs<float2>(" 8 bytes", table, out);
+        run_fill_regs<float4>("16 bytes", table, out);
+        CK(hipFree(table));
+    }
     CK(hipFree(out));
     return 0;
 }

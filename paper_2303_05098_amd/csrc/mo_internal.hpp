@@ -102,6 +102,12 @@ struct mo_matrix {
     int32_t dia_ncl = 0;
     int64_t dia_lds_elems = 0;
     int32_t *dia_xpos = nullptr, *dia_clusters = nullptr;
+    // the same kind of plan for blocks of SPMM_ROWS rows: windows of X for the multi-vector product
+    int64_t mm_lds_elems = 0;         // staged rows of X per block; 0 = no plan (windows too large), direct kernel
+    int32_t *mm_xpos = nullptr;       // per diagonal: staged row that the block's first matrix row reads
+    int32_t *mm_map = nullptr;        // per run of SPMM_ROWS staged rows: (first staged row of the next window, row of X minus
+                                      // staged row in the run's first window, the same in the next), rows of X relative to the
+                                      // block's first matrix row
     // ELL part
     int64_t k = 0;
     int32_t *ell_col = nullptr;
@@ -192,6 +198,8 @@ mo_status spmv_hdc_fused(const mo_matrix &a, const void *x, void *y, hipStream_t
 bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_elems, std::vector<int32_t> *xpos,
                        std::vector<int32_t> *clusters, int64_t *total_elems);
 constexpr int64_t DIA_LDS_BYTES = 48 * 1024;  // LDS budget for staged x windows per block
+constexpr int SPMM_ROWS = 64;                 // matrix rows per block of the DIA multi-vector kernel with staged windows of X
+constexpr int64_t SPMM_WIN_BYTES = 64 * 1024; // its LDS budget per block (two blocks per CU at least; four below 40 KB)
 // column slices of a CSR handle: from an x of this size on (one XCD's L2 is 4 MB), so many that a slice is at most
 // CSR_SLICE_X_BYTES, at most CSR_MAX_SLICES; only for matrices of at least CSR_SLICE_MIN_NNZ entries whose rows are
 // long enough (CSR_SLICE_MIN_WORK)
