@@ -22,7 +22,6 @@
 namespace mo {
 
 constexpr int MB = 256;
-constexpr int RCAP = 1024;   // entries a wave of 64 rows stages at a time in the row-pointer kernel (fewer rows per wave: fewer entries)
 constexpr int SPMM_LONG_ROW = 64;   // rows longer than this are walked by the whole wave
 
 // Lanes per matrix row for a panel of K columns: pieces of 16 bytes, at least one.
@@ -107,15 +106,14 @@ __device__ __forceinline__ void for_group2(A v, B w, F &&f)
     if constexpr (G == 4) { f(2, group_bcast<G, 2>(v), group_bcast<G, 2>(w)); f(3, group_bcast<G, 3>(v), group_bcast<G, 3>(w)); }
 }
 
-// HDC with short remainder rows: the lanes of row i add the row's run of the CSR remainder after the diagonals (rp ==
-// nullptr: no remainder, or one that a kernel of its own adds).
+// HDC with short remainder rows: the lanes of row i add the row's run [p0, p1) of the CSR remainder after the diagonals
+// (the callers read the two row pointers before the diagonals, so that they have arrived by now; an empty run when
+// there is no remainder, or one that a kernel of its own adds).
 template <typename T, int V>
-__device__ __forceinline__ void add_remainder(T (&acc)[V], const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
-                                              const T *__restrict__ val, int64_t i, const T *__restrict__ xc, int64_t ldk)
+__device__ __forceinline__ void add_remainder(T (&acc)[V], int32_t p0, int32_t p1, const int32_t *__restrict__ col,
+                                              const T *__restrict__ val, const T *__restrict__ xc, int64_t ldk)
 {
-    if (!rp) return;
-    const int32_t p1 = rp[i + 1];
-    for (int32_t p = rp[i]; p < p1; ++p) fma_row<T, V>(acc, val[p], xc + (int64_t)col[p] * ldk);
+    for (int32_t p = p0; p < p1; ++p) fma_row<T, V>(acc, val[p], xc + (int64_t)col[p] * ldk);
 }
 
 constexpr int DIA_U = 8;   // slab values a lane holds per pass of the DIA kernels: DIA_U * G diagonals per pass
@@ -140,6 +138,7 @@ __global__ __launch_bounds__(MB) void k_spmm_dia(const int32_t *__restrict__ off
     for (int v = 0; v < V; ++v) acc[v] = (T)0;
     const T *vp = val + i;
     const T *xc = x + c;
+    const int32_t p0 = rem_rp ? rem_rp[i] : 0, p1 = rem_rp ? rem_rp[i + 1] : 0;
     for (int64_t d0 = 0; d0 < nd; d0 += DIA_U * G) {
         T av[DIA_U];
 #pragma unroll
@@ -167,7 +166,7 @@ __global__ __launch_bounds__(MB) void k_spmm_dia(const int32_t *__restrict__ off
             for (int q = 0; q < XU; ++q) fma_row<T, V>(acc, aa[q], xr[q]);
         }
     }
-    add_remainder<T, V>(acc, rem_rp, rem_col, rem_val, i, xc, ldk);
+    add_remainder<T, V>(acc, p0, p1, rem_col, rem_val, xc, ldk);
     if (i0 < m) store_row<T, V, false>(y + i * ldk + c, acc);
 }
 
@@ -182,7 +181,10 @@ __global__ __launch_bounds__(MB) void k_spmm_dia(const int32_t *__restrict__ off
 // pieces); columns outside [0, n) are staged as 0 and the slab holds +0 there, so the loop needs
 // no bounds test.  A block's LDS footprint allows few waves per CU, so everything a thread needs from memory is
 // requested before the barrier: the first DIA_U * G slab values of its row (shared among the row's lanes as in the
-// direct kernel) and its pieces of the windows, WIN_SB at a time.
+// direct kernel) and its pieces of the windows, WIN_SB at a time.  (A fixed grid of blocks that walk over tiles and
+// request the next tile's pieces into registers while the current one is computed out of LDS was measured slower,
+// 280 against 236 us for 8 columns of the 27-point stencil on 128^3 points: its registers allow three blocks per CU
+// where the LDS allows four, and what counts is how much the resident blocks have in flight.)
 constexpr int WIN_SB = 12;
 template <typename T, int K>
 __global__ __launch_bounds__(SPMM_ROWS * 4) void k_spmm_dia_win(const int32_t *__restrict__ xpos, const int32_t *__restrict__ map, int elems,
@@ -199,6 +201,7 @@ __global__ __launch_bounds__(SPMM_ROWS * 4) void k_spmm_dia_win(const int32_t *_
     const int r = (int)threadIdx.x / G, cg = (int)threadIdx.x % G, c = cg * V;
     const int64_t i0 = row0 + r, i = i0 < m ? i0 : m - 1;
     const T *vp = val + i;
+    const int32_t p0 = rem_rp ? rem_rp[i] : 0, p1 = rem_rp ? rem_rp[i + 1] : 0;
     T av[DIA_U];
 #pragma unroll
     for (int u = 0; u < DIA_U; ++u) {
@@ -252,14 +255,14 @@ __global__ __launch_bounds__(SPMM_ROWS * 4) void k_spmm_dia_win(const int32_t *_
             });
         }
     }
-    add_remainder<T, V>(acc, rem_rp, rem_col, rem_val, i, x + c, ldk);
+    add_remainder<T, V>(acc, p0, p1, rem_col, rem_val, x + c, ldk);
     if (i0 < m) store_row<T, V, false>(y + i * ldk + c, acc);
 }
 
 // Eight slots per pass; the G lanes of a row share the loads of the pass's columns and values (lane cg fetches slots
 // cg, cg + G, ...) and pass them round, and the next pass's are requested before this pass's rows of X, so the two
-// latencies overlap.  Padding slots carry column -1 and value +0: row 0 of X is read for them and selected away (it may
-// hold anything).  Lanes of rows past the end compute on row m - 1 and store nothing.
+// latencies overlap.  Padding slots carry column -1 and value +0: nothing is fetched for them (a matrix with rows of
+// very different lengths is mostly padding in its last slots).  Lanes of rows past the end compute on row m - 1 and store nothing.
 // coo_rp != nullptr: a HYB handle whose rows keep few entries in the COO part; the row's lanes add their own COO run.
 template <typename T, int K>
 __global__ __launch_bounds__(MB) void k_spmm_ell(const int32_t *__restrict__ col, const T *__restrict__ val, int64_t W, int64_t ld,
@@ -277,6 +280,7 @@ __global__ __launch_bounds__(MB) void k_spmm_ell(const int32_t *__restrict__ col
     const int32_t *cp = col + i;
     const T *vp = val + i;
     const T *xc = x + c;
+    const int32_t p0 = coo_rp ? coo_rp[i] : 0, p1 = coo_rp ? coo_rp[i + 1] : 0;   // asked for now, needed after the slots
     int32_t nj[EU];
     T na[EU];
 #pragma unroll
@@ -305,19 +309,15 @@ __global__ __launch_bounds__(MB) void k_spmm_ell(const int32_t *__restrict__ col
         for (int u = 0; u < EU; ++u)
             for_group2<G>(cj[u], ca[u], [&](int cc, int32_t j, T a) {
                 const bool on = s0 + u * G + cc < W && j >= 0;
-                const T *xp = xc + (int64_t)(on ? j : 0) * ldk;
                 aa[u * G + cc] = on ? a : (T)0;
-                load_piece<T, V>(xp, xr[u * G + cc]);
 #pragma unroll
-                for (int v = 0; v < V; ++v) xr[u * G + cc][v] = on ? xr[u * G + cc][v] : (T)0;   // whatever X holds in row 0
+                for (int v = 0; v < V; ++v) xr[u * G + cc][v] = (T)0;
+                if (on) load_piece<T, V>(xc + (int64_t)j * ldk, xr[u * G + cc]);   // nothing is fetched for padding
             });
 #pragma unroll
         for (int q = 0; q < PASS; ++q) fma_row<T, V>(acc, aa[q], xr[q]);
     }
-    if (coo_rp) {
-        const int32_t p1 = coo_rp[i + 1];
-        for (int32_t p = coo_rp[i]; p < p1; ++p) fma_row<T, V>(acc, cval[p], xc + (int64_t)ccol[p] * ldk);
-    }
+    for (int32_t p = p0; p < p1; ++p) fma_row<T, V>(acc, cval[p], xc + (int64_t)ccol[p] * ldk);
     if (i0 < m) store_row<T, V, false>(y + i * ldk + c, acc);
 }
 
@@ -327,14 +327,15 @@ __global__ __launch_bounds__(MB) void k_spmm_ell(const int32_t *__restrict__ col
 // entries are left to the whole wave, so that one long row does not keep the other lanes waiting.  rp comes from a
 // validated CSR or was built by the conversions, so it is non-decreasing; the conditions below still keep every
 // LDS index inside the chunk.  The G lanes of a row hold the same lo / hi, so runs of rows begin and end on
-// multiples of G lanes.
-template <typename T, int K, bool ACC>
+// multiples of G lanes.  RCAP is the host's choice by the average length of the part's rows (launch_rows): the
+// stage decides how many waves a CU holds (12 bytes per entry in fp64: 13 waves at 1024 entries, 26 at 512), and a
+// wave that needs a second chunk for its 64 / G rows pays the stage's latency twice.
+template <typename T, int K, bool ACC, int RCAP>
 __global__ __launch_bounds__(MB) void k_spmm_rows(const int32_t *__restrict__ rp, const int32_t *__restrict__ col,
                                                    const T *__restrict__ val, int64_t m, int64_t ldk, const T *__restrict__ x,
                                                    T *__restrict__ y)
 {
     constexpr int V = Panel<T, K>::V, G = Panel<T, K>::G;
-    constexpr int RCAP = ::mo::RCAP / (G == 4 ? 2 : 1);   // 512 entries for 16 rows per wave: 24 KB per block, six blocks per CU
     __shared__ int32_t s_col_all[(MB / WAVE) * RCAP];
     __shared__ T s_val_all[(MB / WAVE) * RCAP];
     int32_t *s_col = s_col_all + (threadIdx.x / WAVE) * RCAP;
@@ -359,12 +360,9 @@ __global__ __launch_bounds__(MB) void k_spmm_rows(const int32_t *__restrict__ rp
         const int last = first + nrun - 1;
         const int end = __builtin_amdgcn_readlane(hi, last);
         const int total = end - start;   // 0 .. RCAP
-        if (total > WAVE) {
+        if (total > 0) {   // (a single load per array for runs of at most 64 entries, as a branch of its own, cost 7 % on CSR)
             stage_to_lds(col + start, s_col, total, lane);
             stage_to_lds(val + start, s_val, total, lane);
-        } else if (lane < total) {   // a sparse remainder or COO part: one load per array instead of a batch
-            s_col[lane] = ld_stream(col + start + lane);
-            s_val[lane] = ld_stream(val + start + lane);
         }
         if (!is_long && lane >= first && lane <= last && hi <= end) {
             constexpr int ROWS_U = V >= 8 ? 4 : 8;   // entries fetched together; fewer for wide pieces (registers)
@@ -429,6 +427,21 @@ static mo_status dia_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, bo
     return MO_OK;
 }
 
+// The row-pointer kernel with the smallest stage (256, 512 or 1024 entries per wave) that holds a wave's 64 / G rows
+// of average length with a tenth to spare.  Measured with 8 fp64 columns (16 rows per wave): the 27-point stencil (432
+// entries per wave) 250 us at 512, 308 at 1024, 389 at 256.
+template <typename T, int K, bool ACC>
+static void launch_rows(const int32_t *rp, const int32_t *col, const T *val, int64_t m, int64_t part_nnz, int64_t ldk, const T *x, T *y,
+                        hipStream_t s)
+{
+    constexpr int RPB = Panel<T, K>::ROWS, RPW = WAVE / Panel<T, K>::G;
+    const unsigned grid = (unsigned)((m + RPB - 1) / RPB);
+    const double need = 1.1 * (double)part_nnz / (double)(m > 0 ? m : 1) * RPW;
+    if (need <= 256) hipLaunchKernelGGL((k_spmm_rows<T, K, ACC, 256>), dim3(grid), dim3(MB), 0, s, rp, col, val, m, ldk, x, y);
+    else if (need <= 512) hipLaunchKernelGGL((k_spmm_rows<T, K, ACC, 512>), dim3(grid), dim3(MB), 0, s, rp, col, val, m, ldk, x, y);
+    else hipLaunchKernelGGL((k_spmm_rows<T, K, ACC, 1024>), dim3(grid), dim3(MB), 0, s, rp, col, val, m, ldk, x, y);
+}
+
 // One column panel of everything that is not a DIA part.  after_dia: the DIA part of an HDC handle has already
 // written this panel of Y, the remainder is added to it.
 template <typename T, int K>
@@ -447,25 +460,25 @@ static mo_status rest_panel(const mo_matrix &a, const T *x, T *y, int64_t ldk, b
                            fused ? a.coo_rp : (const int32_t *)nullptr, a.coo_col, (const T *)a.coo_val, x, y);
         MO_LAUNCH_CHECK();
         if (a.fmt == MO_HYB && a.nnz_coo > 0 && !fused) {
-            hipLaunchKernelGGL((k_spmm_rows<T, K, true>), dim3(grid), dim3(MB), 0, s, a.coo_rp, a.coo_col, (const T *)a.coo_val, a.m, ldk, x, y);
+            launch_rows<T, K, true>(a.coo_rp, a.coo_col, (const T *)a.coo_val, a.m, a.nnz_coo, ldk, x, y, s);
             MO_LAUNCH_CHECK();
         }
         return MO_OK;
     }
     case MO_COO:
-        hipLaunchKernelGGL((k_spmm_rows<T, K, false>), dim3(grid), dim3(MB), 0, s, a.coo_rp, a.coo_col, (const T *)a.coo_val, a.m, ldk, x, y);
+        launch_rows<T, K, false>(a.coo_rp, a.coo_col, (const T *)a.coo_val, a.m, a.nnz_coo, ldk, x, y, s);
         MO_LAUNCH_CHECK();
         return MO_OK;
     case MO_CSR:
-        hipLaunchKernelGGL((k_spmm_rows<T, K, false>), dim3(grid), dim3(MB), 0, s, a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, a.m, ldk, x, y);
+        launch_rows<T, K, false>(a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, a.m, a.nnz_csr, ldk, x, y, s);
         MO_LAUNCH_CHECK();
         return MO_OK;
     case MO_HDC:
         if (!after_dia) {
-            hipLaunchKernelGGL((k_spmm_rows<T, K, false>), dim3(grid), dim3(MB), 0, s, a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, a.m, ldk, x, y);
+            launch_rows<T, K, false>(a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, a.m, a.nnz_csr, ldk, x, y, s);
             MO_LAUNCH_CHECK();
         } else if (a.nnz_csr > 0) {
-            hipLaunchKernelGGL((k_spmm_rows<T, K, true>), dim3(grid), dim3(MB), 0, s, a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, a.m, ldk, x, y);
+            launch_rows<T, K, true>(a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, a.m, a.nnz_csr, ldk, x, y, s);
             MO_LAUNCH_CHECK();
         }
         return MO_OK;
