@@ -11,7 +11,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmo.so")
 
-SOURCES = ["api.hip", "features.hip", "scan.hip", "convert.hip", "spmv_csr.hip", "spmv_coo.hip", "spmv_dia.hip",
+SOURCES = ["api.hip", "features.hip", "feat_part.hip", "scan.hip", "convert.hip", "spmv_csr.hip", "spmv_coo.hip", "spmv_dia.hip",
            "spmv_ell.hip", "spmm.hip", "switch.hip", "xplan.hip", "model.cpp", "fit.cpp", "mtx.cpp"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -87,16 +87,6 @@ __global__ void k_fill_i32(int32_t *p, int64_t n, int32_t v)
 // i.e. when the tile spans many empty rows).
 constexpr int COO_CT = 2048;
 
-__device__ __forceinline__ int64_t row_of_entry(const int32_t *__restrict__ row_ptr, int64_t lo, int64_t hi, int64_t p)
-{
-    // largest r in [lo, hi] with row_ptr[r] <= p  (row_ptr[lo] <= p is given)
-    while (lo < hi) {
-        const int64_t mid = (lo + hi + 1) >> 1;
-        if ((int64_t)row_ptr[mid] <= p) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
 template <typename T>
 __global__ __launch_bounds__(CB) void k_csr_to_coo(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                     const T *__restrict__ val, int64_t m, int64_t nnz, int32_t *__restrict__ orow,

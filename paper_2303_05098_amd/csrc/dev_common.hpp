@@ -117,6 +117,17 @@ __device__ __forceinline__ void stage_pair_to_lds(const A *__restrict__ ga, cons
     }
 }
 
+// The row that holds entry p of a CSR matrix: the largest r in [lo, hi] with row_ptr[r] <= p (row_ptr[lo] <= p is
+// given).  Terminates with a result in [lo, hi] whatever row_ptr holds.
+__device__ __forceinline__ int64_t row_of_entry(const int32_t *__restrict__ row_ptr, int64_t lo, int64_t hi, int64_t p)
+{
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if ((int64_t)row_ptr[mid] <= p) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef int int2v __attribute__((ext_vector_type(2)));
 typedef double dbl2v __attribute__((ext_vector_type(2)));

@@ -13,6 +13,11 @@ struct Counters {
     unsigned int pad;
 };
 
+// Non-empty and true diagonals one block counted (no atomics: whoever reads the results adds them up).
+struct DiagPart {
+    unsigned long long n_diag, n_true;
+};
+
 constexpr int FB = 256;        // threads per block
 constexpr int SHORT_ROW = 32;  // entries of a row handled lane-per-row; the rest is walked by the whole wave
 

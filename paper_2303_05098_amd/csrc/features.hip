@@ -10,6 +10,7 @@
 #include "mo_internal.hpp"
 
 #include <mutex>
+#include <vector>
 
 namespace mo {
 
@@ -249,6 +250,45 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
     }
 }
 
+// The row half of the traversal alone: row lengths (max, min, sum of squares) and the row-pointer half of the CSR
+// precondition (row_ptr[0] = 0, row_ptr[m] = nnz, non-decreasing, inside [0, nnz]), for the path that counts the
+// diagonals by partition and checks the columns there.  Same block layout and results as k_traverse.
+__global__ __launch_bounds__(TB) void k_row_stats(const int32_t *__restrict__ row_ptr, int64_t m, int64_t nnz, int64_t rows_per_block,
+                                                   RowPart *__restrict__ part)
+{
+    unsigned long long mx = 0ull, mn = ~0ull, sq = 0ull;
+    bool err = false;
+    const int64_t row_begin = (int64_t)blockIdx.x * rows_per_block;
+    int64_t row_end = row_begin + rows_per_block;
+    row_end = row_end < m ? row_end : m;
+    for (int64_t row = row_begin + threadIdx.x; row < row_end; row += TB) {
+        const int64_t a = row_ptr[row], b = row_ptr[row + 1];
+        if (row == 0 && a != 0) err = true;
+        if (row == m - 1 && b != nnz) err = true;
+        if (b < a || a < 0 || b > nnz) err = true;
+        const unsigned long long l = b > a ? (unsigned long long)(b - a) : 0ull;
+        mx = l > mx ? l : mx;
+        mn = l < mn ? l : mn;
+        sq += l * l;
+    }
+    mx = wave_max(mx); mn = wave_min(mn); sq = wave_sum(sq);
+    __shared__ unsigned long long s_mx[TB / WAVE], s_mn[TB / WAVE], s_sq[TB / WAVE];
+    __shared__ int s_err;
+    if (threadIdx.x == 0) s_err = 0;
+    __syncthreads();
+    if (err) s_err = 1;
+    if (lane_id() == 0) { s_mx[threadIdx.x / WAVE] = mx; s_mn[threadIdx.x / WAVE] = mn; s_sq[threadIdx.x / WAVE] = sq; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < TB / WAVE; ++w) {
+            mx = s_mx[w] > mx ? s_mx[w] : mx;
+            mn = s_mn[w] < mn ? s_mn[w] : mn;
+            sq += s_sq[w];
+        }
+        part[blockIdx.x] = RowPart{mx, mn, sq, s_err ? 1ull : 0ull};
+    }
+}
+
 mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis *out, Scratch &scratch, hipStream_t s)
 {
     // blocks own contiguous runs of rows (a multiple of the block size)
@@ -264,7 +304,22 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     Counters *ctr = (Counters *)base;
     RowPart *part = (RowPart *)(base + 256);
     uint32_t *hist = want_hist ? (uint32_t *)(base + head) : nullptr;
-    if (want_hist) {
+    bool by_partition = false;
+    if (want_hist && partition_possible(a)) {   // scattered columns: nothing to merge, see feat_part.hip
+        uint32_t *sdev = (uint32_t *)scratch.get(partition_sample_bytes());
+        if (!sdev) return MO_E_ALLOC;
+        std::vector<uint32_t> shost(partition_sample_bytes() / sizeof(uint32_t));
+        MO_TRY(partition_wanted(a, sdev, shost.data(), &by_partition, s));
+    }
+    if (want_hist && by_partition) {
+        void *pbuf = scratch.get(partition_scratch_bytes(a));
+        if (!pbuf) return MO_E_ALLOC;
+        hipLaunchKernelGGL(k_init_counters, dim3(1), dim3(64), 0, s, ctr);
+        MO_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_row_stats, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.m, a.nnz, rows_per_block, part);
+        MO_LAUNCH_CHECK();
+        MO_TRY(partition_counts(a, p, pbuf, hist, nullptr, ctr, &ctr->err, s));
+    } else if (want_hist) {
         hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr);
         MO_LAUNCH_CHECK();
         hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
@@ -291,6 +346,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
         sq += h.part[b].sum_sq;
         err |= h.part[b].err;
     }
+    if (by_partition) err |= h.c.err;   // the columns were checked by the partition's first pass
     if (err) return MO_E_CSR_INVALID;
     out->max_row = (int64_t)mx;
     out->min_row = (int64_t)mnr;
@@ -316,9 +372,6 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
 // mo_set_allocator releases the block through the allocator it came from.
 namespace {
 
-struct DiagPart {
-    unsigned long long n_diag, n_true;
-};
 constexpr int DIAG_BLOCKS = 2048;
 
 // Counts the non-empty and the true diagonals and clears the counters it reads; every block leaves its two counts in
@@ -354,8 +407,10 @@ struct FeatureCache {
     uint32_t *dev = nullptr;   // histogram of hist_cap counters
     int64_t hist_cap = 0;
     bool clean = false;
-    void *host = nullptr;      // pinned: [RowPart x TRAV_BLOCKS | DiagPart x DIAG_BLOCKS]
+    void *host = nullptr;      // pinned: [RowPart x TRAV_BLOCKS | DiagPart x DIAG_BLOCKS | sample counts of the partition's decision]
     int device = -1;
+    void *pbuf = nullptr;      // scratch of the partition path (feat_part.hip)
+    size_t pbuf_cap = 0;
 };
 FeatureCache g_fc;
 
@@ -365,7 +420,9 @@ void release_feature_cache()
 {
     std::lock_guard<std::mutex> lk(g_fc.mu);
     if (g_fc.dev) dev_free(g_fc.dev, nullptr);
+    if (g_fc.pbuf) dev_free(g_fc.pbuf, nullptr);
     g_fc.dev = nullptr; g_fc.hist_cap = 0; g_fc.clean = false;
+    g_fc.pbuf = nullptr; g_fc.pbuf_cap = 0;
 }
 
 mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hipStream_t s)
@@ -373,13 +430,14 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     std::unique_lock<std::mutex> lk(g_fc.mu, std::try_to_lock);
     int dev_now = -1;
     bool usable = lk.owns_lock() && hipGetDevice(&dev_now) == hipSuccess;
-    if (usable && !g_fc.host && hipHostMalloc(&g_fc.host, HOST_BYTES, hipHostMallocDefault) != hipSuccess) {
+    if (usable && !g_fc.host && hipHostMalloc(&g_fc.host, HOST_BYTES + partition_sample_bytes() + 256, hipHostMallocDefault) != hipSuccess) {
         g_fc.host = nullptr;
         usable = false;
     }
     const int64_t ndiag = a.m + a.n - 1;
     if (usable && (g_fc.hist_cap < ndiag || g_fc.device != dev_now)) {
         if (g_fc.dev) dev_free(g_fc.dev, s);
+        if (g_fc.pbuf && g_fc.device != dev_now) { dev_free(g_fc.pbuf, s); g_fc.pbuf = nullptr; g_fc.pbuf_cap = 0; }
         g_fc.hist_cap = ndiag + ndiag / 2;
         g_fc.dev = (uint32_t *)dev_alloc((size_t)g_fc.hist_cap * sizeof(uint32_t), s);
         g_fc.clean = false;
@@ -396,25 +454,53 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     RowPart *part = (RowPart *)g_fc.host;
     DiagPart *dpart = (DiagPart *)((char *)g_fc.host + (size_t)TRAV_BLOCKS * sizeof(RowPart));
     uint32_t *hist = g_fc.dev;
-    const bool was_clean = g_fc.clean;
-    g_fc.clean = false;
-    if (!was_clean) {
-        hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, 0u);
-        MO_LAUNCH_CHECK();
-    }
     int64_t rows_per_block = (a.m + TRAV_BLOCKS - 1) / TRAV_BLOCKS;
     rows_per_block = ((rows_per_block + TB - 1) / TB) * TB;
     const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;
-    hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                       rows_per_block, hist, part);
-    MO_LAUNCH_CHECK();
-    const int64_t mn = a.m < a.n ? a.m : a.n;
-    const int dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
-    hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
-                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart);
-    MO_LAUNCH_CHECK();
-    MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
-    g_fc.clean = true;
+    // Scattered columns (decided from a sample): the diagonals are counted by partition, in scratch that is kept
+    // like the histogram; the histogram itself is not touched and stays as clean as it was.
+    bool by_partition = false;
+    if (partition_possible(a)) {
+        // the sample's counts go straight into the pinned block, like the other per-block results
+        uint32_t *sample = (uint32_t *)((char *)g_fc.host + HOST_BYTES);
+        MO_TRY(partition_wanted(a, sample, sample, &by_partition, s));
+        if (by_partition) {
+            const size_t need = partition_scratch_bytes(a);
+            if (g_fc.pbuf_cap < need) {
+                if (g_fc.pbuf) dev_free(g_fc.pbuf, s);
+                g_fc.pbuf = dev_alloc(need + need / 4, s);
+                g_fc.pbuf_cap = g_fc.pbuf ? need + need / 4 : 0;
+            }
+            if (!g_fc.pbuf) by_partition = false;
+        }
+    }
+    int dblocks = 0;
+    if (by_partition) {
+        uint32_t *col_err = (uint32_t *)((char *)g_fc.host + HOST_BYTES + partition_sample_bytes());
+        *col_err = 0u;   // pinned memory, written before the launches that may set it
+        hipLaunchKernelGGL(k_row_stats, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.m, a.nnz, rows_per_block, part);
+        MO_LAUNCH_CHECK();
+        MO_TRY(partition_counts(a, p, g_fc.pbuf, nullptr, dpart, nullptr, col_err, s));
+        dblocks = partition_buckets(a);
+        MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
+    } else {
+        const bool was_clean = g_fc.clean;
+        g_fc.clean = false;
+        if (!was_clean) {
+            hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, 0u);
+            MO_LAUNCH_CHECK();
+        }
+        hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
+                           rows_per_block, hist, part);
+        MO_LAUNCH_CHECK();
+        const int64_t mn = a.m < a.n ? a.m : a.n;
+        dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
+        hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
+                           (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart);
+        MO_LAUNCH_CHECK();
+        MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
+        g_fc.clean = true;
+    }
     const RowPart *hp = part;
     unsigned long long mx = 0ull, mnr = ~0ull, sq = 0ull, err = 0ull;
     for (int64_t b = 0; b < row_blocks; ++b) {
@@ -423,6 +509,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         sq += hp[b].sum_sq;
         err |= hp[b].err;
     }
+    if (by_partition) err |= *(const uint32_t *)((const char *)g_fc.host + HOST_BYTES + partition_sample_bytes());
     unsigned long long n_diag = 0ull, n_true = 0ull;
     for (int b = 0; b < dblocks; ++b) { n_diag += dpart[b].n_diag; n_true += dpart[b].n_true; }
     if (err) return MO_E_CSR_INVALID;

@@ -163,6 +163,16 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
 // The same numbers (histogram included in the counts, not handed out) with scratch that is kept between calls.
 mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hipStream_t s);
 void release_feature_cache();
+// The diagonal counts by partition into buckets of diagonals (feat_part.hip), for matrices with scattered columns.
+struct DiagPart;
+struct Counters;
+bool partition_possible(const mo_csr &a);
+int partition_buckets(const mo_csr &a);
+size_t partition_sample_bytes();
+size_t partition_scratch_bytes(const mo_csr &a);
+mo_status partition_wanted(const mo_csr &a, uint32_t *dev, uint32_t *host, bool *wanted, hipStream_t s);
+mo_status partition_counts(const mo_csr &a, const mo_params &p, void *buf, uint32_t *hist, DiagPart *dpart, Counters *ctr, uint32_t *err,
+                           hipStream_t s);
 // The no-allocation variant: integers and status into caller memory, asynchronous.
 mo_status features_static(const mo_csr &a, const mo_params &p, mo_feature_result *out_dev, hipStream_t s);
 
