@@ -395,7 +395,7 @@ size_t partition_scratch_bytes(const mo_csr &a)
     int64_t share = 0;
     const int nblk = part_blocks(a.nnz, &share);
     const size_t cells = (size_t)partition_buckets(a) * (size_t)nblk;
-    const size_t ints = (cells * 4 + 255) / 256 * 256;
+    const size_t ints = ((cells + 1) * 4 + 255) / 256 * 256;   // the scan also writes the total behind its last prefix
     const size_t tmp = (scan_tmp_bytes((int64_t)cells) + 255) / 256 * 256;
     return 2 * ints + tmp + (size_t)a.nnz * sizeof(uint16_t) + 256;
 }
@@ -413,7 +413,7 @@ mo_status partition_counts(const mo_csr &a, const mo_params &p, void *buf, uint3
     const int nblk = part_blocks(a.nnz, &share);
     const int nb = partition_buckets(a);
     const size_t cells = (size_t)nb * (size_t)nblk;
-    const size_t ints = (cells * 4 + 255) / 256 * 256;
+    const size_t ints = ((cells + 1) * 4 + 255) / 256 * 256;   // the scan also writes the total behind its last prefix
     const size_t tmp = (scan_tmp_bytes((int64_t)cells) + 255) / 256 * 256;
     int32_t *counts = (int32_t *)buf;
     int32_t *offs = (int32_t *)((char *)buf + ints);

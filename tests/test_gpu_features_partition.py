@@ -16,6 +16,8 @@ pytestmark = pytest.mark.gpu
 def scattered(kind):
     if kind == "uniform":                 # 12 distinct uniform columns in every row
         return synth.uniform_rows(180000, 12, 91)
+    if kind == "pow2":                    # 2^17 rows of 16: the bucket-by-block count table is a whole number of 256-byte lines
+        return synth.uniform_rows(131072, 16, 97)
     if kind == "lognormal":               # rows of very different lengths, some empty, some beyond the lane-per-row limit
         return synth.lognormal_rows(140000, 92, mean=16.0, sigma=1.2)
     if kind == "wide":                    # more columns than rows
@@ -40,7 +42,7 @@ def scattered(kind):
     raise ValueError(kind)
 
 
-@pytest.mark.parametrize("kind", ["uniform", "lognormal", "wide", "tall", "with_diagonal"])
+@pytest.mark.parametrize("kind", ["uniform", "pow2", "lognormal", "wide", "tall", "with_diagonal"])
 def test_features_bit_exact(kind):
     m, n, rp, ci, v = scattered(kind)
     assert ci.shape[0] >= 1 << 21
