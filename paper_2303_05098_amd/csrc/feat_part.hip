@@ -305,11 +305,19 @@ __global__ __launch_bounds__(PH) void k_part_hist(const uint16_t *__restrict__ k
     }
 }
 
+// The rule of the decision: enough sampled entries, and fewer than a quarter of them on a diagonal that another row
+// of their group of adjacent rows also holds (nothing for the traversal kernel to merge).
+__host__ __device__ inline bool sample_says_partition(uint64_t total, uint64_t repeated) { return total >= 2048 && repeated * 4 < total; }
+
 // Block g samples the SR adjacent rows that start at row floor(g * (m - SR + 1) / SG), SE entries of each (entry
 // floor(e * len / SE) of the row, or every entry when the row holds at most SE), and leaves two counts in
 // out[2 g], out[2 g + 1]: the sampled entries, and those among them whose diagonal another row of the group also holds.
+// acc (or nullptr): three device words, zero on entry: the counts are also added up there, and the block that
+// finishes last turns them into the decision (1 = partition), stores it in *flag_dev and *flag_host and clears acc
+// for the next call: kernels launched behind this one can read the decision without the host in between.
 __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, int64_t m,
-                                                          int64_t nnz, int64_t ndiag, uint32_t *__restrict__ out)
+                                                          int64_t nnz, int64_t ndiag, uint32_t *__restrict__ out, uint32_t *acc,
+                                                          uint32_t *flag_dev, uint32_t *flag_host)
 {
     __shared__ int32_t s_key[SR * SE];
     __shared__ uint32_t s_tot[SR * SE / WAVE], s_rep[SR * SE / WAVE];
@@ -341,8 +349,19 @@ __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restri
     if (threadIdx.x == 0) {
         uint32_t t = 0, q = 0;
         for (int w = 0; w < SR * SE / WAVE; ++w) { t += s_tot[w]; q += s_rep[w]; }
-        out[2 * blockIdx.x] = t;
-        out[2 * blockIdx.x + 1] = q;
+        if (out) { out[2 * blockIdx.x] = t; out[2 * blockIdx.x + 1] = q; }
+        if (acc) {
+            atomicAdd(&acc[0], t);
+            atomicAdd(&acc[1], q);
+            __threadfence();
+            if (atomicAdd(&acc[2], 1u) == gridDim.x - 1) {   // every other block's counts are in
+                const uint32_t total = atomicAdd(&acc[0], 0u), repeated = atomicAdd(&acc[1], 0u);
+                const uint32_t want = sample_says_partition(total, repeated) ? 1u : 0u;
+                *flag_dev = want;
+                *flag_host = want;
+                acc[0] = 0u; acc[1] = 0u; acc[2] = 0u;
+            }
+        }
     }
 }
 
@@ -372,6 +391,7 @@ size_t partition_sample_bytes() { return (size_t)SG * 2 * sizeof(uint32_t); }
 // The sample is analysed on the device; what comes back is two counts per group.  dev: device-visible buffer of
 // partition_sample_bytes() that the kernel writes; host: where the host reads them after the synchronisation (the
 // same pinned block, or a host buffer that dev is copied to when dev is device memory).  Synchronises the stream.
+// (The feature call proper uses partition_decide_async below and saves this synchronisation.)
 // Diagonals that crowd into few buckets although adjacent rows share none (columns scattered inside a narrow band)
 // leave the last step to few blocks: slower than intended, about as slow as the atomics it replaces, and exact.
 mo_status partition_wanted(const mo_csr &a, uint32_t *dev, uint32_t *host, bool *wanted, hipStream_t s)
@@ -379,13 +399,26 @@ mo_status partition_wanted(const mo_csr &a, uint32_t *dev, uint32_t *host, bool 
     *wanted = false;
     if (!partition_possible(a)) return MO_OK;
     const int64_t ndiag = a.m + a.n - 1;
-    hipLaunchKernelGGL(k_part_sample, dim3(SG), dim3(SR * SE), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, dev);
+    hipLaunchKernelGGL(k_part_sample, dim3(SG), dim3(SR * SE), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, dev, (uint32_t *)nullptr,
+                       (uint32_t *)nullptr, (uint32_t *)nullptr);
     MO_LAUNCH_CHECK();
     if (host != dev) MO_HIP(hipMemcpyAsync(host, dev, partition_sample_bytes(), hipMemcpyDeviceToHost, s));
     MO_HIP(hipStreamSynchronize(s));
     uint64_t total = 0, repeated = 0;
     for (int g = 0; g < SG; ++g) { total += host[2 * g]; repeated += host[2 * g + 1]; }
-    *wanted = total >= 2048 && repeated * 4 < total;
+    *wanted = sample_says_partition(total, repeated);
+    return MO_OK;
+}
+
+// The same decision without the host: enqueues the sample, whose last block leaves the decision in *flag_dev (for the
+// kernels enqueued behind it) and in *flag_host (pinned; for the host after its next synchronisation).  acc: three
+// device words that are zero between calls.
+mo_status partition_decide_async(const mo_csr &a, uint32_t *acc, uint32_t *flag_dev, uint32_t *flag_host, hipStream_t s)
+{
+    const int64_t ndiag = a.m + a.n - 1;
+    hipLaunchKernelGGL(k_part_sample, dim3(SG), dim3(SR * SE), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, (uint32_t *)nullptr, acc,
+                       flag_dev, flag_host);
+    MO_LAUNCH_CHECK();
     return MO_OK;
 }
 

@@ -53,8 +53,10 @@ struct RowPart {
 template <bool DO_HIST>
 __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   int64_t m, int64_t n, int64_t nnz, int64_t rows_per_block,
-                                                  uint32_t *__restrict__ hist, RowPart *__restrict__ part)
+                                                  uint32_t *__restrict__ hist, RowPart *__restrict__ part,
+                                                  const uint32_t *__restrict__ skip)
 {
+    if (skip && *skip) return;   // a kernel ahead in the stream has decided that another path counts this matrix
     __shared__ int ht_key[DO_HIST ? HT_SIZE : 1];
     __shared__ uint32_t ht_cnt[DO_HIST ? HT_SIZE : 1];
     __shared__ int ht_full;
@@ -323,7 +325,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
         hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr);
         MO_LAUNCH_CHECK();
         hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part);
+                           rows_per_block, hist, part, (const uint32_t *)nullptr);
         MO_LAUNCH_CHECK();
         const int64_t mn = a.m < a.n ? a.m : a.n;
         hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
@@ -331,7 +333,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
         MO_LAUNCH_CHECK();
     } else {
         hipLaunchKernelGGL(k_traverse<false>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part);
+                           rows_per_block, hist, part, (const uint32_t *)nullptr);
         MO_LAUNCH_CHECK();
     }
     struct { Counters c; char pad[256 - sizeof(Counters)]; RowPart part[TRAV_BLOCKS]; } h;
@@ -377,8 +379,10 @@ constexpr int DIAG_BLOCKS = 2048;
 // Counts the non-empty and the true diagonals and clears the counters it reads; every block leaves its two counts in
 // dpart[blockIdx.x] (no atomics: the host adds the few hundred partial results).
 __global__ __launch_bounds__(FB) void k_diag_count_clear(uint32_t *__restrict__ hist, int64_t nd, unsigned long long thr_rhs,
-                                                          unsigned long long td_den, DiagPart *__restrict__ dpart)
+                                                          unsigned long long td_den, DiagPart *__restrict__ dpart,
+                                                          const uint32_t *__restrict__ skip)
 {
+    if (skip && *skip) return;
     unsigned long long c_nd = 0, c_td = 0;
     const int64_t stride = (int64_t)gridDim.x * FB;
     for (int64_t i = (int64_t)blockIdx.x * FB + threadIdx.x; i < nd; i += stride) {
@@ -439,7 +443,11 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         if (g_fc.dev) dev_free(g_fc.dev, s);
         if (g_fc.pbuf && g_fc.device != dev_now) { dev_free(g_fc.pbuf, s); g_fc.pbuf = nullptr; g_fc.pbuf_cap = 0; }
         g_fc.hist_cap = ndiag + ndiag / 2;
-        g_fc.dev = (uint32_t *)dev_alloc((size_t)g_fc.hist_cap * sizeof(uint32_t), s);
+        g_fc.dev = (uint32_t *)dev_alloc(((size_t)g_fc.hist_cap + 64) * sizeof(uint32_t), s);   // + the sample's counters and flag
+        if (g_fc.dev) {
+            hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, g_fc.dev + g_fc.hist_cap, (int64_t)64, 0u);
+            MO_LAUNCH_CHECK();
+        }
         g_fc.clean = false;
         g_fc.device = dev_now;
         if (!g_fc.dev) { g_fc.hist_cap = 0; usable = false; }
@@ -459,47 +467,48 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;
     // Scattered columns (decided from a sample): the diagonals are counted by partition, in scratch that is kept
     // like the histogram; the histogram itself is not touched and stays as clean as it was.
-    bool by_partition = false;
-    if (partition_possible(a)) {
-        // the sample's counts go straight into the pinned block, like the other per-block results
-        uint32_t *sample = (uint32_t *)((char *)g_fc.host + HOST_BYTES);
-        MO_TRY(partition_wanted(a, sample, sample, &by_partition, s));
-        if (by_partition) {
-            const size_t need = partition_scratch_bytes(a);
-            if (g_fc.pbuf_cap < need) {
-                if (g_fc.pbuf) dev_free(g_fc.pbuf, s);
-                g_fc.pbuf = dev_alloc(need + need / 4, s);
-                g_fc.pbuf_cap = g_fc.pbuf ? need + need / 4 : 0;
-            }
-            if (!g_fc.pbuf) by_partition = false;
-        }
+    // Matrices that could take the partition path (feat_part.hip) are sampled first, on the device; the traversal
+    // kernels behind the sample skip themselves when it decides for the partition, and the host learns the decision
+    // with the results, after the one synchronisation every call has.  A structured matrix pays one small kernel; a
+    // scattered one pays two empty kernels and a second synchronisation on a call that is several times cheaper.
+    const bool sampled = partition_possible(a);
+    uint32_t *acc = g_fc.dev + g_fc.hist_cap, *flag_dev = acc + 3;
+    uint32_t *flag_host = (uint32_t *)((char *)g_fc.host + HOST_BYTES);
+    uint32_t *col_err = flag_host + 1;
+    *flag_host = 0u;   // pinned memory, written before the launches that may set it
+    *col_err = 0u;
+    if (sampled) MO_TRY(partition_decide_async(a, acc, flag_dev, flag_host, s));
+    const bool was_clean = g_fc.clean;
+    g_fc.clean = false;
+    if (!was_clean) {
+        hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, 0u);
+        MO_LAUNCH_CHECK();
     }
-    int dblocks = 0;
+    hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
+                       rows_per_block, hist, part, sampled ? flag_dev : (const uint32_t *)nullptr);
+    MO_LAUNCH_CHECK();
+    const int64_t mn = a.m < a.n ? a.m : a.n;
+    int dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
+    hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart,
+                       sampled ? flag_dev : (const uint32_t *)nullptr);
+    MO_LAUNCH_CHECK();
+    MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
+    g_fc.clean = true;                 // skipped or not, the kernels leave the histogram all zero
+    const bool by_partition = sampled && *flag_host != 0u;
     if (by_partition) {
-        uint32_t *col_err = (uint32_t *)((char *)g_fc.host + HOST_BYTES + partition_sample_bytes());
-        *col_err = 0u;   // pinned memory, written before the launches that may set it
+        const size_t need = partition_scratch_bytes(a);
+        if (g_fc.pbuf_cap < need) {
+            if (g_fc.pbuf) dev_free(g_fc.pbuf, s);
+            g_fc.pbuf = dev_alloc(need + need / 4, s);
+            g_fc.pbuf_cap = g_fc.pbuf ? need + need / 4 : 0;
+        }
+        if (!g_fc.pbuf) return MO_E_ALLOC;
         hipLaunchKernelGGL(k_row_stats, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.m, a.nnz, rows_per_block, part);
         MO_LAUNCH_CHECK();
         MO_TRY(partition_counts(a, p, g_fc.pbuf, nullptr, dpart, nullptr, col_err, s));
         dblocks = partition_buckets(a);
-        MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
-    } else {
-        const bool was_clean = g_fc.clean;
-        g_fc.clean = false;
-        if (!was_clean) {
-            hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, 0u);
-            MO_LAUNCH_CHECK();
-        }
-        hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part);
-        MO_LAUNCH_CHECK();
-        const int64_t mn = a.m < a.n ? a.m : a.n;
-        dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
-        hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
-                           (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart);
-        MO_LAUNCH_CHECK();
-        MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
-        g_fc.clean = true;
+        MO_HIP(hipStreamSynchronize(s));
     }
     const RowPart *hp = part;
     unsigned long long mx = 0ull, mnr = ~0ull, sq = 0ull, err = 0ull;
@@ -509,7 +518,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         sq += hp[b].sum_sq;
         err |= hp[b].err;
     }
-    if (by_partition) err |= *(const uint32_t *)((const char *)g_fc.host + HOST_BYTES + partition_sample_bytes());
+    if (by_partition) err |= *col_err;
     unsigned long long n_diag = 0ull, n_true = 0ull;
     for (int b = 0; b < dblocks; ++b) { n_diag += dpart[b].n_diag; n_true += dpart[b].n_true; }
     if (err) return MO_E_CSR_INVALID;
@@ -601,12 +610,12 @@ mo_status features_static(const mo_csr &a, const mo_params &p, mo_feature_result
     rows_per_block = ((rows_per_block + TB - 1) / TB) * TB;
     const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;
     hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                       rows_per_block, sc->hist, sc->part);
+                       rows_per_block, sc->hist, sc->part, (const uint32_t *)nullptr);
     MO_LAUNCH_CHECK();
     const int64_t mn = a.m < a.n ? a.m : a.n;
     const int dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
     hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, sc->hist, ndiag,
-                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, sc->dpart);
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, sc->dpart, (const uint32_t *)nullptr);
     MO_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_static_finish, dim3(1), dim3(FB), 0, s, sc->part, (int)row_blocks, sc->dpart, dblocks, a.m, a.n, a.nnz, out_dev);
     MO_LAUNCH_CHECK();
