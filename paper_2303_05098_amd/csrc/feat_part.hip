@@ -53,19 +53,77 @@ struct TileRows {
     bool staged;
 };
 
-// The first and the last row of every tile of a block's share, found by all threads at once before the tiles are
-// walked (a search is some twenty dependent loads: done by one thread per tile it would cost more than the tile).
-// s_first / s_last: P_MAX_TILES ints each.
+// The first and the last row of every tile of a block's share: 2 * tiles searches for the largest row r with
+// row_ptr[r] <= p.  A binary search is some twenty dependent loads, which cost more than the tile's own work, so the
+// block searches with all its threads instead, in three rounds of independent loads: PT rows spread over the whole
+// matrix, then 32 rows inside the interval each search fell into, then 64 inside the next, and a few binary steps on
+// what is left (none for matrices of up to a million rows).  scr: PSUB ints of LDS (the tile stage, not in use yet);
+// shares of more than 32 tiles (more than 2^27 entries in the matrix) search one boundary per thread the plain way.
+// tile_rows (global, or nullptr): the block's results are also written there (2 ints per tile, at tile_base) for
+// the scatter pass, which walks the same tiles.  Indices stay inside [0, m) whatever row_ptr holds.
+constexpr int FT_MAX = 32;   // tiles per block up to which the cooperative search is used
+__device__ __forceinline__ int last_not_above(const int32_t *v, int cnt, int64_t p)
+{
+    int lo = 0, hi = cnt - 1;   // largest j with v[j] <= p, 0 when there is none
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)v[mid] <= p) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
 __device__ __forceinline__ void find_tile_rows(const int32_t *__restrict__ row_ptr, int64_t m, int64_t b0, int64_t b1, int32_t *s_first,
-                                               int32_t *s_last)
+                                               int32_t *s_last, int32_t *scr, int32_t *__restrict__ tile_rows, int64_t tile_base)
 {
     const int nt = (int)((b1 - b0 + PSUB - 1) / PSUB);
-    for (int q = threadIdx.x; q < 2 * nt; q += PT) {
-        const int t = q >> 1;
-        const int64_t t0 = b0 + (int64_t)t * PSUB, t1 = t0 + PSUB < b1 ? t0 + PSUB : b1;
-        const int64_t r = row_of_entry(row_ptr, 0, m - 1, (q & 1) ? t1 - 1 : t0);
-        if (q & 1) s_last[t] = (int32_t)r; else s_first[t] = (int32_t)r;
+    auto target = [&](int q) {
+        const int64_t t0 = b0 + (int64_t)(q >> 1) * PSUB, t1 = t0 + PSUB < b1 ? t0 + PSUB : b1;
+        return (q & 1) ? t1 - 1 : t0;
+    };
+    auto publish = [&](int q, int64_t r) {
+        if (q & 1) s_last[q >> 1] = (int32_t)r; else s_first[q >> 1] = (int32_t)r;
+        if (tile_rows) tile_rows[2 * tile_base + q] = (int32_t)r;
+    };
+    if (nt > FT_MAX) {
+        for (int q = threadIdx.x; q < 2 * nt; q += PT) publish(q, row_of_entry(row_ptr, 0, m - 1, target(q)));
+        __syncthreads();
+        return;
     }
+    __shared__ int32_t s_lo[2 * FT_MAX], s_hi[2 * FT_MAX];
+    const int nq = 2 * nt;
+    const int64_t l1 = (m + PT - 1) / PT;   // rows between the probes of round 1
+    {
+        const int64_t r = (int64_t)threadIdx.x * l1;
+        scr[threadIdx.x] = row_ptr[r < m ? r : m - 1];
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < nq) {
+        const int j = last_not_above(scr, PT, target(threadIdx.x));
+        const int64_t lo = (int64_t)j * l1 < m ? (int64_t)j * l1 : m - 1, hi = lo + l1 < m ? lo + l1 : m - 1;
+        s_lo[threadIdx.x] = (int32_t)lo; s_hi[threadIdx.x] = (int32_t)hi;
+    }
+    __syncthreads();
+    int64_t len = l1;
+    for (int probes = 32; probes <= 64; probes *= 2) {   // rounds 2 and 3
+        const int64_t step = (len + probes - 1) / probes;
+        for (int i = threadIdx.x; i < nq * probes; i += PT) {
+            const int q = i / probes, j = i % probes;
+            const int64_t r = (int64_t)s_lo[q] + j * step;
+            scr[i] = row_ptr[r < s_hi[q] ? r : s_hi[q]];
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < nq) {
+            const int q = threadIdx.x;
+            const int j = last_not_above(scr + q * probes, probes, target(q));
+            int64_t lo = (int64_t)s_lo[q] + j * step;
+            lo = lo < s_hi[q] ? lo : s_hi[q];
+            const int64_t hi = lo + step < s_hi[q] ? lo + step : s_hi[q];
+            s_lo[q] = (int32_t)lo; s_hi[q] = (int32_t)hi;
+        }
+        __syncthreads();
+        len = step;
+    }
+    if ((int)threadIdx.x < nq) publish(threadIdx.x, row_of_entry(row_ptr, s_lo[threadIdx.x], s_hi[threadIdx.x], target(threadIdx.x)));
     __syncthreads();
 }
 
@@ -150,7 +208,8 @@ __device__ __forceinline__ bool tile_keys(const int32_t *__restrict__ row_ptr, c
 // err: set to 1 when an entry of the share violates the column half of the CSR precondition.
 __global__ __launch_bounds__(PT) void k_part_count(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, int64_t m,
                                                    int64_t n, int64_t nnz, int64_t ndiag, int64_t share, int nb,
-                                                   int32_t *__restrict__ counts, uint32_t *__restrict__ err)
+                                                   int32_t *__restrict__ counts, uint32_t *__restrict__ err,
+                                                   int32_t *__restrict__ tile_rows)
 {
     __shared__ int32_t rps[PSUB + 2];
     __shared__ int32_t s_first[P_MAX_TILES], s_last[P_MAX_TILES];
@@ -158,7 +217,7 @@ __global__ __launch_bounds__(PT) void k_part_count(const int32_t *__restrict__ r
     for (int i = threadIdx.x; i < nb; i += PT) s_cnt[i] = 0;
     const int64_t b0 = (int64_t)blockIdx.x * share;
     const int64_t b1 = b0 + share < nnz ? b0 + share : nnz;
-    find_tile_rows(row_ptr, m, b0, b1, s_first, s_last);
+    find_tile_rows(row_ptr, m, b0, b1, s_first, s_last, rps, tile_rows, (int64_t)blockIdx.x * (share / PSUB));
     int t = 0;
     bool bad = false;
     for (int64_t t0 = b0; t0 < b1; t0 += PSUB, ++t) {   // uniform trip count across the block
@@ -209,7 +268,7 @@ __device__ __forceinline__ void block_scan(const int32_t *s_in, int32_t *s_out, 
 // bucket b, as diagonal numbers relative to the bucket.
 __global__ __launch_bounds__(PT) void k_part_scatter(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, int64_t m,
                                                      int64_t nnz, int64_t ndiag, int64_t share, int nb, const int32_t *__restrict__ offs,
-                                                     uint16_t *__restrict__ keys16)
+                                                     const int32_t *__restrict__ tile_rows, uint16_t *__restrict__ keys16)
 {
     __shared__ int32_t rps[PSUB + 2];
     __shared__ int32_t s_first[P_MAX_TILES], s_last[P_MAX_TILES];
@@ -218,7 +277,16 @@ __global__ __launch_bounds__(PT) void k_part_scatter(const int32_t *__restrict__
     for (int i = threadIdx.x; i < nb; i += PT) s_goff[i] = offs[(int64_t)i * gridDim.x + blockIdx.x];
     const int64_t b0 = (int64_t)blockIdx.x * share;
     const int64_t b1 = b0 + share < nnz ? b0 + share : nnz;
-    find_tile_rows(row_ptr, m, b0, b1, s_first, s_last);
+    {   // the rows of the tiles, as the count pass found them (clamped: they index row_ptr)
+        const int nt = (int)((b1 - b0 + PSUB - 1) / PSUB);
+        const int64_t tile_base = (int64_t)blockIdx.x * (share / PSUB);
+        for (int q = threadIdx.x; q < 2 * nt; q += PT) {
+            int64_t r = tile_rows[2 * tile_base + q];
+            r = r < 0 ? 0 : (r > m - 1 ? m - 1 : r);
+            if (q & 1) s_last[q >> 1] = (int32_t)r; else s_first[q >> 1] = (int32_t)r;
+        }
+        __syncthreads();
+    }
     int t = 0;
     for (int64_t t0 = b0; t0 < b1; t0 += PSUB, ++t) {   // uniform trip count across the block
         const int64_t t1 = t0 + PSUB < b1 ? t0 + PSUB : b1;
@@ -422,7 +490,7 @@ mo_status partition_decide_async(const mo_csr &a, uint32_t *acc, uint32_t *flag_
     return MO_OK;
 }
 
-// Device memory the partition needs besides the histogram: [counts | offsets | scan temporary | keys16].
+// Device memory the partition needs besides the histogram: [counts | offsets | scan temporary | tile rows | keys16].
 size_t partition_scratch_bytes(const mo_csr &a)
 {
     int64_t share = 0;
@@ -430,7 +498,8 @@ size_t partition_scratch_bytes(const mo_csr &a)
     const size_t cells = (size_t)partition_buckets(a) * (size_t)nblk;
     const size_t ints = ((cells + 1) * 4 + 255) / 256 * 256;   // the scan also writes the total behind its last prefix
     const size_t tmp = (scan_tmp_bytes((int64_t)cells) + 255) / 256 * 256;
-    return 2 * ints + tmp + (size_t)a.nnz * sizeof(uint16_t) + 256;
+    const size_t trows = ((size_t)nblk * (size_t)(share / PSUB) * 2 * 4 + 255) / 256 * 256;
+    return 2 * ints + tmp + trows + (size_t)a.nnz * sizeof(uint16_t) + 256;
 }
 
 // The diagonal counts by partition.  buf: partition_scratch_bytes(a) of device memory.  hist (or nullptr): receives all
@@ -451,11 +520,13 @@ mo_status partition_counts(const mo_csr &a, const mo_params &p, void *buf, uint3
     int32_t *counts = (int32_t *)buf;
     int32_t *offs = (int32_t *)((char *)buf + ints);
     void *scan_tmp = (char *)buf + 2 * ints;
-    uint16_t *keys16 = (uint16_t *)((char *)buf + 2 * ints + tmp);
-    hipLaunchKernelGGL(k_part_count, dim3((unsigned)nblk), dim3(PT), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, ndiag, share, nb, counts, err);
+    const size_t trows = ((size_t)nblk * (size_t)(share / PSUB) * 2 * 4 + 255) / 256 * 256;
+    int32_t *tile_rows = (int32_t *)((char *)buf + 2 * ints + tmp);
+    uint16_t *keys16 = (uint16_t *)((char *)buf + 2 * ints + tmp + trows);
+    hipLaunchKernelGGL(k_part_count, dim3((unsigned)nblk), dim3(PT), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, ndiag, share, nb, counts, err, tile_rows);
     MO_LAUNCH_CHECK();
     MO_TRY(exclusive_scan_i32(counts, offs, (int64_t)cells, scan_tmp, s));
-    hipLaunchKernelGGL(k_part_scatter, dim3((unsigned)nblk), dim3(PT), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, share, nb, offs, keys16);
+    hipLaunchKernelGGL(k_part_scatter, dim3((unsigned)nblk), dim3(PT), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, share, nb, offs, tile_rows, keys16);
     MO_LAUNCH_CHECK();
     const int64_t mn = a.m < a.n ? a.m : a.n;
     hipLaunchKernelGGL(k_part_hist, dim3((unsigned)nb), dim3(PH), 0, s, keys16, offs, nblk, nb, a.nnz, ndiag,
