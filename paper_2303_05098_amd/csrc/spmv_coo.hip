@@ -23,9 +23,6 @@ __global__ void k_zero(T *__restrict__ p, int64_t n)
     for (; i < n; i += stride) p[i] = (T)0;
 }
 
-template <typename T> struct Vec2;
-template <> struct Vec2<double> { using type = double2; };
-template <> struct Vec2<float> { using type = float2; };
 
 template <typename T, int COO_STRIP, bool ACC>
 __global__ __launch_bounds__(COO_B) void k_coo_tile(const int32_t *__restrict__ row, const int32_t *__restrict__ col,
