@@ -55,7 +55,7 @@ struct TileRows {
 
 // The first and the last row of every tile of a block's share: 2 * tiles searches for the largest row r with
 // row_ptr[r] <= p.  A binary search is some twenty dependent loads, which cost more than the tile's own work, so the
-// block searches with all its threads instead, in three rounds of independent loads: PT rows spread over the whole
+// block searches with all its threads instead, in three steps of independent loads: PT rows spread over the whole
 // matrix, then 32 rows inside the interval each search fell into, then 64 inside the next, and a few binary steps on
 // what is left (none for matrices of up to a million rows).  scr: PSUB ints of LDS (the tile stage, not in use yet);
 // shares of more than 32 tiles (more than 2^27 entries in the matrix) search one boundary per thread the plain way.
@@ -91,7 +91,7 @@ __device__ __forceinline__ void find_tile_rows(const int32_t *__restrict__ row_p
     }
     __shared__ int32_t s_lo[2 * FT_MAX], s_hi[2 * FT_MAX];
     const int nq = 2 * nt;
-    const int64_t l1 = (m + PT - 1) / PT;   // rows between the probes of round 1
+    const int64_t l1 = (m + PT - 1) / PT;   // rows between the probes of the first step
     {
         const int64_t r = (int64_t)threadIdx.x * l1;
         scr[threadIdx.x] = row_ptr[r < m ? r : m - 1];
@@ -104,7 +104,7 @@ __device__ __forceinline__ void find_tile_rows(const int32_t *__restrict__ row_p
     }
     __syncthreads();
     int64_t len = l1;
-    for (int probes = 32; probes <= 64; probes *= 2) {   // rounds 2 and 3
+    for (int probes = 32; probes <= 64; probes *= 2) {   // second and third step
         const int64_t step = (len + probes - 1) / probes;
         for (int i = threadIdx.x; i < nq * probes; i += PT) {
             const int q = i / probes, j = i % probes;

@@ -39,7 +39,36 @@ constexpr int TB = 512;           // threads per block of the traversal: 8 waves
 constexpr int TCAP = 1920;        // entries a wave stages at a time: 64 rows of up to 30 entries are walked in one go.  Not
                                   // 2048 (64 rows of SHORT_ROW entries): with the hash table that made 82 120 bytes of LDS per
                                   // block, 200 bytes too many for two blocks per CU, and the kernel ran with 8 waves per CU
-static_assert((TB / WAVE) * TCAP * 4 + HT_SIZE * 8 + 1024 <= 80 * 1024, "two traversal blocks must fit one CU's 160 KB of LDS");
+constexpr int HV_SIZE = 256;      // slots of the block's second, small table: diagonals that came out of a candidate list
+constexpr int HV_PROBES = 4;
+static_assert((TB / WAVE) * TCAP * 4 + HT_SIZE * 8 + HV_SIZE * 8 + 1024 <= 80 * 1024, "two traversal blocks must fit one CU's 160 KB of LDS");
+
+// A diagonal that a candidate list has counted is a frequent one.  When its list is given up (rows that hold too many
+// entries off the list) its entries come one by one, and they must not end as global atomics on one address (served
+// one after the other: a 4 M-row band with 30 % scattered entries took 38 ms that way, the hash table being full of
+// scattered diagonals by the time the lists failed).  Such diagonals therefore get a table of their own, which
+// single entries look up first.
+__device__ __forceinline__ bool heavy_insert_add(int key, uint32_t n, int *hv_key, uint32_t *hv_cnt)
+{
+    const uint32_t h = ((uint32_t)key * 2654435761u) >> 24;   // 8 bits
+    for (int p = 0; p < HV_PROBES; ++p) {
+        const int s = (int)((h + p) & (HV_SIZE - 1));
+        const int old = atomicCAS(&hv_key[s], -1, key);
+        if (old == -1 || old == key) { atomicAdd(&hv_cnt[s], n); return true; }
+    }
+    return false;
+}
+__device__ __forceinline__ bool heavy_find_add(int key, const int *hv_key, uint32_t *hv_cnt)
+{
+    const uint32_t h = ((uint32_t)key * 2654435761u) >> 24;
+    for (int p = 0; p < HV_PROBES; ++p) {
+        const int s = (int)((h + p) & (HV_SIZE - 1));
+        const int k = hv_key[s];
+        if (k == key) { atomicAdd(&hv_cnt[s], 1u); return true; }
+        if (k == -1) return false;   // nothing is ever removed: the key is not there (or is being put there: counted elsewhere then)
+    }
+    return false;
+}
 constexpr int TSTAGE = 16;        // column loads a lane has in flight while a chunk is staged: two round trips to memory per
                                   // full chunk (8: four round trips, with the few waves this kernel runs each one shows)
 constexpr int TRAV_BLOCKS = 512;  // at most this many blocks: every block ends with one atomic per distinct
@@ -59,12 +88,15 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
     if (skip && *skip) return;   // a kernel ahead in the stream has decided that another path counts this matrix
     __shared__ int ht_key[DO_HIST ? HT_SIZE : 1];
     __shared__ uint32_t ht_cnt[DO_HIST ? HT_SIZE : 1];
+    __shared__ int hv_key[DO_HIST ? HV_SIZE : 1];
+    __shared__ uint32_t hv_cnt[DO_HIST ? HV_SIZE : 1];
     __shared__ int ht_full;
     __shared__ int32_t s_col_all[(TB / WAVE) * TCAP];
     int32_t *s_col = s_col_all + (threadIdx.x / WAVE) * TCAP;
     if (threadIdx.x == 0) ht_full = 0;
     if (DO_HIST) {
         for (int i = threadIdx.x; i < HT_SIZE; i += TB) { ht_key[i] = -1; ht_cnt[i] = 0u; }
+        for (int i = threadIdx.x; i < HV_SIZE; i += TB) { hv_key[i] = -1; hv_cnt[i] = 0u; }
     }
     __syncthreads();
     const int lane = lane_id();
@@ -176,7 +208,7 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
                     while (below) {                            // entries on diagonals that are not in the list
                         nmiss += (int)__popcll(below);
                         if (cur < target) {
-                            count_key(cur, 1u, ht_key, ht_cnt, &ht_full, hist);
+                            if (!heavy_find_add(cur, hv_key, hv_cnt)) count_key(cur, 1u, ht_key, ht_cnt, &ht_full, hist);
                             advance();
                         }
                         below = __builtin_amdgcn_sicmp(cur, target, 40);
@@ -193,14 +225,14 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
                 while (left) {                                 // entries beyond the last candidate
                     nmiss += (int)__popcll(left);
                     if (cur != NONE) {
-                        count_key(cur, 1u, ht_key, ht_cnt, &ht_full, hist);
+                        if (!heavy_find_add(cur, hv_key, hv_cnt)) count_key(cur, 1u, ht_key, ht_cnt, &ht_full, hist);
                         advance();
                     }
                     left = __builtin_amdgcn_sicmp(cur, NONE, 33);
                 }
                 if (nc > 0) {
                     if (nmiss * 4 > nhit + nmiss) {            // the list does not fit these rows: write it out, start over
-                        if (lane < ncand && ccnt) count_key(cand, (uint32_t)ccnt, ht_key, ht_cnt, &ht_full, hist);
+                        if (lane < ncand && ccnt && !heavy_insert_add(cand, (uint32_t)ccnt, hv_key, hv_cnt)) count_key(cand, (uint32_t)ccnt, ht_key, ht_cnt, &ht_full, hist);
                         cand = NONE; ccnt = 0; ncand = 0;
                         ++tmpl_fail;
                     } else {
@@ -225,11 +257,15 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
         }
     }
     if (DO_HIST) {
-        if (lane < ncand && ccnt) count_key(cand, (uint32_t)ccnt, ht_key, ht_cnt, &ht_full, hist);
+        if (lane < ncand && ccnt && !heavy_insert_add(cand, (uint32_t)ccnt, hv_key, hv_cnt)) count_key(cand, (uint32_t)ccnt, ht_key, ht_cnt, &ht_full, hist);
         __syncthreads();
         for (int i = threadIdx.x; i < HT_SIZE; i += TB) {
             const uint32_t c = ht_cnt[i];
             if (c) atomicAdd(&hist[ht_key[i]], c);
+        }
+        for (int i = threadIdx.x; i < HV_SIZE; i += TB) {
+            const uint32_t c = hv_cnt[i];
+            if (c) atomicAdd(&hist[hv_key[i]], c);
         }
     }
     // row-length statistics and the error flag of this block

@@ -57,6 +57,9 @@ def small_cases():
     spread = [1500 * k for k in range(-8, 8)]
     out.append(("spread16", *synth.banded_scatter(20000, spread, 0, 100, 15)))
     out.append(("spread16s", *synth.banded_scatter(20000, spread, 2, 100, 16)))
+    # a band with as many scattered entries as the feature traversal's candidate lists do not survive (30 %): the band's
+    # diagonals are then counted entry by entry through the block's table of frequent diagonals
+    out.append(("band30s", *synth.banded_scatter(60000, synth.C4_OFFSETS, 30, 100, 17)))
     return out
 
 
