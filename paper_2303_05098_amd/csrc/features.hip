@@ -32,7 +32,7 @@ namespace mo {
 //      stencil's 27 diagonals cost 27 global atomics per block, not one per wave and step).
 // Keys that find no free slot within a few probes (matrices with many distinct diagonals) go straight to memory.
 // A row longer than SHORT_ROW is walked by the whole wave with coalesced loads; entries of one row lie on distinct
-// diagonals, so they are counted directly.
+// diagonals, so the lanes of one step never meet in a table slot.
 static_assert(SHORT_ROW <= WAVE, "one candidate diagonal per lane");
 
 constexpr int TB = 512;           // threads per block of the traversal: 8 waves share one hash table
@@ -252,7 +252,12 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
                 const int64_t c = col_idx[q], cp = q > rlo ? (int64_t)col_idx[q - 1] : (int64_t)-1;
                 const bool ok = c >= 0 && c < n && c > cp;
                 if (!ok) err = true;
-                else if (DO_HIST) atomicAdd(&hist[c - r + (m - 1)], 1u);
+                else if (DO_HIST) {
+                    // through the block's tables like every other entry: the rows of a wide band hold the same diagonals,
+                    // and one atomic per entry on a few hundred addresses took 50 - 100 CSR SpMVs
+                    const int key = (int)(c - r + (m - 1));
+                    if (!heavy_find_add(key, hv_key, hv_cnt)) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
+                }
             }
         }
     }

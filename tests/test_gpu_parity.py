@@ -60,6 +60,8 @@ def small_cases():
     # a band with as many scattered entries as the feature traversal's candidate lists do not survive (30 %): the band's
     # diagonals are then counted entry by entry through the block's table of frequent diagonals
     out.append(("band30s", *synth.banded_scatter(60000, synth.C4_OFFSETS, 30, 100, 17)))
+    # a band of 40 diagonals: every row is longer than the traversal's lane-per-row limit and is walked by a whole wave
+    out.append(("band40", *synth.banded_scatter(20000, range(-20, 20), 1, 100, 18)))
     return out
 
 
