@@ -248,15 +248,26 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
             longmask &= longmask - 1;
             const int64_t r = base + (threadIdx.x - lane) + l;
             const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
-            for (int q = rlo + lane; q < rhi; q += WAVE) {
-                const int64_t c = col_idx[q], cp = q > rlo ? (int64_t)col_idx[q - 1] : (int64_t)-1;
-                const bool ok = c >= 0 && c < n && c > cp;
-                if (!ok) err = true;
-                else if (DO_HIST) {
-                    // through the block's tables like every other entry: the rows of a wide band hold the same diagonals,
-                    // and one atomic per entry on a few hundred addresses took 50 - 100 CSR SpMVs
-                    const int key = (int)(c - r + (m - 1));
-                    if (!heavy_find_add(key, hv_key, hv_cnt)) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
+            constexpr int LU = 8;   // loads of LU steps are issued together: one wave walks the row, and a row may hold millions
+            for (int q0 = rlo + lane; q0 < rhi; q0 += WAVE * LU) {
+                int64_t c[LU], cp[LU];
+#pragma unroll
+                for (int u = 0; u < LU; ++u) {
+                    const int q = q0 + u * WAVE, qc = q < rhi ? q : rhi - 1;   // clamped into the row: unconditional loads
+                    c[u] = col_idx[qc];
+                    cp[u] = qc > rlo ? (int64_t)col_idx[qc - 1] : (int64_t)-1;
+                }
+#pragma unroll
+                for (int u = 0; u < LU; ++u) {
+                    if (q0 + u * WAVE >= rhi) continue;
+                    const bool ok = c[u] >= 0 && c[u] < n && c[u] > cp[u];
+                    if (!ok) err = true;
+                    else if (DO_HIST) {
+                        // through the block's tables like every other entry: the rows of a wide band hold the same
+                        // diagonals, and one atomic per entry on a few hundred addresses took 50 - 100 CSR SpMVs
+                        const int key = (int)(c[u] - r + (m - 1));
+                        if (!heavy_find_add(key, hv_key, hv_cnt)) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
+                    }
                 }
             }
         }
