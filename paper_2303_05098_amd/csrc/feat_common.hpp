@@ -18,6 +18,17 @@ struct DiagPart {
     unsigned long long n_diag, n_true;
 };
 
+// Rows that are too long for one wave (one row of a million entries, walked 64 entries at a time, costs a hundred
+// SpMVs) are not walked where they are met: the traversal notes them here and a kernel of its own spreads their
+// entries over the whole chip (k_long_rows in features.hip).  count may exceed LR_CAP (rows beyond it are walked in
+// place after all); count and done are zero between calls (the kernel's last block clears them).
+constexpr int VLONG_ROW = 8192;
+constexpr int LR_CAP = 1022;
+struct LongRows {
+    uint32_t count, done;
+    int32_t rows[LR_CAP];
+};
+
 constexpr int FB = 256;        // threads per block
 constexpr int SHORT_ROW = 32;  // entries of a row handled lane-per-row; the rest is walked by the whole wave
 

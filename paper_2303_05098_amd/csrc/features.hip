@@ -83,7 +83,8 @@ template <bool DO_HIST>
 __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   int64_t m, int64_t n, int64_t nnz, int64_t rows_per_block,
                                                   uint32_t *__restrict__ hist, RowPart *__restrict__ part,
-                                                  const uint32_t *__restrict__ skip)
+                                                  const uint32_t *__restrict__ skip, LongRows *__restrict__ lr,
+                                                  uint32_t *__restrict__ lr_flag)
 {
     if (skip && *skip) return;   // a kernel ahead in the stream has decided that another path counts this matrix
     __shared__ int ht_key[DO_HIST ? HT_SIZE : 1];
@@ -129,6 +130,16 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
             sq += l * l;
         }
         const int len = hi - lo;
+        // A very long row is noted for k_long_rows and not walked here (its length has been counted above).
+        bool deferred = false;
+        if (lr && rv && len > VLONG_ROW) {
+            const uint32_t slot = atomicAdd(&lr->count, 1u);
+            if (slot < (uint32_t)LR_CAP) {
+                lr->rows[slot] = (int32_t)row;
+                if (lr_flag) *lr_flag = 1u;
+                deferred = true;
+            }
+        }
         // The entries of the wave's 64 rows are one contiguous run of col_idx.  It is streamed through the wave's LDS
         // region with coalesced loads, in chunks that hold whole rows (as many consecutive rows as fit TCAP entries),
         // and every lane picks the entries of its own row out of LDS.  Whole rows per chunk keep step k of the walk
@@ -242,7 +253,7 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
             }
             first = last + 1;
         }
-        uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+        uint64_t longmask = ballot64(rv && len > SHORT_ROW && !deferred);
         while (longmask) {
             const int l = __ffsll((unsigned long long)longmask) - 1;
             longmask &= longmask - 1;
@@ -304,6 +315,50 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
     }
 }
 
+// The rows the traversal noted in lr, entry-parallel over the whole grid: every block takes chunks of LB * LR_U entries
+// of each row in turn, checks them (inside [0, n), above their predecessor) and, with DO_HIST, counts them straight
+// into the histogram (the entries of one row lie on distinct diagonals: no two atomics of a chunk meet).  An error is
+// left in part[0].err, where the host looks for the traversal's errors.  The block that finishes last clears the list.
+constexpr int LB = 256, LR_U = 4, LR_BLOCKS = 512;
+template <bool DO_HIST>
+__global__ __launch_bounds__(LB) void k_long_rows(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, int64_t m,
+                                                  int64_t n, int64_t nnz, uint32_t *__restrict__ hist, LongRows *__restrict__ lr,
+                                                  RowPart *__restrict__ part)
+{
+    const uint32_t cnt_all = lr->count;
+    const int cnt = (int)(cnt_all < (uint32_t)LR_CAP ? cnt_all : (uint32_t)LR_CAP);
+    bool err = false;
+    for (int li = 0; li < cnt; ++li) {
+        int64_t row = lr->rows[li];
+        row = row < 0 ? 0 : (row > m - 1 ? m - 1 : row);
+        int64_t lo = row_ptr[row], hi = row_ptr[row + 1];
+        lo = lo < 0 ? 0 : (lo > nnz ? nnz : lo);
+        hi = hi < lo ? lo : (hi > nnz ? nnz : hi);
+        for (int64_t q0 = lo + (int64_t)blockIdx.x * (LB * LR_U) + threadIdx.x; q0 - threadIdx.x < hi; q0 += (int64_t)gridDim.x * (LB * LR_U)) {
+            int64_t c[LR_U], cp[LR_U];
+#pragma unroll
+            for (int u = 0; u < LR_U; ++u) {
+                const int64_t q = q0 + u * LB, qc = q < hi ? q : hi - 1;   // hi > lo here
+                c[u] = col_idx[qc];
+                cp[u] = qc > lo ? (int64_t)col_idx[qc - 1] : (int64_t)-1;
+            }
+#pragma unroll
+            for (int u = 0; u < LR_U; ++u) {
+                if (q0 + u * LB >= hi) continue;
+                const bool ok = c[u] >= 0 && c[u] < n && c[u] > cp[u];
+                if (!ok) err = true;
+                else if (DO_HIST) atomicAdd(&hist[c[u] - row + (m - 1)], 1u);
+            }
+        }
+    }
+    if (err) part[0].err = 1ull;   // every writer stores the same value
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        if (atomicAdd(&lr->done, 1u) == gridDim.x - 1) { lr->count = 0u; lr->done = 0u; }
+    }
+}
+
 // The row half of the traversal alone: row lengths (max, min, sum of squares) and the row-pointer half of the CSR
 // precondition (row_ptr[0] = 0, row_ptr[m] = nnz, non-decreasing, inside [0, nnz]), for the path that counts the
 // diagonals by partition and checks the columns there.  Same block layout and results as k_traverse.
@@ -349,15 +404,18 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     int64_t rows_per_block = (a.m + TRAV_BLOCKS - 1) / TRAV_BLOCKS;
     rows_per_block = ((rows_per_block + TB - 1) / TB) * TB;
     const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;   // 1 .. TRAV_BLOCKS
-    // one allocation: [diagonal counters | row partials | histogram]
     const int64_t ndiag = a.m + a.n - 1;
-    const size_t head = 256 + (size_t)TRAV_BLOCKS * sizeof(RowPart);
+    // one allocation: [diagonal counters | row partials | list of very long rows | histogram]
+    static_assert(sizeof(LongRows) == 4096, "the list of very long rows owns 4096 bytes");
+    const size_t head = 256 + sizeof(LongRows) + (size_t)TRAV_BLOCKS * sizeof(RowPart);
     static_assert(sizeof(Counters) <= 256, "the counters own the first 256 bytes");
     char *base = (char *)scratch.get(head + (want_hist ? (size_t)ndiag * sizeof(uint32_t) : 0));
     if (!base) return MO_E_ALLOC;
     Counters *ctr = (Counters *)base;
     RowPart *part = (RowPart *)(base + 256);
+    LongRows *lr = (LongRows *)(base + 256 + (size_t)TRAV_BLOCKS * sizeof(RowPart));
     uint32_t *hist = want_hist ? (uint32_t *)(base + head) : nullptr;
+    const bool may_defer = a.nnz > VLONG_ROW;   // a row of more than VLONG_ROW entries can exist: it goes to k_long_rows
     bool by_partition = false;
     if (want_hist && partition_possible(a)) {   // scattered columns: nothing to merge, see feat_part.hip
         uint32_t *sdev = (uint32_t *)scratch.get(partition_sample_bytes());
@@ -376,17 +434,33 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     } else if (want_hist) {
         hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr);
         MO_LAUNCH_CHECK();
+        if (may_defer) {
+            hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, (uint32_t *)lr, (int64_t)2, 0u);
+            MO_LAUNCH_CHECK();
+        }
         hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part, (const uint32_t *)nullptr);
+                           rows_per_block, hist, part, (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr, (uint32_t *)nullptr);
         MO_LAUNCH_CHECK();
+        if (may_defer) {
+            hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part);
+            MO_LAUNCH_CHECK();
+        }
         const int64_t mn = a.m < a.n ? a.m : a.n;
         hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
                            (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
         MO_LAUNCH_CHECK();
     } else {
+        if (may_defer) {
+            hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, (uint32_t *)lr, (int64_t)2, 0u);
+            MO_LAUNCH_CHECK();
+        }
         hipLaunchKernelGGL(k_traverse<false>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part, (const uint32_t *)nullptr);
+                           rows_per_block, hist, part, (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr, (uint32_t *)nullptr);
         MO_LAUNCH_CHECK();
+        if (may_defer) {
+            hipLaunchKernelGGL(k_long_rows<false>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part);
+            MO_LAUNCH_CHECK();
+        }
     }
     struct { Counters c; char pad[256 - sizeof(Counters)]; RowPart part[TRAV_BLOCKS]; } h;
     static_assert(sizeof(h) == 256 + TRAV_BLOCKS * sizeof(RowPart), "host mirror of the head of the scratch block");
@@ -432,9 +506,9 @@ constexpr int DIAG_BLOCKS = 2048;
 // dpart[blockIdx.x] (no atomics: the host adds the few hundred partial results).
 __global__ __launch_bounds__(FB) void k_diag_count_clear(uint32_t *__restrict__ hist, int64_t nd, unsigned long long thr_rhs,
                                                           unsigned long long td_den, DiagPart *__restrict__ dpart,
-                                                          const uint32_t *__restrict__ skip)
+                                                          const uint32_t *__restrict__ skip, const uint32_t *__restrict__ skip2)
 {
-    if (skip && *skip) return;
+    if ((skip && *skip) || (skip2 && *skip2)) return;
     unsigned long long c_nd = 0, c_td = 0;
     const int64_t stride = (int64_t)gridDim.x * FB;
     for (int64_t i = (int64_t)blockIdx.x * FB + threadIdx.x; i < nd; i += stride) {
@@ -495,9 +569,12 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         if (g_fc.dev) dev_free(g_fc.dev, s);
         if (g_fc.pbuf && g_fc.device != dev_now) { dev_free(g_fc.pbuf, s); g_fc.pbuf = nullptr; g_fc.pbuf_cap = 0; }
         g_fc.hist_cap = ndiag + ndiag / 2;
-        g_fc.dev = (uint32_t *)dev_alloc(((size_t)g_fc.hist_cap + 64) * sizeof(uint32_t), s);   // + the sample's counters and flag
+        // + the sample's counters and flag (64 words) + the list of very long rows
+        constexpr size_t TAIL = 64 + sizeof(LongRows) / sizeof(uint32_t);
+        g_fc.hist_cap = (g_fc.hist_cap + 63) / 64 * 64;   // the list starts on a 256-byte boundary
+        g_fc.dev = (uint32_t *)dev_alloc(((size_t)g_fc.hist_cap + TAIL) * sizeof(uint32_t), s);
         if (g_fc.dev) {
-            hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, g_fc.dev + g_fc.hist_cap, (int64_t)64, 0u);
+            hipLaunchKernelGGL(k_fill_u32, dim3(4), dim3(256), 0, s, g_fc.dev + g_fc.hist_cap, (int64_t)TAIL, 0u);
             MO_LAUNCH_CHECK();
         }
         g_fc.clean = false;
@@ -536,16 +613,30 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(g_fc.hist_cap, FB * 4, 4096)), dim3(FB), 0, s, hist, g_fc.hist_cap, 0u);
         MO_LAUNCH_CHECK();
     }
+    // Rows of more than VLONG_ROW entries are noted by the traversal, not walked; the counting kernel then skips itself,
+    // and the host, which learns of them with the results, sends k_long_rows and the counting kernel after them.
+    LongRows *lr = a.nnz > VLONG_ROW ? (LongRows *)(g_fc.dev + g_fc.hist_cap + 64) : (LongRows *)nullptr;
+    uint32_t *long_host = flag_host + 2;
+    *long_host = 0u;
     hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                       rows_per_block, hist, part, sampled ? flag_dev : (const uint32_t *)nullptr);
+                       rows_per_block, hist, part, sampled ? flag_dev : (const uint32_t *)nullptr, lr, long_host);
     MO_LAUNCH_CHECK();
     const int64_t mn = a.m < a.n ? a.m : a.n;
     int dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
     hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
                        (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart,
-                       sampled ? flag_dev : (const uint32_t *)nullptr);
+                       sampled ? flag_dev : (const uint32_t *)nullptr, lr ? &lr->count : (const uint32_t *)nullptr);
     MO_LAUNCH_CHECK();
     MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
+    if (lr && *long_host != 0u) {
+        hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part);
+        MO_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
+                           (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart,
+                           (const uint32_t *)nullptr, (const uint32_t *)nullptr);
+        MO_LAUNCH_CHECK();
+        MO_HIP(hipStreamSynchronize(s));
+    }
     g_fc.clean = true;                 // skipped or not, the kernels leave the histogram all zero
     const bool by_partition = sampled && *flag_host != 0u;
     if (by_partition) {
@@ -592,6 +683,7 @@ namespace {
 
 constexpr int64_t STATIC_MAX_DIAGS = (int64_t)MO_STATIC_MAX_DIAGS;
 struct StaticScratch {
+    LongRows lr;               // zero when the module is loaded, cleared again by the kernel that reads it
     uint32_t hist[STATIC_MAX_DIAGS];
     RowPart part[TRAV_BLOCKS];
     DiagPart dpart[DIAG_BLOCKS];
@@ -662,12 +754,19 @@ mo_status features_static(const mo_csr &a, const mo_params &p, mo_feature_result
     rows_per_block = ((rows_per_block + TB - 1) / TB) * TB;
     const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;
     hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                       rows_per_block, sc->hist, sc->part, (const uint32_t *)nullptr);
+                       rows_per_block, sc->hist, sc->part, (const uint32_t *)nullptr, a.nnz > VLONG_ROW ? &sc->lr : (LongRows *)nullptr,
+                       (uint32_t *)nullptr);
     MO_LAUNCH_CHECK();
+    if (a.nnz > VLONG_ROW) {   // no host in between here: the kernel for very long rows always runs (usually over an empty list)
+        hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, sc->hist, &sc->lr,
+                           sc->part);
+        MO_LAUNCH_CHECK();
+    }
     const int64_t mn = a.m < a.n ? a.m : a.n;
     const int dblocks = grid_for(ndiag, FB * 16, DIAG_BLOCKS);
     hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, sc->hist, ndiag,
-                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, sc->dpart, (const uint32_t *)nullptr);
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, sc->dpart, (const uint32_t *)nullptr,
+                       (const uint32_t *)nullptr);
     MO_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_static_finish, dim3(1), dim3(FB), 0, s, sc->part, (int)row_blocks, sc->dpart, dblocks, a.m, a.n, a.nnz, out_dev);
     MO_LAUNCH_CHECK();

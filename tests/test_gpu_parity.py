@@ -13,6 +13,19 @@ from tests.gpu_util import TOL, gpu_spmv, oracle_inputs, try_convert, upload
 pytestmark = pytest.mark.gpu
 
 
+def very_long_rows():
+    """Two rows of 12 000 and 9 000 entries (every other column, every third) among rows of two: longer than what the
+    feature traversal walks where it meets them, so they go through its list of deferred rows."""
+    m, n, rp, ci, v = synth.uniform_rows(30000, 2, 19)
+    lens = np.diff(rp).astype(np.int64)
+    lens[700], lens[20001] = 12000, 9000
+    rp2 = np.zeros(m + 1, np.int64)
+    np.cumsum(lens, out=rp2[1:])
+    ci2 = np.concatenate([ci[:rp[700]], np.arange(12000, dtype=np.int32) * 2 + 1, ci[rp[701]:rp[20001]],
+                          np.arange(9000, dtype=np.int32) * 3, ci[rp[20002]:]])
+    return m, n, rp2.astype(np.int32), ci2.astype(np.int32), synth.uniform_pm1(19, 0, np.arange(ci2.shape[0]))
+
+
 def small_cases():
     """(name, m, n, row_ptr, col_idx, val) — sizes the oracle finishes in seconds."""
     out = [("c1", *synth.config(1)),
@@ -39,6 +52,7 @@ def small_cases():
     ci2 = np.concatenate([ci[:rp[1500]], np.arange(3000, dtype=np.int32), ci[rp[1501]:]])
     v2 = synth.uniform_pm1(13, 0, np.arange(ci2.shape[0]))
     out.append(("long_row", m, n, rp2.astype(np.int32), ci2.astype(np.int32), v2))
+    out.append(("very_long_rows", *very_long_rows()))
     # a tridiagonal matrix with a 256-row stretch of 29 diagonals: the mean row is short, so a wave takes 64 rows, and in
     # the stretch their entries exceed one LDS stage of the conversion kernels (rows past the staged window)
     m = n = 4096
@@ -238,6 +252,13 @@ def bad_csr(kind):
     elif kind == "col_duplicate":
         p = int(np.nonzero(np.diff(rp) >= 2)[0][0])
         ci[rp[p] + 1] = ci[rp[p]]
+    elif kind in ("vlong_unsorted", "vlong_col_high"):
+        m, n, rp, ci, v = very_long_rows()
+        ci = ci.copy()
+        if kind == "vlong_unsorted":
+            ci[rp[20001] + 7000], ci[rp[20001] + 7001] = ci[rp[20001] + 7001], ci[rp[20001] + 7000]
+        else:
+            ci[rp[701] - 1] = n
     elif kind == "long_row_unsorted":
         m, n, rp, ci, v = synth.random_csr(4, 400, 0.9, 22)
         ci = ci.copy()
@@ -246,7 +267,7 @@ def bad_csr(kind):
 
 
 @pytest.mark.parametrize("kind", ["rp0", "rp_decreasing", "rp_last", "rp_beyond", "rp_negative", "col_high", "col_negative",
-                                  "col_unsorted", "col_duplicate", "long_row_unsorted"])
+                                  "col_unsorted", "col_duplicate", "long_row_unsorted", "vlong_unsorted", "vlong_col_high"])
 def test_invalid_csr_is_rejected(kind):
     m, n, rp, ci, v = bad_csr(kind)
     a = upload(m, n, rp, ci, v)

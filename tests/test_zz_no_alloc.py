@@ -46,6 +46,18 @@ def test_two_calls_second_smaller():
     check(m, n, rp, ci, v, {"td_num": 1, "td_den": 5})
 
 
+def test_rows_too_long_for_one_wave():
+    """Rows of 12 000 and 9 000 entries go through the list of deferred rows that lives in the same device array: twice, so
+    that the second call finds the list as the first one left it, then with such a row out of order."""
+    from tests.test_gpu_parity import bad_csr, very_long_rows
+    m, n, rp, ci, v = very_long_rows()
+    check(m, n, rp, ci, v)
+    check(m, n, rp, ci, v)
+    status, _ = run_static(upload(*bad_csr("vlong_unsorted")))
+    assert status == mo.MO_E_CSR_INVALID
+    check(m, n, rp, ci, v)
+
+
 def test_largest_size_and_limit():
     m, n, rp, ci, v = synth.config(2)          # m + n - 1 = 4 194 303: just inside the limit
     assert m + n - 1 <= mo.STATIC_MAX_DIAGS
