@@ -143,7 +143,25 @@ __global__ void k_coo_fixup(const int32_t *__restrict__ carry_row, const T *__re
     if (r < 0) return;
     if (k > 0 && carry_row[k - 1] == r) return;
     T total = carry_val[k];
-    for (int64_t u = k + 1; u < tiles && carry_row[u] == r; ++u) total += carry_val[u];
+    // the same sum in the same order, with the loads of FU tiles in flight together: a row that crosses a thousand tiles
+    // is otherwise a thousand dependent loads
+    constexpr int FU = 16;
+    bool more = true;
+    for (int64_t u0 = k + 1; more && u0 < tiles; u0 += FU) {
+        int32_t rr[FU];
+        T vv[FU];
+#pragma unroll
+        for (int j = 0; j < FU; ++j) {
+            const int64_t u = u0 + j < tiles ? u0 + j : tiles - 1;
+            rr[j] = carry_row[u];
+            vv[j] = carry_val[u];
+        }
+#pragma unroll
+        for (int j = 0; j < FU; ++j) {
+            more = more && u0 + j < tiles && rr[j] == r;
+            if (more) total += vv[j];
+        }
+    }
     y[r] += total;
 }
 
