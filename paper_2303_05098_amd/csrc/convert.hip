@@ -5,6 +5,7 @@
 // Rows are mapped one per lane, which makes the writes into the slot-major ELL slabs and the diagonal-major DIA
 // slabs coalesced; a row longer than SHORT_ROW entries is handled by the whole wave.
 #include "dev_common.hpp"
+#include "feat_common.hpp"
 #include "mo_internal.hpp"
 
 #include <algorithm>
@@ -14,7 +15,7 @@
 namespace mo {
 
 constexpr int CB = 256;
-constexpr int SHORT_ROW = 32;
+// SHORT_ROW (feat_common.hpp): entries of a row handled lane-per-row; the rest is walked by the whole wave
 
 // ------------------------------------------------------------------ row walker
 // Calls f(row, p, s, col, val, own) for every stored entry p of the rows owned by this wave (one row per lane), s =
@@ -29,7 +30,7 @@ constexpr int WALK_U = 4;
 
 template <typename T, class F>
 __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo64, int64_t hi64, const int32_t *__restrict__ col_idx,
-                                              const T *__restrict__ val, int32_t *s_col, T *s_val, F f)
+                                              const T *__restrict__ val, int32_t *s_col, T *s_val, int skip_len, F f)
 {
     const int lane = lane_id();
     const int lo = (int)lo64, hi = (int)hi64;   // positions fit 32 bits: nnz < 2^31
@@ -62,13 +63,14 @@ __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo64
                 if (k + u < cnt) f(row, (int64_t)a + k + u, (int64_t)(a + k + u - lo), cc[u], vv[u], true);
         }
     }
-    uint64_t longmask = ballot64(rv && len > SHORT_ROW);
+    // skip_len > 0: rows longer than that are left to a kernel that spreads their entries over the whole chip
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW && !(skip_len > 0 && len > skip_len));
     while (longmask) {
         const int l = __ffsll((unsigned long long)longmask) - 1;
         longmask &= longmask - 1;
         const int64_t r = row - lane + l;
         const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
-        constexpr int LU = 8;   // loads of LU steps are issued together: one wave walks the row, and a row may hold millions
+        constexpr int LU = 8;   // loads of LU steps are issued together: one wave walks the row
         for (int q0 = rlo + lane; q0 < rhi; q0 += WAVE * LU) {
             int32_t cc[LU];
             T vv[LU];
@@ -279,7 +281,7 @@ __global__ __launch_bounds__(CB) void k_fill_ell(const int32_t *__restrict__ row
                                                   const T *__restrict__ val, int64_t m, int64_t K, int64_t ld,
                                                   int32_t *__restrict__ ecol, T *__restrict__ eval,
                                                   const int32_t *__restrict__ coo_ptr, int32_t *__restrict__ crow,
-                                                  int32_t *__restrict__ ccol, T *__restrict__ cval, int rw)
+                                                  int32_t *__restrict__ ccol, T *__restrict__ cval, int rw, int skip_len)
 {
     const int64_t row = (xcd_block(blockIdx.x, gridDim.x) * (CB / WAVE) + threadIdx.x / WAVE) * rw + lane_id();
     const bool rv = lane_id() < rw && row < m;
@@ -293,7 +295,8 @@ __global__ __launch_bounds__(CB) void k_fill_ell(const int32_t *__restrict__ row
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
     __shared__ T s_val[(CB / WAVE) * WCAP];
     const int w = threadIdx.x / WAVE;
-    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP, [&](int64_t r, int64_t, int64_t s, int32_t c, T v, bool) {
+    walk_rows_lds<T>(rv, row, lo, hi, col_idx, val, s_col + w * WCAP, s_val + w * WCAP, skip_len,
+                     [&](int64_t r, int64_t, int64_t s, int32_t c, T v, bool) {
         if (s < K) {
             ecol[s * ld + r] = c;
             eval[s * ld + r] = v;
@@ -304,6 +307,49 @@ __global__ __launch_bounds__(CB) void k_fill_ell(const int32_t *__restrict__ row
             cval[q] = v;
         }
     });
+}
+
+// The rows that k_fill_ell skipped (longer than VLONG_ROW; listed by the analysis), entry-parallel over the whole grid:
+// the same stores, FL_B * FL_U entries of a row per block and step.  One wave alone walks 64 entries per step, which
+// for a row of a million entries took 5 ms.
+constexpr int FL_B = 256, FL_U = 4, FL_BLOCKS = 512;
+template <typename T>
+__global__ __launch_bounds__(FL_B) void k_fill_ell_long(const LongRows *__restrict__ lr, int nrows, const int32_t *__restrict__ row_ptr,
+                                                        const int32_t *__restrict__ col_idx, const T *__restrict__ val, int64_t m,
+                                                        int64_t K, int64_t ld, int32_t *__restrict__ ecol, T *__restrict__ eval,
+                                                        const int32_t *__restrict__ coo_ptr, int32_t *__restrict__ crow,
+                                                        int32_t *__restrict__ ccol, T *__restrict__ cval)
+{
+    for (int li = 0; li < nrows; ++li) {
+        const int64_t r = lr->rows[li];
+        if (r < 0 || r >= m) continue;   // the list was written for this matrix: never taken
+        const int64_t lo = row_ptr[r], hi = row_ptr[r + 1];
+        for (int64_t q0 = lo + (int64_t)blockIdx.x * (FL_B * FL_U) + threadIdx.x; q0 - threadIdx.x < hi; q0 += (int64_t)gridDim.x * (FL_B * FL_U)) {
+            int32_t cc[FL_U];
+            T vv[FL_U];
+#pragma unroll
+            for (int u = 0; u < FL_U; ++u) {
+                const int64_t q = q0 + u * FL_B, qc = q < hi ? q : hi - 1;
+                cc[u] = ld_stream(col_idx + qc);
+                vv[u] = ld_stream(val + qc);
+            }
+#pragma unroll
+            for (int u = 0; u < FL_U; ++u) {
+                const int64_t q = q0 + u * FL_B;
+                if (q >= hi) continue;
+                const int64_t s = q - lo;
+                if (s < K) {
+                    ecol[s * ld + r] = cc[u];
+                    eval[s * ld + r] = vv[u];
+                } else {
+                    const int64_t p = (int64_t)coo_ptr[r] + (s - K);
+                    crow[p] = (int32_t)r;
+                    ccol[p] = cc[u];
+                    cval[p] = vv[u];
+                }
+            }
+        }
+    }
 }
 
 // Histogram of row lengths.  Regular matrices put every row on the same counter, and same-address atomics serialise
@@ -878,8 +924,14 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         if (b.failed) return MO_E_ALLOC;
         const int rw = rows_per_wave(a.m, a.nnz);
         hipLaunchKernelGGL(k_fill_ell<T>, dim3(wave_blocks_for(h->ld, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m, K, h->ld,
-                           h->ell_col, (T *)h->ell_val, coo_ptr, h->coo_row, h->coo_col, (T *)h->coo_val, rw);
+                           h->ell_col, (T *)h->ell_val, coo_ptr, h->coo_row, h->coo_col, (T *)h->coo_val, rw,
+                           an.n_long > 0 ? (int)VLONG_ROW : 0);
         MO_LAUNCH_CHECK();
+        if (an.n_long > 0) {
+            hipLaunchKernelGGL(k_fill_ell_long<T>, dim3(FL_BLOCKS), dim3(FL_B), 0, s, an.long_rows, an.n_long, a.row_ptr, a.col_idx, aval, a.m,
+                               K, h->ld, h->ell_col, (T *)h->ell_val, coo_ptr, h->coo_row, h->coo_col, (T *)h->coo_val);
+            MO_LAUNCH_CHECK();
+        }
         MO_TRY(plan_x_windows(a.row_ptr, a.col_idx, a.m, a.nnz, &h->xplan, s));
         break;
     }

@@ -318,12 +318,13 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
 // The rows the traversal noted in lr, entry-parallel over the whole grid: every block takes chunks of LB * LR_U entries
 // of each row in turn, checks them (inside [0, n), above their predecessor) and, with DO_HIST, counts them straight
 // into the histogram (the entries of one row lie on distinct diagonals: no two atomics of a chunk meet).  An error is
-// left in part[0].err, where the host looks for the traversal's errors.  The block that finishes last clears the list.
+// left in part[0].err, where the host looks for the traversal's errors.  The block that finishes last clears the list
+// (unless a conversion wants it: keep).
 constexpr int LB = 256, LR_U = 4, LR_BLOCKS = 512;
 template <bool DO_HIST>
 __global__ __launch_bounds__(LB) void k_long_rows(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, int64_t m,
                                                   int64_t n, int64_t nnz, uint32_t *__restrict__ hist, LongRows *__restrict__ lr,
-                                                  RowPart *__restrict__ part)
+                                                  RowPart *__restrict__ part, int keep)
 {
     const uint32_t cnt_all = lr->count;
     const int cnt = (int)(cnt_all < (uint32_t)LR_CAP ? cnt_all : (uint32_t)LR_CAP);
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(LB) void k_long_rows(const int32_t *__restrict__ ro
     __syncthreads();
     if (threadIdx.x == 0) {
         __threadfence();
-        if (atomicAdd(&lr->done, 1u) == gridDim.x - 1) { lr->count = 0u; lr->done = 0u; }
+        if (atomicAdd(&lr->done, 1u) == gridDim.x - 1) { if (!keep) lr->count = 0u; lr->done = 0u; }   // keep: the caller reads the list
     }
 }
 
@@ -442,7 +443,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
                            rows_per_block, hist, part, (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr, (uint32_t *)nullptr);
         MO_LAUNCH_CHECK();
         if (may_defer) {
-            hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part);
+            hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part, 1);
             MO_LAUNCH_CHECK();
         }
         const int64_t mn = a.m < a.n ? a.m : a.n;
@@ -458,7 +459,7 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
                            rows_per_block, hist, part, (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr, (uint32_t *)nullptr);
         MO_LAUNCH_CHECK();
         if (may_defer) {
-            hipLaunchKernelGGL(k_long_rows<false>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part);
+            hipLaunchKernelGGL(k_long_rows<false>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part, 1);
             MO_LAUNCH_CHECK();
         }
     }
@@ -466,6 +467,9 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     static_assert(sizeof(h) == 256 + TRAV_BLOCKS * sizeof(RowPart), "host mirror of the head of the scratch block");
     const size_t bytes = 256 + (size_t)row_blocks * sizeof(RowPart);
     MO_HIP(hipMemcpyAsync(&h, base, bytes, hipMemcpyDeviceToHost, s));
+    uint32_t n_long = 0;
+    const bool listed = may_defer && !by_partition;   // the traversal ran with the list
+    if (listed) MO_HIP(hipMemcpyAsync(&n_long, &lr->count, sizeof(n_long), hipMemcpyDeviceToHost, s));
     MO_HIP(hipStreamSynchronize(s));
     unsigned long long mx = 0ull, mnr = ~0ull, sq = 0ull, err = 0ull;
     for (int64_t b = 0; b < row_blocks; ++b) {
@@ -482,6 +486,8 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     out->n_diag = want_hist ? (int64_t)h.c.n_diag : 0;
     out->n_true = want_hist ? (int64_t)h.c.n_true : 0;
     out->hist = hist;
+    out->long_rows = listed ? lr : nullptr;
+    out->n_long = (listed && n_long <= (uint32_t)LR_CAP) ? (int)n_long : 0;
     return MO_OK;
 }
 
@@ -629,7 +635,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     MO_LAUNCH_CHECK();
     MO_HIP(hipStreamSynchronize(s));   // the kernels' stores to the pinned block are visible after this
     if (lr && *long_host != 0u) {
-        hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part);
+        hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part, 0);
         MO_LAUNCH_CHECK();
         hipLaunchKernelGGL(k_diag_count_clear, dim3(dblocks), dim3(FB), 0, s, hist, ndiag,
                            (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, dpart,
@@ -759,7 +765,7 @@ mo_status features_static(const mo_csr &a, const mo_params &p, mo_feature_result
     MO_LAUNCH_CHECK();
     if (a.nnz > VLONG_ROW) {   // no host in between here: the kernel for very long rows always runs (usually over an empty list)
         hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, sc->hist, &sc->lr,
-                           sc->part);
+                           sc->part, 0);
         MO_LAUNCH_CHECK();
     }
     const int64_t mn = a.m < a.n ? a.m : a.n;

@@ -155,6 +155,10 @@ struct Analysis {
     uint64_t sum_sq = 0;
     int64_t n_diag = 0, n_true = 0;
     uint32_t *hist = nullptr;  // device, m + n - 1 counters (only when requested); owned by the Scratch passed in
+    // rows of more than VLONG_ROW entries, which one wave should not walk alone (device list, owned by the Scratch passed
+    // in; n_long = how many it holds, 0 also when there were more than it can hold)
+    struct LongRows *long_rows = nullptr;
+    int n_long = 0;
 };
 
 // Validates the CSR arrays and gathers the row statistics; with want_hist also the per-diagonal counts and the
@@ -166,6 +170,7 @@ void release_feature_cache();
 // The diagonal counts by partition into buckets of diagonals (feat_part.hip), for matrices with scattered columns.
 struct DiagPart;
 struct Counters;
+struct LongRows;
 bool partition_possible(const mo_csr &a);
 int partition_buckets(const mo_csr &a);
 size_t partition_sample_bytes();
