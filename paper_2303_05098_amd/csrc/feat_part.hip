@@ -373,22 +373,28 @@ __global__ __launch_bounds__(PH) void k_part_hist(const uint16_t *__restrict__ k
     }
 }
 
-// The rule of the decision: enough sampled entries, and fewer than a quarter of them on a diagonal that another row
-// of their group of adjacent rows also holds (nothing for the traversal kernel to merge).
-__host__ __device__ inline bool sample_says_partition(uint64_t total, uint64_t repeated) { return total >= 2048 && repeated * 4 < total; }
+// The rule of the decision: enough sampled entries, fewer than a quarter of them on a diagonal that another row of
+// their group of adjacent rows also holds (nothing for the traversal kernel to merge), and no bucket with more than a
+// tenth of them (columns scattered inside a narrow band would leave the last pass to one or two blocks).
+__host__ __device__ inline bool sample_says_partition(uint64_t total, uint64_t repeated, uint64_t biggest_bucket)
+{
+    return total >= 2048 && repeated * 4 < total && biggest_bucket * 10 <= total;
+}
 
 // Block g samples the SR adjacent rows that start at row floor(g * (m - SR + 1) / SG), SE entries of each (entry
 // floor(e * len / SE) of the row, or every entry when the row holds at most SE), and leaves two counts in
 // out[2 g], out[2 g + 1]: the sampled entries, and those among them whose diagonal another row of the group also holds.
-// acc (or nullptr): three device words, zero on entry: the counts are also added up there, and the block that
-// finishes last turns them into the decision (1 = partition), stores it in *flag_dev and *flag_host and clears acc
-// for the next call: kernels launched behind this one can read the decision without the host in between.
+// acc: device words, zero on entry: [0] sampled entries, [1] those on a diagonal that another row of their group also
+// holds, [2] blocks that are done, [3] the decision, [4 .. 4 + nb) sampled entries per bucket.  The block that finishes
+// last turns the counts into the decision (1 = partition), stores it in acc[3] and, when given, in *flag_host (pinned),
+// and clears the rest for the next call: kernels launched behind this one can read the decision without the host in
+// between.
 __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx, int64_t m,
-                                                          int64_t nnz, int64_t ndiag, uint32_t *__restrict__ out, uint32_t *acc,
-                                                          uint32_t *flag_dev, uint32_t *flag_host)
+                                                          int64_t nnz, int64_t ndiag, int nb, uint32_t *acc, uint32_t *flag_host)
 {
     __shared__ int32_t s_key[SR * SE];
     __shared__ uint32_t s_tot[SR * SE / WAVE], s_rep[SR * SE / WAVE];
+    __shared__ uint32_t s_last, s_max;
     const int r = threadIdx.x / SE, e = threadIdx.x % SE;
     const int64_t span = m - SR + 1 > 0 ? m - SR + 1 : 1;
     const int64_t row = (int64_t)blockIdx.x * span / SG + r;
@@ -406,30 +412,49 @@ __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restri
         }
     }
     s_key[threadIdx.x] = key;
+    if (threadIdx.x == 0) { s_last = 0u; s_max = 0u; }
+    // bucket counts of the block first (a structured matrix puts all its samples into a few buckets: one global atomic
+    // per sample on those few addresses took 100 us), then one atomic per bucket the block met
+    __shared__ uint32_t s_bkt[PB_MAX];
+    for (int i = threadIdx.x; i < nb; i += SR * SE) s_bkt[i] = 0u;
     __syncthreads();
+    if (key >= 0) atomicAdd(&s_bkt[key >> PB_BITS], 1u);   // key >> PB_BITS < nb <= PB_MAX
+    __syncthreads();
+    for (int i = threadIdx.x; i < nb; i += SR * SE) {
+        const uint32_t c = s_bkt[i];
+        if (c) atomicAdd(&acc[4 + i], c);
+    }
     int hits = 0;   // every lane runs the whole loop: its LDS reads are independent and overlap
 #pragma unroll 16
     for (int j = 0; j < SR * SE; ++j) hits += (s_key[j] == key) & (j / SE != r);
     const bool rep = key >= 0 && hits > 0;
     const uint32_t tot_w = (uint32_t)__popcll(ballot64(key >= 0)), rep_w = (uint32_t)__popcll(ballot64(rep));
     if (lane_id() == 0) { s_tot[threadIdx.x / WAVE] = tot_w; s_rep[threadIdx.x / WAVE] = rep_w; }
+    __threadfence();   // this thread's bucket count is out before the block reports itself done
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t t = 0, q = 0;
         for (int w = 0; w < SR * SE / WAVE; ++w) { t += s_tot[w]; q += s_rep[w]; }
-        if (out) { out[2 * blockIdx.x] = t; out[2 * blockIdx.x + 1] = q; }
-        if (acc) {
-            atomicAdd(&acc[0], t);
-            atomicAdd(&acc[1], q);
-            __threadfence();
-            if (atomicAdd(&acc[2], 1u) == gridDim.x - 1) {   // every other block's counts are in
-                const uint32_t total = atomicAdd(&acc[0], 0u), repeated = atomicAdd(&acc[1], 0u);
-                const uint32_t want = sample_says_partition(total, repeated) ? 1u : 0u;
-                *flag_dev = want;
-                *flag_host = want;
-                acc[0] = 0u; acc[1] = 0u; acc[2] = 0u;
-            }
-        }
+        atomicAdd(&acc[0], t);
+        atomicAdd(&acc[1], q);
+        __threadfence();
+        if (atomicAdd(&acc[2], 1u) == gridDim.x - 1) s_last = 1u;   // every other block's counts are in
+    }
+    __syncthreads();
+    if (!s_last) return;
+    uint32_t mx = 0u;
+    for (int i = threadIdx.x; i < nb; i += SR * SE) {   // read and cleared with atomics: they were counted with atomics
+        const uint32_t c = atomicExch(&acc[4 + i], 0u);
+        mx = c > mx ? c : mx;
+    }
+    atomicMax(&s_max, mx);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t total = atomicExch(&acc[0], 0u), repeated = atomicExch(&acc[1], 0u);
+        const uint32_t want = sample_says_partition(total, repeated, s_max) ? 1u : 0u;
+        acc[3] = want;
+        if (flag_host) *flag_host = want;
+        atomicExch(&acc[2], 0u);
     }
 }
 
@@ -452,41 +477,30 @@ bool partition_possible(const mo_csr &a)
 
 int partition_buckets(const mo_csr &a) { return (int)((a.m + a.n - 1 + PB_KEYS - 1) / PB_KEYS); }
 
-size_t partition_sample_bytes() { return (size_t)SG * 2 * sizeof(uint32_t); }
+size_t partition_sample_bytes() { return (size_t)(4 + PB_MAX) * sizeof(uint32_t); }
 
-// Decides from a sample whether the partition pays: yes when fewer than a quarter of the sampled entries lie on a
-// diagonal that another row of their group of adjacent rows also holds (nothing for the traversal kernel to merge).
-// The sample is analysed on the device; what comes back is two counts per group.  dev: device-visible buffer of
-// partition_sample_bytes() that the kernel writes; host: where the host reads them after the synchronisation (the
-// same pinned block, or a host buffer that dev is copied to when dev is device memory).  Synchronises the stream.
-// (The feature call proper uses partition_decide_async below and saves this synchronisation.)
-// Diagonals that crowd into few buckets although adjacent rows share none (columns scattered inside a narrow band)
-// leave the last step to few blocks: slower than intended, about as slow as the atomics it replaces, and exact.
-mo_status partition_wanted(const mo_csr &a, uint32_t *dev, uint32_t *host, bool *wanted, hipStream_t s)
+// Enqueues the sample, whose last block leaves the decision in acc[3] (for the kernels enqueued behind it) and in
+// *flag_host (pinned, or nullptr).  acc: partition_sample_bytes() of device memory that is zero between calls (the
+// kernel leaves it so, acc[3] aside).
+mo_status partition_decide_async(const mo_csr &a, uint32_t *acc, uint32_t *flag_host, hipStream_t s)
 {
-    *wanted = false;
-    if (!partition_possible(a)) return MO_OK;
     const int64_t ndiag = a.m + a.n - 1;
-    hipLaunchKernelGGL(k_part_sample, dim3(SG), dim3(SR * SE), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, dev, (uint32_t *)nullptr,
-                       (uint32_t *)nullptr, (uint32_t *)nullptr);
+    hipLaunchKernelGGL(k_part_sample, dim3(SG), dim3(SR * SE), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, partition_buckets(a), acc,
+                       flag_host);
     MO_LAUNCH_CHECK();
-    if (host != dev) MO_HIP(hipMemcpyAsync(host, dev, partition_sample_bytes(), hipMemcpyDeviceToHost, s));
-    MO_HIP(hipStreamSynchronize(s));
-    uint64_t total = 0, repeated = 0;
-    for (int g = 0; g < SG; ++g) { total += host[2 * g]; repeated += host[2 * g + 1]; }
-    *wanted = sample_says_partition(total, repeated);
     return MO_OK;
 }
 
-// The same decision without the host: enqueues the sample, whose last block leaves the decision in *flag_dev (for the
-// kernels enqueued behind it) and in *flag_host (pinned; for the host after its next synchronisation).  acc: three
-// device words that are zero between calls.
-mo_status partition_decide_async(const mo_csr &a, uint32_t *acc, uint32_t *flag_dev, uint32_t *flag_host, hipStream_t s)
+// The same decision for a caller that waits for it.  acc as above.  Synchronises the stream.
+mo_status partition_wanted(const mo_csr &a, uint32_t *acc, bool *wanted, hipStream_t s)
 {
-    const int64_t ndiag = a.m + a.n - 1;
-    hipLaunchKernelGGL(k_part_sample, dim3(SG), dim3(SR * SE), 0, s, a.row_ptr, a.col_idx, a.m, a.nnz, ndiag, (uint32_t *)nullptr, acc,
-                       flag_dev, flag_host);
-    MO_LAUNCH_CHECK();
+    *wanted = false;
+    if (!partition_possible(a)) return MO_OK;
+    MO_TRY(partition_decide_async(a, acc, nullptr, s));
+    uint32_t flag = 0;
+    MO_HIP(hipMemcpyAsync(&flag, acc + 3, sizeof(flag), hipMemcpyDeviceToHost, s));
+    MO_HIP(hipStreamSynchronize(s));
+    *wanted = flag != 0u;
     return MO_OK;
 }
 

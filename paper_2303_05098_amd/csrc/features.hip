@@ -419,10 +419,11 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     const bool may_defer = a.nnz > VLONG_ROW;   // a row of more than VLONG_ROW entries can exist: it goes to k_long_rows
     bool by_partition = false;
     if (want_hist && partition_possible(a)) {   // scattered columns: nothing to merge, see feat_part.hip
-        uint32_t *sdev = (uint32_t *)scratch.get(partition_sample_bytes());
-        if (!sdev) return MO_E_ALLOC;
-        std::vector<uint32_t> shost(partition_sample_bytes() / sizeof(uint32_t));
-        MO_TRY(partition_wanted(a, sdev, shost.data(), &by_partition, s));
+        uint32_t *acc = (uint32_t *)scratch.get(partition_sample_bytes());
+        if (!acc) return MO_E_ALLOC;
+        hipLaunchKernelGGL(k_fill_u32, dim3(4), dim3(256), 0, s, acc, (int64_t)(partition_sample_bytes() / sizeof(uint32_t)), 0u);
+        MO_LAUNCH_CHECK();
+        MO_TRY(partition_wanted(a, acc, &by_partition, s));
     }
     if (want_hist && by_partition) {
         void *pbuf = scratch.get(partition_scratch_bytes(a));
@@ -536,6 +537,7 @@ __global__ __launch_bounds__(FB) void k_diag_count_clear(uint32_t *__restrict__ 
 }
 
 // results of one call, written by the kernels straight into pinned host memory (no copy command after them)
+constexpr size_t SAMPLE_WORDS = 1088;   // >= partition_sample_bytes() / 4, a multiple of 64: what follows starts on a 256-byte boundary
 constexpr size_t HOST_BYTES = (size_t)TRAV_BLOCKS * sizeof(RowPart) + (size_t)DIAG_BLOCKS * sizeof(DiagPart);
 
 struct FeatureCache {
@@ -575,8 +577,8 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
         if (g_fc.dev) dev_free(g_fc.dev, s);
         if (g_fc.pbuf && g_fc.device != dev_now) { dev_free(g_fc.pbuf, s); g_fc.pbuf = nullptr; g_fc.pbuf_cap = 0; }
         g_fc.hist_cap = ndiag + ndiag / 2;
-        // + the sample's counters and flag (64 words) + the list of very long rows
-        constexpr size_t TAIL = 64 + sizeof(LongRows) / sizeof(uint32_t);
+        // + the sample's words + the list of very long rows
+        const size_t TAIL = SAMPLE_WORDS + sizeof(LongRows) / sizeof(uint32_t);
         g_fc.hist_cap = (g_fc.hist_cap + 63) / 64 * 64;   // the list starts on a 256-byte boundary
         g_fc.dev = (uint32_t *)dev_alloc(((size_t)g_fc.hist_cap + TAIL) * sizeof(uint32_t), s);
         if (g_fc.dev) {
@@ -607,12 +609,12 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     // with the results, after the one synchronisation every call has.  A structured matrix pays one small kernel; a
     // scattered one pays two empty kernels and a second synchronisation on a call that is several times cheaper.
     const bool sampled = partition_possible(a);
-    uint32_t *acc = g_fc.dev + g_fc.hist_cap, *flag_dev = acc + 3;
+    uint32_t *acc = g_fc.dev + g_fc.hist_cap, *flag_dev = acc + 3;   // the sample's words: counts, decision, bucket counts
     uint32_t *flag_host = (uint32_t *)((char *)g_fc.host + HOST_BYTES);
     uint32_t *col_err = flag_host + 1;
     *flag_host = 0u;   // pinned memory, written before the launches that may set it
     *col_err = 0u;
-    if (sampled) MO_TRY(partition_decide_async(a, acc, flag_dev, flag_host, s));
+    if (sampled) MO_TRY(partition_decide_async(a, acc, flag_host, s));
     const bool was_clean = g_fc.clean;
     g_fc.clean = false;
     if (!was_clean) {
@@ -621,7 +623,7 @@ mo_status analyse_cached(const mo_csr &a, const mo_params &p, Analysis *out, hip
     }
     // Rows of more than VLONG_ROW entries are noted by the traversal, not walked; the counting kernel then skips itself,
     // and the host, which learns of them with the results, sends k_long_rows and the counting kernel after them.
-    LongRows *lr = a.nnz > VLONG_ROW ? (LongRows *)(g_fc.dev + g_fc.hist_cap + 64) : (LongRows *)nullptr;
+    LongRows *lr = a.nnz > VLONG_ROW ? (LongRows *)(g_fc.dev + g_fc.hist_cap + SAMPLE_WORDS) : (LongRows *)nullptr;
     uint32_t *long_host = flag_host + 2;
     *long_host = 0u;
     hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,

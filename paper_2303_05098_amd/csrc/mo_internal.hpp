@@ -175,8 +175,8 @@ bool partition_possible(const mo_csr &a);
 int partition_buckets(const mo_csr &a);
 size_t partition_sample_bytes();
 size_t partition_scratch_bytes(const mo_csr &a);
-mo_status partition_wanted(const mo_csr &a, uint32_t *dev, uint32_t *host, bool *wanted, hipStream_t s);
-mo_status partition_decide_async(const mo_csr &a, uint32_t *acc, uint32_t *flag_dev, uint32_t *flag_host, hipStream_t s);
+mo_status partition_wanted(const mo_csr &a, uint32_t *acc, bool *wanted, hipStream_t s);
+mo_status partition_decide_async(const mo_csr &a, uint32_t *acc, uint32_t *flag_host, hipStream_t s);
 mo_status partition_counts(const mo_csr &a, const mo_params &p, void *buf, uint32_t *hist, DiagPart *dpart, Counters *ctr, uint32_t *err,
                            hipStream_t s);
 // The no-allocation variant: integers and status into caller memory, asynchronous.
