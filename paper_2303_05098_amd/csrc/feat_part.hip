@@ -384,8 +384,8 @@ __host__ __device__ inline bool sample_says_partition(uint64_t total, uint64_t r
 // Block g samples the SR adjacent rows that start at row floor(g * (m - SR + 1) / SG), SE entries of each (entry
 // floor(e * len / SE) of the row, or every entry when the row holds at most SE), and leaves two counts in
 // out[2 g], out[2 g + 1]: the sampled entries, and those among them whose diagonal another row of the group also holds.
-// acc: device words, zero on entry: [0] sampled entries, [1] those on a diagonal that another row of their group also
-// holds, [2] blocks that are done, [3] the decision, [4 .. 4 + nb) sampled entries per bucket.  The block that finishes
+// acc: device words (8-byte aligned), zero on entry: [0, 1] one 64-bit word that packs the sampled entries, those on a
+// diagonal that another row of their group also holds, and the blocks that are done, [2] unused, [3] the decision, [4 .. 4 + nb) sampled entries per bucket.  The block that finishes
 // last turns the counts into the decision (1 = partition), stores it in acc[3] and, when given, in *flag_host (pinned),
 // and clears the rest for the next call: kernels launched behind this one can read the decision without the host in
 // between.
@@ -395,6 +395,8 @@ __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restri
     __shared__ int32_t s_key[SR * SE];
     __shared__ uint32_t s_tot[SR * SE / WAVE], s_rep[SR * SE / WAVE];
     __shared__ uint32_t s_last, s_max;
+    __shared__ unsigned long long s_sum;
+    static_assert(SG < 256 && SR * SE * SG < (1 << 20), "the packed counters of the sample");
     const int r = threadIdx.x / SE, e = threadIdx.x % SE;
     const int64_t span = m - SR + 1 > 0 ? m - SR + 1 : 1;
     const int64_t row = (int64_t)blockIdx.x * span / SG + r;
@@ -422,7 +424,10 @@ __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restri
     __syncthreads();
     for (int i = threadIdx.x; i < nb; i += SR * SE) {
         const uint32_t c = s_bkt[i];
-        if (c) atomicAdd(&acc[4 + i], c);
+        if (c) {
+            atomicAdd(&acc[4 + i], c);
+            __threadfence();   // out before the block reports itself done (few threads get here)
+        }
     }
     int hits = 0;   // every lane runs the whole loop: its LDS reads are independent and overlap
 #pragma unroll 16
@@ -430,15 +435,18 @@ __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restri
     const bool rep = key >= 0 && hits > 0;
     const uint32_t tot_w = (uint32_t)__popcll(ballot64(key >= 0)), rep_w = (uint32_t)__popcll(ballot64(rep));
     if (lane_id() == 0) { s_tot[threadIdx.x / WAVE] = tot_w; s_rep[threadIdx.x / WAVE] = rep_w; }
-    __threadfence();   // this thread's bucket count is out before the block reports itself done
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t t = 0, q = 0;
         for (int w = 0; w < SR * SE / WAVE; ++w) { t += s_tot[w]; q += s_rep[w]; }
-        atomicAdd(&acc[0], t);
-        atomicAdd(&acc[1], q);
-        __threadfence();
-        if (atomicAdd(&acc[2], 1u) == gridDim.x - 1) s_last = 1u;   // every other block's counts are in
+        // one atomic for the three: sampled entries in bits 0-19, repeated ones in bits 20-39, blocks done from bit 40 on
+        // (same-address atomics are served one after the other, and 128 blocks send theirs at about the same time)
+        unsigned long long *word = reinterpret_cast<unsigned long long *>(acc);
+        const unsigned long long old = atomicAdd(word, (unsigned long long)t | ((unsigned long long)q << 20) | (1ull << 40));
+        if ((old >> 40) == gridDim.x - 1) {   // every other block's counts are in
+            s_last = 1u;
+            s_sum = old + ((unsigned long long)t | ((unsigned long long)q << 20));
+        }
     }
     __syncthreads();
     if (!s_last) return;
@@ -450,11 +458,11 @@ __global__ __launch_bounds__(SR * SE) void k_part_sample(const int32_t *__restri
     atomicMax(&s_max, mx);
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t total = atomicExch(&acc[0], 0u), repeated = atomicExch(&acc[1], 0u);
+        const uint32_t total = (uint32_t)(s_sum & 0xfffffull), repeated = (uint32_t)((s_sum >> 20) & 0xfffffull);
         const uint32_t want = sample_says_partition(total, repeated, s_max) ? 1u : 0u;
         acc[3] = want;
         if (flag_host) *flag_host = want;
-        atomicExch(&acc[2], 0u);
+        atomicExch(reinterpret_cast<unsigned long long *>(acc), 0ull);
     }
 }
 
