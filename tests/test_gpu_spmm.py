@@ -67,6 +67,25 @@ def test_spmm_fp32_and_wide():
             h.free()
 
 
+@pytest.mark.parametrize("cname", ["c2s", "c4s", "dense", "band40", "band30s", "very_long_rows", "rect_wide", "rect_tall", "bulge"])
+def test_spmm_fp32_pieces(cname):
+    """fp32 panels are fetched as 16-byte pieces of four floats whatever the alignment of the rows of X: widths whose rows
+    start on 4-, 8- and 16-byte boundaries, on matrices that reach the window kernel, the direct DIA kernel with several
+    passes, the fused remainder, long rows and rectangular shapes."""
+    name, m, n, rp, ci, v = CASES[IDS.index(cname)]
+    a = upload(m, n, rp, ci, v, np.float32)
+    ti, tj, ta = ref.csr_to_triplets(rp, ci, np.asarray(v, dtype=np.float32).astype(np.float64))
+    for k in (5, 8, 12, 17):
+        X = make_X(n, k, 60 + k).astype(np.float32)
+        Y_ref, mag = ref.spmm(m, n, ti, tj, ta, X.astype(np.float64))
+        for fmt in range(6):
+            h = try_convert(a, fmt, PARAMS)
+            if h is None:
+                continue
+            check(gpu_spmm(h, X, m, np.float32), Y_ref, mag, TOL[np.float32], (name, mo.FORMAT_NAMES[fmt], k))
+            h.free()
+
+
 def test_spmm_k1_equals_spmv_layout():
     """k = 1 is SpMV with the same operands."""
     m, n, rp, ci, v = synth.config(2, 0.19)
