@@ -70,22 +70,7 @@ __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo64
         longmask &= longmask - 1;
         const int64_t r = row - lane + l;
         const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
-        constexpr int LU = 8;   // loads of LU steps are issued together: one wave walks the row
-        for (int q0 = rlo + lane; q0 < rhi; q0 += WAVE * LU) {
-            int32_t cc[LU];
-            T vv[LU];
-#pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * WAVE, qc = q < rhi ? q : rhi - 1;
-                cc[u] = col_idx[qc];
-                vv[u] = val[qc];
-            }
-#pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * WAVE;
-                if (q < rhi) f(r, (int64_t)q, (int64_t)(q - rlo), cc[u], vv[u], false);
-            }
-        }
+        for (int q = rlo + lane; q < rhi; q += WAVE) f(r, (int64_t)q, (int64_t)(q - rlo), col_idx[q], val[q], false);
     }
 }
 
@@ -248,26 +233,14 @@ __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row
         for (int d = lane; d < nd; d += WAVE) dval[(int64_t)d * ld + r] = (T)0;
         __threadfence();                         // the zeros are in place before other lanes store values of this row
         int rest = 0;
-        constexpr int LU = 8;   // loads of LU steps are issued together
-        for (int q0 = rlo + lane; q0 < rhi + lane; q0 += WAVE * LU) {   // uniform trip count: the ballots below need every lane
-            int32_t cc[LU];
-            T vv[LU];
-#pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * WAVE, qc = q < rhi ? q : rhi - 1;
-                cc[u] = col_idx[qc];
-                vv[u] = val[qc];
+        for (int q0 = rlo; q0 < rhi; q0 += WAVE) {
+            const int q = q0 + lane;
+            int k = 0;
+            if (q < rhi) {
+                k = find_slot(dia_off, nd, (int32_t)((int64_t)col_idx[q] - r));
+                if (k >= 0) dval[(int64_t)k * ld + r] = val[q];
             }
-#pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * WAVE;
-                int k = 0;
-                if (q < rhi) {
-                    k = find_slot(dia_off, nd, (int32_t)((int64_t)cc[u] - r));
-                    if (k >= 0) dval[(int64_t)k * ld + r] = vv[u];
-                }
-                rest += (int)__popcll(ballot64(k < 0));
-            }
+            rest += (int)__popcll(ballot64(k < 0));
         }
         if (rest_cnt && lane == 0) rest_cnt[r] = rest;
     }
@@ -480,28 +453,21 @@ __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row
         const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
         const int64_t rbase = __shfl(base, l, WAVE);
         int64_t run = 0;
-        constexpr int LU = 8;   // loads of LU steps are issued together
-        for (int q0 = rlo + lane; q0 < rhi + lane; q0 += WAVE * LU) {   // uniform trip count: the ballots below need every lane
-            int32_t cc[LU];
-            T vv[LU];
-#pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * WAVE, qc = q < rhi ? q : rhi - 1;
-                cc[u] = col_idx[qc];
-                vv[u] = val[qc];
+        for (int q0 = rlo; q0 < rhi; q0 += WAVE) {
+            const int q = q0 + lane;
+            bool rest = false;
+            int32_t c = 0;
+            if (q < rhi) {
+                c = col_idx[q];
+                rest = find_slot(dia_off, nd, (int32_t)((int64_t)c - r)) < 0;
             }
-#pragma unroll
-            for (int u = 0; u < LU; ++u) {
-                const int q = q0 + u * WAVE;
-                const bool rest = q < rhi && find_slot(dia_off, nd, (int32_t)((int64_t)cc[u] - r)) < 0;
-                const uint64_t mask = ballot64(rest);
-                if (rest) {
-                    const int64_t pos = rbase + run + __popcll(mask & below);
-                    rcol[pos] = cc[u];
-                    rval[pos] = vv[u];
-                }
-                run += __popcll(mask);
+            const uint64_t mask = ballot64(rest);
+            if (rest) {
+                const int64_t pos = rbase + run + __popcll(mask & below);
+                rcol[pos] = c;
+                rval[pos] = val[q];
             }
+            run += __popcll(mask);
         }
     }
 }
@@ -742,37 +708,23 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         hipLaunchKernelGGL(k_surplus, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.m, (int64_t)0, rest_cnt);
         MO_LAUNCH_CHECK();
     }
-    // launch plan for the LDS-staged SpMV kernel, from the offsets the host already holds
+    // launch plans for the LDS-staged kernels, from the offsets the host already holds; the four arrays go to the device
+    // as one block with one copy
     if (nd > 0) {
         const std::vector<int32_t> hoff = b.keep.back();
-        // 512 threads per block, one row per lane in fp64 and two in fp32 (8 bytes per lane and load either way):
+        // SpMV: 512 threads per block, one row per lane in fp64 and two in fp32 (8 bytes per lane and load either way):
         // measured best of {256, 512} x {1, 2} on the stencil and band configurations.  Matrices of fewer than 2^17
         // rows get 256-thread blocks: twice as many, shorter blocks on a chip they cannot fill anyway.
         const int block = a.m < 131072 ? 256 : 512, rows = sizeof(T) == 4 ? 2 : 1;
-        std::vector<int32_t> xpos, cl;
-        int64_t elems = 0;
-        if (plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems)) {
-            h->dia_xpos = (int32_t *)b.own(xpos.size() * 4);
-            h->dia_clusters = (int32_t *)b.own(cl.size() * 4);
-            if (b.failed) return MO_E_ALLOC;
-            const size_t nx = xpos.size(), ncl = cl.size();
-            b.keep.push_back(std::move(xpos));   // the uploads complete by the conversion's final synchronisation
-            b.keep.push_back(std::move(cl));
-            const std::vector<int32_t> &kx = b.keep[b.keep.size() - 2], &kc = b.keep.back();
-            MO_HIP(hipMemcpyAsync(h->dia_xpos, kx.data(), nx * 4, hipMemcpyHostToDevice, s));
-            MO_HIP(hipMemcpyAsync(h->dia_clusters, kc.data(), ncl * 4, hipMemcpyHostToDevice, s));
-            h->dia_block = block;
-            h->dia_rows = rows;
-            h->dia_ncl = (int32_t)(ncl / 3);
-            h->dia_lds_elems = elems;
-        }
-        // the same for the multi-vector product: blocks of SPMM_ROWS rows; kept when a 16-byte piece per row of X fits
-        std::vector<int32_t> mxpos, mcl;
-        int64_t melems = 0;
-        if (plan_dia_clusters(hoff, SPMM_ROWS, SPMM_WIN_BYTES / 16, &mxpos, &mcl, &melems)) {
+        std::vector<int32_t> xpos, cl, mxpos, mcl, mmap;
+        int64_t elems = 0, melems = 0;
+        const bool have_v = plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems);
+        // the multi-vector product: blocks of SPMM_ROWS rows; kept when a 16-byte piece per row of X fits
+        const bool have_m = plan_dia_clusters(hoff, SPMM_ROWS, SPMM_WIN_BYTES / 16, &mxpos, &mcl, &melems);
+        if (have_m) {
             // Every window is at least SPMM_ROWS long, so a run of SPMM_ROWS staged rows lies in at most two windows.
             const int64_t nrun = (melems + SPMM_ROWS - 1) / SPMM_ROWS;
-            std::vector<int32_t> mmap((size_t)nrun * 3);
+            mmap.resize((size_t)nrun * 3);
             for (int64_t u = 0; u < nrun; ++u) {
                 size_t q = 0;   // window that holds staged row u * SPMM_ROWS
                 while (q + 5 < mcl.size() && (int64_t)mcl[q + 5] <= u * SPMM_ROWS) q += 3;
@@ -781,16 +733,31 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
                 mmap[3 * u + 1] = mcl[q] - mcl[q + 2];
                 mmap[3 * u + 2] = more ? mcl[q + 3] - mcl[q + 5] : 0;
             }
-            h->mm_xpos = (int32_t *)b.own(mxpos.size() * 4);
-            h->mm_map = (int32_t *)b.own(mmap.size() * 4);
+        }
+        if (have_v || have_m) {
+            b.keep.emplace_back();
+            std::vector<int32_t> &all = b.keep.back();   // alive until the conversion's final synchronisation
+            const size_t o_xpos = 0, o_cl = o_xpos + (have_v ? xpos.size() : 0), o_mx = o_cl + (have_v ? cl.size() : 0),
+                         o_map = o_mx + (have_m ? mxpos.size() : 0), total = o_map + (have_m ? mmap.size() : 0);
+            all.reserve(total);
+            if (have_v) { all.insert(all.end(), xpos.begin(), xpos.end()); all.insert(all.end(), cl.begin(), cl.end()); }
+            if (have_m) { all.insert(all.end(), mxpos.begin(), mxpos.end()); all.insert(all.end(), mmap.begin(), mmap.end()); }
+            int32_t *dev = (int32_t *)b.own(total * 4);
             if (b.failed) return MO_E_ALLOC;
-            const size_t nx = mxpos.size(), ns = mmap.size();
-            b.keep.push_back(std::move(mxpos));
-            b.keep.push_back(std::move(mmap));
-            const std::vector<int32_t> &kx = b.keep[b.keep.size() - 2], &ks = b.keep.back();
-            MO_HIP(hipMemcpyAsync(h->mm_xpos, kx.data(), nx * 4, hipMemcpyHostToDevice, s));
-            MO_HIP(hipMemcpyAsync(h->mm_map, ks.data(), ns * 4, hipMemcpyHostToDevice, s));
-            h->mm_lds_elems = melems;
+            MO_HIP(hipMemcpyAsync(dev, all.data(), total * 4, hipMemcpyHostToDevice, s));
+            if (have_v) {
+                h->dia_xpos = dev + o_xpos;
+                h->dia_clusters = dev + o_cl;
+                h->dia_block = block;
+                h->dia_rows = rows;
+                h->dia_ncl = (int32_t)(cl.size() / 3);
+                h->dia_lds_elems = elems;
+            }
+            if (have_m) {
+                h->mm_xpos = dev + o_mx;
+                h->mm_map = dev + o_map;
+                h->mm_lds_elems = melems;
+            }
         }
     }
     return MO_OK;

@@ -46,12 +46,16 @@ static __global__ void k_fill_u32(uint32_t *p, int64_t n, uint32_t v)
     for (; i < n; i += stride) p[i] = v;
 }
 
-// p[0, n) = 0 and the counter block reset, in one launch.
-static __global__ void k_zero_and_reset(uint32_t *p, int64_t n, Counters *c)
+// p[0, n) = 0, q[0, nq) = 0 (q may be nullptr) and the counter block reset (the counters and the rest of the 256 bytes
+// they own, which callers use for flags that come back with them), in one launch of at least 64 threads.
+static __global__ void k_zero_and_reset(uint32_t *p, int64_t n, Counters *c, uint32_t *q, int nq)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     if (i == 0) { c->max_row = 0ull; c->min_row = ~0ull; c->sum_sq = 0ull; c->n_diag = 0ull; c->n_true = 0ull; c->err = 0u; c->pad = 0u; }
+    if (i >= (int64_t)(sizeof(Counters) / 4) && i < 64) reinterpret_cast<uint32_t *>(c)[i] = 0u;   // the rest of the counters' 256 bytes
+    if (q)
+        for (int64_t j = i; j < nq; j += stride) q[j] = 0u;
     for (; i < n; i += stride) p[i] = 0u;
 }
 
@@ -84,9 +88,13 @@ __device__ __forceinline__ void count_key(int key, uint32_t n, int *ht_key, uint
 }
 
 // N_D = diagonals with at least one entry; N_TD = non-empty diagonals with cnt * td_den >= min(m, n) * td_num.
+// skip, skip2 (or nullptr): device words that a kernel ahead in the stream may have set; when either is non-zero this
+// kernel does nothing (its caller then counts in another way, or once more later).
 static __global__ __launch_bounds__(FB) void k_diag_count(const uint32_t *__restrict__ hist, int64_t nd, unsigned long long thr_rhs,
-                                                    unsigned long long td_den, Counters *ctr)
+                                                    unsigned long long td_den, Counters *ctr, const uint32_t *__restrict__ skip,
+                                                    const uint32_t *__restrict__ skip2)
 {
+    if ((skip && *skip) || (skip2 && *skip2)) return;
     unsigned long long c_nd = 0, c_td = 0;
     const int64_t stride = (int64_t)gridDim.x * FB;
     for (int64_t i = (int64_t)blockIdx.x * FB + threadIdx.x; i < nd; i += stride) {

@@ -9,6 +9,7 @@
 #include "feat_common.hpp"
 #include "mo_internal.hpp"
 
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -71,6 +72,7 @@ __device__ __forceinline__ bool heavy_find_add(int key, const int *hv_key, uint3
 }
 constexpr int TSTAGE = 16;        // column loads a lane has in flight while a chunk is staged: two round trips to memory per
                                   // full chunk (8: four round trips, with the few waves this kernel runs each one shows)
+constexpr size_t SAMPLE_WORDS = 1088;   // >= partition_sample_bytes() / 4, a multiple of 64: what follows starts on a 256-byte boundary
 constexpr int TRAV_BLOCKS = 512;  // at most this many blocks: every block ends with one atomic per distinct
                                   // diagonal it met, and same-address atomics are served one after the other
 
@@ -259,26 +261,15 @@ __global__ __launch_bounds__(TB) void k_traverse(const int32_t *__restrict__ row
             longmask &= longmask - 1;
             const int64_t r = base + (threadIdx.x - lane) + l;
             const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
-            constexpr int LU = 8;   // loads of LU steps are issued together: one wave walks the row, and a row may hold millions
-            for (int q0 = rlo + lane; q0 < rhi; q0 += WAVE * LU) {
-                int64_t c[LU], cp[LU];
-#pragma unroll
-                for (int u = 0; u < LU; ++u) {
-                    const int q = q0 + u * WAVE, qc = q < rhi ? q : rhi - 1;   // clamped into the row: unconditional loads
-                    c[u] = col_idx[qc];
-                    cp[u] = qc > rlo ? (int64_t)col_idx[qc - 1] : (int64_t)-1;
-                }
-#pragma unroll
-                for (int u = 0; u < LU; ++u) {
-                    if (q0 + u * WAVE >= rhi) continue;
-                    const bool ok = c[u] >= 0 && c[u] < n && c[u] > cp[u];
-                    if (!ok) err = true;
-                    else if (DO_HIST) {
-                        // through the block's tables like every other entry: the rows of a wide band hold the same
-                        // diagonals, and one atomic per entry on a few hundred addresses took 50 - 100 CSR SpMVs
-                        const int key = (int)(c[u] - r + (m - 1));
-                        if (!heavy_find_add(key, hv_key, hv_cnt)) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
-                    }
+            for (int q = rlo + lane; q < rhi; q += WAVE) {
+                const int64_t c = col_idx[q], cp = q > rlo ? (int64_t)col_idx[q - 1] : (int64_t)-1;
+                const bool ok = c >= 0 && c < n && c > cp;
+                if (!ok) err = true;
+                else if (DO_HIST) {
+                    // through the block's tables like every other entry: the rows of a wide band hold the same diagonals,
+                    // and one atomic per entry on a few hundred addresses took 50 - 100 CSR SpMVs
+                    const int key = (int)(c - r + (m - 1));
+                    if (!heavy_find_add(key, hv_key, hv_cnt)) count_key(key, 1u, ht_key, ht_cnt, &ht_full, hist);
                 }
             }
         }
@@ -406,72 +397,87 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     rows_per_block = ((rows_per_block + TB - 1) / TB) * TB;
     const int64_t row_blocks = (a.m + rows_per_block - 1) / rows_per_block;   // 1 .. TRAV_BLOCKS
     const int64_t ndiag = a.m + a.n - 1;
-    // one allocation: [diagonal counters | row partials | list of very long rows | histogram]
+    // one allocation: [diagonal counters | row partials | words of the partition's sample | list of very long rows | histogram]
     static_assert(sizeof(LongRows) == 4096, "the list of very long rows owns 4096 bytes");
-    const size_t head = 256 + sizeof(LongRows) + (size_t)TRAV_BLOCKS * sizeof(RowPart);
     static_assert(sizeof(Counters) <= 256, "the counters own the first 256 bytes");
+    const size_t off_acc = 256 + (size_t)TRAV_BLOCKS * sizeof(RowPart);
+    const size_t off_lr = off_acc + SAMPLE_WORDS * sizeof(uint32_t);
+    const size_t head = off_lr + sizeof(LongRows);
     char *base = (char *)scratch.get(head + (want_hist ? (size_t)ndiag * sizeof(uint32_t) : 0));
     if (!base) return MO_E_ALLOC;
     Counters *ctr = (Counters *)base;
     RowPart *part = (RowPart *)(base + 256);
-    LongRows *lr = (LongRows *)(base + 256 + (size_t)TRAV_BLOCKS * sizeof(RowPart));
+    uint32_t *acc = (uint32_t *)(base + off_acc);
+    LongRows *lr = (LongRows *)(base + off_lr);
     uint32_t *hist = want_hist ? (uint32_t *)(base + head) : nullptr;
-    const bool may_defer = a.nnz > VLONG_ROW;   // a row of more than VLONG_ROW entries can exist: it goes to k_long_rows
-    bool by_partition = false;
-    if (want_hist && partition_possible(a)) {   // scattered columns: nothing to merge, see feat_part.hip
-        uint32_t *acc = (uint32_t *)scratch.get(partition_sample_bytes());
-        if (!acc) return MO_E_ALLOC;
-        hipLaunchKernelGGL(k_fill_u32, dim3(4), dim3(256), 0, s, acc, (int64_t)(partition_sample_bytes() / sizeof(uint32_t)), 0u);
+    // The usual case costs no more launches than it needs: the kernels are enqueued as if the matrix were structured and
+    // held no very long rows; what a kernel ahead in the stream finds out (the partition's sample, the traversal's list)
+    // makes the kernels behind it return at once, and the host, which reads those findings with the results, then sends
+    // what is missing.
+    const bool may_defer = a.nnz > VLONG_ROW;             // a row of more than VLONG_ROW entries can exist
+    const bool sampled = want_hist && partition_possible(a);
+    const int nzero = (int)SAMPLE_WORDS + 2;              // the sample's words and the head of the list (count, done)
+    const int64_t mn = a.m < a.n ? a.m : a.n;
+    const unsigned long long thr = (unsigned long long)mn * (unsigned long long)p.td_num;
+    // two flags in the spare words of the counters' 256 bytes, so that they come back in the same copy
+    uint32_t *long_flag = (uint32_t *)(base + 64), *part_flag_dev = (uint32_t *)(base + 68);
+    if (want_hist) {
+        hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr, acc, nzero);
         MO_LAUNCH_CHECK();
-        MO_TRY(partition_wanted(a, acc, &by_partition, s));
-    }
-    if (want_hist && by_partition) {
-        void *pbuf = scratch.get(partition_scratch_bytes(a));
-        if (!pbuf) return MO_E_ALLOC;
-        hipLaunchKernelGGL(k_init_counters, dim3(1), dim3(64), 0, s, ctr);
-        MO_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_row_stats, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.m, a.nnz, rows_per_block, part);
-        MO_LAUNCH_CHECK();
-        MO_TRY(partition_counts(a, p, pbuf, hist, nullptr, ctr, &ctr->err, s));
-    } else if (want_hist) {
-        hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag, FB * 4, 4096)), dim3(FB), 0, s, hist, ndiag, ctr);
-        MO_LAUNCH_CHECK();
-        if (may_defer) {
-            hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, (uint32_t *)lr, (int64_t)2, 0u);
-            MO_LAUNCH_CHECK();
-        }
+        if (sampled) MO_TRY(partition_decide_async(a, acc, part_flag_dev, s));
         hipLaunchKernelGGL(k_traverse<true>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part, (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr, (uint32_t *)nullptr);
+                           rows_per_block, hist, part, sampled ? acc + 3 : (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr,
+                           long_flag);
         MO_LAUNCH_CHECK();
-        if (may_defer) {
-            hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part, 1);
-            MO_LAUNCH_CHECK();
-        }
-        const int64_t mn = a.m < a.n ? a.m : a.n;
-        hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
-                           (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
+        hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag, thr, (unsigned long long)p.td_den, ctr,
+                           sampled ? acc + 3 : (const uint32_t *)nullptr, may_defer ? &lr->count : (const uint32_t *)nullptr);
         MO_LAUNCH_CHECK();
     } else {
-        if (may_defer) {
-            hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, s, (uint32_t *)lr, (int64_t)2, 0u);
+        if (may_defer) {   // the counters' block (for its flags) and the head of the list
+            hipLaunchKernelGGL(k_zero_and_reset, dim3(1), dim3(64), 0, s, (uint32_t *)nullptr, (int64_t)0, ctr, (uint32_t *)lr, 2);
             MO_LAUNCH_CHECK();
         }
         hipLaunchKernelGGL(k_traverse<false>, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz,
-                           rows_per_block, hist, part, (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr, (uint32_t *)nullptr);
+                           rows_per_block, hist, part, (const uint32_t *)nullptr, may_defer ? lr : (LongRows *)nullptr, long_flag);
         MO_LAUNCH_CHECK();
-        if (may_defer) {
-            hipLaunchKernelGGL(k_long_rows<false>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part, 1);
-            MO_LAUNCH_CHECK();
-        }
     }
     struct { Counters c; char pad[256 - sizeof(Counters)]; RowPart part[TRAV_BLOCKS]; } h;
     static_assert(sizeof(h) == 256 + TRAV_BLOCKS * sizeof(RowPart), "host mirror of the head of the scratch block");
     const size_t bytes = 256 + (size_t)row_blocks * sizeof(RowPart);
     MO_HIP(hipMemcpyAsync(&h, base, bytes, hipMemcpyDeviceToHost, s));
-    uint32_t n_long = 0;
-    const bool listed = may_defer && !by_partition;   // the traversal ran with the list
-    if (listed) MO_HIP(hipMemcpyAsync(&n_long, &lr->count, sizeof(n_long), hipMemcpyDeviceToHost, s));
     MO_HIP(hipStreamSynchronize(s));
+    static_assert(sizeof(Counters) <= 64, "the flags live at bytes 64 and 68 of the counters' block");
+    uint32_t flags[2];
+    memcpy(flags, h.pad + (64 - sizeof(Counters)), sizeof(flags));
+    const bool by_partition = sampled && flags[1] != 0u;
+    uint32_t n_long = 0;
+    if (may_defer && flags[0] != 0u) {   // rare: how many rows the list holds
+        MO_HIP(hipMemcpyAsync(&n_long, &lr->count, sizeof(n_long), hipMemcpyDeviceToHost, s));
+        MO_HIP(hipStreamSynchronize(s));
+    }
+    if (by_partition) {           // the traversal and the counting kernel returned at once; the list is empty
+        void *pbuf = scratch.get(partition_scratch_bytes(a));
+        if (!pbuf) return MO_E_ALLOC;
+        hipLaunchKernelGGL(k_row_stats, dim3((unsigned)row_blocks), dim3(TB), 0, s, a.row_ptr, a.m, a.nnz, rows_per_block, part);
+        MO_LAUNCH_CHECK();
+        MO_TRY(partition_counts(a, p, pbuf, hist, nullptr, ctr, &ctr->err, s));
+        n_long = 0;
+    } else if (n_long > 0) {      // the traversal left rows to k_long_rows, and the counting kernel returned at once
+        if (want_hist) {
+            hipLaunchKernelGGL(k_long_rows<true>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part, 1);
+            MO_LAUNCH_CHECK();
+            hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag, thr, (unsigned long long)p.td_den,
+                               ctr, (const uint32_t *)nullptr, (const uint32_t *)nullptr);
+            MO_LAUNCH_CHECK();
+        } else {
+            hipLaunchKernelGGL(k_long_rows<false>, dim3(LR_BLOCKS), dim3(LB), 0, s, a.row_ptr, a.col_idx, a.m, a.n, a.nnz, hist, lr, part, 1);
+            MO_LAUNCH_CHECK();
+        }
+    }
+    if (by_partition || n_long > 0) {
+        MO_HIP(hipMemcpyAsync(&h, base, bytes, hipMemcpyDeviceToHost, s));
+        MO_HIP(hipStreamSynchronize(s));
+    }
     unsigned long long mx = 0ull, mnr = ~0ull, sq = 0ull, err = 0ull;
     for (int64_t b = 0; b < row_blocks; ++b) {
         mx = h.part[b].max_row > mx ? h.part[b].max_row : mx;
@@ -487,8 +493,8 @@ mo_status analyse(const mo_csr &a, const mo_params &p, bool want_hist, Analysis 
     out->n_diag = want_hist ? (int64_t)h.c.n_diag : 0;
     out->n_true = want_hist ? (int64_t)h.c.n_true : 0;
     out->hist = hist;
-    out->long_rows = listed ? lr : nullptr;
-    out->n_long = (listed && n_long <= (uint32_t)LR_CAP) ? (int)n_long : 0;
+    out->long_rows = n_long > 0 ? lr : nullptr;
+    out->n_long = (n_long > 0 && n_long <= (uint32_t)LR_CAP) ? (int)n_long : 0;
     return MO_OK;
 }
 
@@ -537,7 +543,6 @@ __global__ __launch_bounds__(FB) void k_diag_count_clear(uint32_t *__restrict__ 
 }
 
 // results of one call, written by the kernels straight into pinned host memory (no copy command after them)
-constexpr size_t SAMPLE_WORDS = 1088;   // >= partition_sample_bytes() / 4, a multiple of 64: what follows starts on a 256-byte boundary
 constexpr size_t HOST_BYTES = (size_t)TRAV_BLOCKS * sizeof(RowPart) + (size_t)DIAG_BLOCKS * sizeof(DiagPart);
 
 struct FeatureCache {

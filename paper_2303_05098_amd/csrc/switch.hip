@@ -412,7 +412,7 @@ static mo_status features_any(const mo_matrix &a, const mo_params &p, Counters *
     uint32_t *hist = (uint32_t *)(base + 512);
     int32_t *len = (int32_t *)(base + 512 + (size_t)ndiag * 4);
     // the total and the histogram are contiguous: one launch zeroes both and resets the counters
-    hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag + 64, FB * 4, 4096)), dim3(FB), 0, s, (uint32_t *)total, ndiag + 64, ctr);
+    hipLaunchKernelGGL(k_zero_and_reset, dim3(grid_for(ndiag + 64, FB * 4, 4096)), dim3(FB), 0, s, (uint32_t *)total, ndiag + 64, ctr, (uint32_t *)nullptr, 0);
     MO_LAUNCH_CHECK();
     const unsigned rb = (unsigned)((a.m + FB - 1) / FB);
     hipLaunchKernelGGL(k_len_any<T>, dim3(rb), dim3(FB), 0, s, v, len);
@@ -434,7 +434,7 @@ static mo_status features_any(const mo_matrix &a, const mo_params &p, Counters *
     }
     const int64_t mn = a.m < a.n ? a.m : a.n;
     hipLaunchKernelGGL(k_diag_count, dim3(grid_for(ndiag, FB * 4, 512)), dim3(FB), 0, s, hist, ndiag,
-                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr);
+                       (unsigned long long)mn * (unsigned long long)p.td_num, (unsigned long long)p.td_den, ctr, (const uint32_t *)nullptr, (const uint32_t *)nullptr);
     MO_LAUNCH_CHECK();
     struct { Counters c; char pad[256 - sizeof(Counters)]; unsigned long long total; } host;   // mirrors the head of the block
     static_assert(sizeof(host) == 264, "counters in the first 256 bytes, the total right after");
