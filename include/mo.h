@@ -117,9 +117,11 @@ void mo_default_params(mo_params *out);
  * The integer counts come from device kernels over the CSR arrays; the four derived doubles are formed on the
  * host from those integers (std = sqrt((M*sum_sq_row - NNZ^2) / M^2), correctly rounded operations only).
  * out: host array of 10 doubles.  ints_opt: optional host struct.  Synchronises `stream`.  This is the call a deployed
- * tuner pays per matrix, so it keeps its device scratch (about 6*(m+n) bytes, grown on demand through the installed
- * allocator) and a small pinned host block between calls; mo_set_allocator releases the device block.  Calls from
- * several threads are safe: one of them uses the kept block, the others allocate and free per call. */
+ * tuner pays per matrix, so it keeps its device scratch (about 6*(m+n) bytes, and about 2*nnz more once a matrix of
+ * at least 2^21 entries with scattered columns has been seen: its diagonals are counted by partition instead of by
+ * atomics; grown on demand through the installed allocator) and a small pinned host block between calls;
+ * mo_set_allocator releases the device blocks.  Calls from several threads are safe: one of them uses the kept
+ * blocks, the others allocate and free per call. */
 mo_status mo_features(const mo_csr *a, const mo_params *params, double out[MO_NUM_FEATURES],
                       mo_feature_ints *ints_opt, void *stream);
 
@@ -130,7 +132,8 @@ mo_status mo_features_finalize(const mo_feature_ints *ints, double out[MO_NUM_FE
 /* mo_features for callers that cannot allocate or wait: code under HIP stream capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same kernels and same integers as mo_features, but the diagonal histogram and the per-block
  * partial results live in a device array inside the library (one copy per GPU, about 16 MiB, held until the process
- * ends) and the call neither allocates, frees nor synchronises: it enqueues four kernels on `stream` and returns.
+ * ends) and the call neither allocates, frees nor synchronises: it enqueues four kernels (five for matrices of more
+ * than 8192 entries, which may hold rows too long for one wavefront) on `stream` and returns.
  *   out_dev : DEVICE-accessible memory owned by the caller (device memory or pinned host memory); when the enqueued
  *             work has finished it holds the integer statistics and status = MO_OK or MO_E_CSR_INVALID (then the
  *             integers mean nothing).  mo_features_finalize turns ints into the ten doubles.
