@@ -192,7 +192,7 @@ template <typename T>
 __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   const T *__restrict__ val, int64_t m,
                                                   const int32_t *__restrict__ dia_off, int nd, int64_t ld, T *__restrict__ dval,
-                                                  int32_t *__restrict__ rest_cnt, int rw)
+                                                  int32_t *__restrict__ rest_cnt, int rw, int skip_len)
 {
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
     __shared__ T s_val[(CB / WAVE) * WCAP];
@@ -231,6 +231,10 @@ __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row
         const int64_t r = row - lane + l;
         const int rlo = __builtin_amdgcn_readlane(lo, l), rhi = __builtin_amdgcn_readlane(hi, l);
         for (int d = lane; d < nd; d += WAVE) dval[(int64_t)d * ld + r] = (T)0;
+        if (skip_len > 0 && rhi - rlo > skip_len) {   // its entries are left to k_fill_dia_long, launched behind this kernel
+            if (rest_cnt && lane == 0) rest_cnt[r] = 0;
+            continue;
+        }
         __threadfence();                         // the zeros are in place before other lanes store values of this row
         int rest = 0;
         for (int q0 = rlo; q0 < rhi; q0 += WAVE) {
@@ -243,6 +247,165 @@ __global__ __launch_bounds__(CB) void k_fill_dia(const int32_t *__restrict__ row
             rest += (int)__popcll(ballot64(k < 0));
         }
         if (rest_cnt && lane == 0) rest_cnt[r] = rest;
+    }
+}
+
+// ------------------------------------------------------------------ rows too long for one wave (DIA / HDC)
+// The rows that k_fill_dia and k_hdc_rest skipped (longer than VLONG_ROW and not merged lane per row; listed by the
+// analysis), entry-parallel over the whole grid in chunks of RL_CHUNK entries, RL_U consecutive entries per thread.
+constexpr int RL_B = 256, RL_U = 4, RL_CHUNK = RL_B * RL_U, RL_BLOCKS = 512;
+
+__device__ __forceinline__ int rl_block_sum(int v, int *s_w)
+{
+    v = wave_sum(v);
+    if (lane_id() == 0) s_w[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    int t = 0;
+    for (int w = 0; w < RL_B / WAVE; ++w) t += s_w[w];
+    __syncthreads();
+    return t;
+}
+
+// s_base[li] = chunks of the listed rows before row li (s_base[nrows] = all chunks); rows that the main kernels did
+// not skip (merged lane per row: at most two entries per kept diagonal) count no chunks.
+__device__ __forceinline__ void rl_chunk_bases(const LongRows *__restrict__ lr, int nrows, const int32_t *__restrict__ row_ptr, int64_t m,
+                                               int nd, int *s_base)
+{
+    for (int li = threadIdx.x; li < nrows; li += RL_B) {
+        const int64_t r = lr->rows[li];
+        int64_t len = (r >= 0 && r < m) ? (int64_t)row_ptr[r + 1] - row_ptr[r] : 0;
+        if (len <= 2 * (int64_t)nd || len <= VLONG_ROW) len = 0;
+        s_base[li + 1] = (int)((len + RL_CHUNK - 1) / RL_CHUNK);
+    }
+    if (threadIdx.x == 0) s_base[0] = 0;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        for (int li = 0; li < nrows; ++li) s_base[li + 1] += s_base[li];
+    __syncthreads();
+}
+
+// Row of the list that chunk g belongs to: the largest li with s_base[li] <= g.
+__device__ __forceinline__ int rl_row_of_chunk(const int *s_base, int nrows, int g)
+{
+    int lo = 0, hi = nrows - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (s_base[mid] <= g) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// DIA part: every entry finds its slot (the main kernel has zeroed the row's slots); entries off the kept diagonals
+// are counted into rest_cnt[row] (HDC; set to 0 by the main kernel).
+template <typename T>
+__global__ __launch_bounds__(RL_B) void k_fill_dia_long(const LongRows *__restrict__ lr, int nrows, const int32_t *__restrict__ row_ptr,
+                                                        const int32_t *__restrict__ col_idx, const T *__restrict__ val, int64_t m,
+                                                        const int32_t *__restrict__ dia_off, int nd, int64_t ld, T *__restrict__ dval,
+                                                        int32_t *__restrict__ rest_cnt)
+{
+    __shared__ int s_base[LR_CAP + 2];
+    __shared__ int s_w[RL_B / WAVE];
+    rl_chunk_bases(lr, nrows, row_ptr, m, nd, s_base);
+    const int total = s_base[nrows];
+    for (int g = blockIdx.x; g < total; g += gridDim.x) {   // uniform across the block
+        const int li = rl_row_of_chunk(s_base, nrows, g);
+        const int64_t r = lr->rows[li];
+        const int64_t lo = row_ptr[r], hi = row_ptr[r + 1];
+        const int64_t q0 = lo + (int64_t)(g - s_base[li]) * RL_CHUNK + (int64_t)threadIdx.x * RL_U;
+        int rest = 0;
+#pragma unroll
+        for (int u = 0; u < RL_U; ++u) {
+            const int64_t q = q0 + u;
+            if (q < hi) {
+                const int k = find_slot(dia_off, nd, (int32_t)((int64_t)col_idx[q] - r));
+                if (k >= 0) dval[(int64_t)k * ld + r] = val[q];
+                else ++rest;
+            }
+        }
+        if (rest_cnt) {   // uniform
+            const int t = rl_block_sum(rest, s_w);
+            if (threadIdx.x == 0 && t) atomicAdd(&rest_cnt[r], t);
+        }
+    }
+}
+
+// CSR remainder of HDC, first pass: chunk_cnt[g] = entries of chunk g that lie off the kept diagonals.
+__global__ __launch_bounds__(RL_B) void k_hdc_rest_long_count(const LongRows *__restrict__ lr, int nrows, const int32_t *__restrict__ row_ptr,
+                                                              const int32_t *__restrict__ col_idx, int64_t m,
+                                                              const int32_t *__restrict__ dia_off, int nd, int32_t *__restrict__ chunk_cnt)
+{
+    __shared__ int s_base[LR_CAP + 2];
+    __shared__ int s_w[RL_B / WAVE];
+    rl_chunk_bases(lr, nrows, row_ptr, m, nd, s_base);
+    const int total = s_base[nrows];
+    for (int g = blockIdx.x; g < total; g += gridDim.x) {
+        const int li = rl_row_of_chunk(s_base, nrows, g);
+        const int64_t r = lr->rows[li];
+        const int64_t lo = row_ptr[r], hi = row_ptr[r + 1];
+        const int64_t q0 = lo + (int64_t)(g - s_base[li]) * RL_CHUNK + (int64_t)threadIdx.x * RL_U;
+        int rest = 0;
+#pragma unroll
+        for (int u = 0; u < RL_U; ++u) {
+            const int64_t q = q0 + u;
+            if (q < hi && find_slot(dia_off, nd, (int32_t)((int64_t)col_idx[q] - r)) < 0) ++rest;
+        }
+        const int t = rl_block_sum(rest, s_w);
+        if (threadIdx.x == 0) chunk_cnt[g] = t;
+    }
+}
+
+// Second pass: the remainder entries of chunk g go to rest_ptr[row] + (remainder entries in the row's chunks before
+// g) + (those before them inside the chunk), in the order of the row.
+template <typename T>
+__global__ __launch_bounds__(RL_B) void k_hdc_rest_long_write(const LongRows *__restrict__ lr, int nrows, const int32_t *__restrict__ row_ptr,
+                                                              const int32_t *__restrict__ col_idx, const T *__restrict__ val, int64_t m,
+                                                              const int32_t *__restrict__ dia_off, int nd,
+                                                              const int32_t *__restrict__ chunk_cnt, const int32_t *__restrict__ rest_ptr,
+                                                              int32_t *__restrict__ rcol, T *__restrict__ rval)
+{
+    __shared__ int s_base[LR_CAP + 2];
+    __shared__ int s_w[RL_B / WAVE];
+    __shared__ int s_scan[RL_B / WAVE];
+    rl_chunk_bases(lr, nrows, row_ptr, m, nd, s_base);
+    const int total = s_base[nrows];
+    for (int g = blockIdx.x; g < total; g += gridDim.x) {
+        const int li = rl_row_of_chunk(s_base, nrows, g);
+        const int64_t r = lr->rows[li];
+        const int64_t lo = row_ptr[r], hi = row_ptr[r + 1];
+        int before = 0;
+        for (int c = s_base[li] + threadIdx.x; c < g; c += RL_B) before += chunk_cnt[c];
+        before = rl_block_sum(before, s_w);
+        const int64_t q0 = lo + (int64_t)(g - s_base[li]) * RL_CHUNK + (int64_t)threadIdx.x * RL_U;
+        int32_t cc[RL_U];
+        bool rest[RL_U];
+        int mine = 0;
+#pragma unroll
+        for (int u = 0; u < RL_U; ++u) {
+            const int64_t q = q0 + u;
+            cc[u] = q < hi ? col_idx[q] : 0;
+            rest[u] = q < hi && find_slot(dia_off, nd, (int32_t)((int64_t)cc[u] - r)) < 0;
+            mine += rest[u] ? 1 : 0;
+        }
+        // exclusive scan of `mine` over the block, in thread order
+        int incl = mine;
+        for (int o = 1; o < WAVE; o <<= 1) {
+            const int t = __shfl_up(incl, o, WAVE);
+            if (lane_id() >= o) incl += t;
+        }
+        if (lane_id() == WAVE - 1) s_scan[threadIdx.x / WAVE] = incl;
+        __syncthreads();
+        int pos = incl - mine;
+        for (int w = 0; w < (int)threadIdx.x / WAVE; ++w) pos += s_scan[w];
+        __syncthreads();
+        int64_t out = (int64_t)rest_ptr[r] + before + pos;
+#pragma unroll
+        for (int u = 0; u < RL_U; ++u) {
+            if (rest[u]) {
+                rcol[out] = cc[u];
+                rval[out] = val[q0 + u];
+                ++out;
+            }
+        }
     }
 }
 
@@ -413,7 +576,7 @@ template <typename T, bool SPARSE>
 __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
                                                   const T *__restrict__ val, int64_t m,
                                                   const int32_t *__restrict__ dia_off, int nd, const int32_t *__restrict__ rest_ptr,
-                                                  int32_t *__restrict__ rcol, T *__restrict__ rval, int rw)
+                                                  int32_t *__restrict__ rcol, T *__restrict__ rval, int rw, int skip_len)
 {
     __shared__ int32_t s_col[(CB / WAVE) * WCAP];
     __shared__ T s_val[SPARSE ? 1 : (CB / WAVE) * WCAP];
@@ -444,7 +607,8 @@ __global__ __launch_bounds__(CB) void k_hdc_rest(const int32_t *__restrict__ row
     if (ballot64(direct && need > 0) != 0ull)
         hdc_rest_row<T>(direct, len, need, row, base, dia_off, nd, rcol, rval,
                         [&](int e) { return col_idx[lo + e]; }, [&](int e) { return val[lo + e]; });
-    uint64_t longmask = ballot64(rv && len > SHORT_ROW && need > 0);
+    // skip_len > 0: rows longer than that (and not merged lane per row by the fill kernel) are left to the chip-wide kernels
+    uint64_t longmask = ballot64(rv && len > SHORT_ROW && need > 0 && !(skip_len > 0 && len > skip_len && (int64_t)len > 2 * (int64_t)nd));
     const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (WAVE - lane));
     while (longmask) {
         const int l = __ffsll((unsigned long long)longmask) - 1;
@@ -702,8 +866,13 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         MO_HIP(hipMemcpyAsync(h->dia_off, hoff.data(), (size_t)nd * 4, hipMemcpyHostToDevice, s));
         const int rw = rows_per_wave(a.m, a.nnz);
         hipLaunchKernelGGL(k_fill_dia<T>, dim3(wave_blocks_for(h->ld, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, (const T *)a.val, a.m,
-                           h->dia_off, (int)nd, h->ld, (T *)h->dia_val, rest_cnt, rw);
+                           h->dia_off, (int)nd, h->ld, (T *)h->dia_val, rest_cnt, rw, an.n_long > 0 ? (int)VLONG_ROW : 0);
         MO_LAUNCH_CHECK();
+        if (an.n_long > 0) {   // rows too long for one wave: their entries, chip-wide
+            hipLaunchKernelGGL(k_fill_dia_long<T>, dim3(RL_BLOCKS), dim3(RL_B), 0, s, an.long_rows, an.n_long, a.row_ptr, a.col_idx,
+                               (const T *)a.val, a.m, h->dia_off, (int)nd, h->ld, (T *)h->dia_val, rest_cnt);
+            MO_LAUNCH_CHECK();
+        }
     } else if (rest_cnt) {   // no diagonal is kept: every entry is remainder
         hipLaunchKernelGGL(k_surplus, dim3(blocks_for(a.m)), dim3(CB), 0, s, a.row_ptr, a.m, (int64_t)0, rest_cnt);
         MO_LAUNCH_CHECK();
@@ -922,13 +1091,24 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
             MO_HIP(hipMemcpyAsync(rval, aval, (size_t)total * sizeof(T), hipMemcpyDeviceToDevice, s));
         } else if (total > 0) {
             const int rw = rows_per_wave(a.m, a.nnz);
+            const int skip_len = an.n_long > 0 ? (int)VLONG_ROW : 0;
             if ((int64_t)total * 4 < a.nnz)
                 hipLaunchKernelGGL((k_hdc_rest<T, true>), dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m,
-                               h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw);
+                               h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw, skip_len);
             else
                 hipLaunchKernelGGL((k_hdc_rest<T, false>), dim3(wave_blocks_for(a.m, rw)), dim3(CB), 0, s, a.row_ptr, a.col_idx, aval, a.m,
-                               h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw);
+                               h->dia_off, (int)h->nd, rest_ptr, rcol, rval, rw, skip_len);
             MO_LAUNCH_CHECK();
+            if (an.n_long > 0) {   // rows too long for one wave: count per chunk, then write in the order of the row
+                int32_t *chunk_cnt = (int32_t *)scr.get((size_t)(a.nnz / RL_CHUNK + an.n_long + 1) * 4);
+                if (!chunk_cnt) return MO_E_ALLOC;
+                hipLaunchKernelGGL(k_hdc_rest_long_count, dim3(RL_BLOCKS), dim3(RL_B), 0, s, an.long_rows, an.n_long, a.row_ptr, a.col_idx,
+                                   a.m, h->dia_off, (int)h->nd, chunk_cnt);
+                MO_LAUNCH_CHECK();
+                hipLaunchKernelGGL(k_hdc_rest_long_write<T>, dim3(RL_BLOCKS), dim3(RL_B), 0, s, an.long_rows, an.n_long, a.row_ptr, a.col_idx,
+                                   aval, a.m, h->dia_off, (int)h->nd, chunk_cnt, rest_ptr, rcol, rval);
+                MO_LAUNCH_CHECK();
+            }
         }
         h->csr_row_ptr = rest_ptr; h->csr_col = rcol; h->csr_val = rval;
         MO_TRY(plan_csr(b, rest_ptr, a.m, total, an.max_row));

@@ -53,6 +53,16 @@ def small_cases():
     v2 = synth.uniform_pm1(13, 0, np.arange(ci2.shape[0]))
     out.append(("long_row", m, n, rp2.astype(np.int32), ci2.astype(np.int32), v2))
     out.append(("very_long_rows", *very_long_rows()))
+    # the same with the full main diagonal and the diagonal above it: HDC keeps two true diagonals, and the long rows,
+    # which hold entries on both of them, go to the chip-wide fill kernels of the DIA part and of the CSR remainder
+    m, n, rp, ci, v = very_long_rows()
+    rows = np.repeat(np.arange(m, dtype=np.int64), np.diff(rp))
+    d = np.arange(m, dtype=np.int64)
+    keys = np.unique(np.concatenate([rows * n + ci.astype(np.int64), d * (n + 1), d[:-1] * (n + 1) + 1]))
+    r2, c2 = keys // n, keys % n
+    rp2 = np.zeros(m + 1, np.int64)
+    np.cumsum(np.bincount(r2, minlength=m), out=rp2[1:])
+    out.append(("arrow", m, n, rp2.astype(np.int32), c2.astype(np.int32), synth.uniform_pm1(20, 0, np.arange(c2.shape[0]))))
     # a tridiagonal matrix with a 256-row stretch of 29 diagonals: the mean row is short, so a wave takes 64 rows, and in
     # the stretch their entries exceed one LDS stage of the conversion kernels (rows past the staged window)
     m = n = 4096
