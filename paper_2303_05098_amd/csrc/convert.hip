@@ -43,6 +43,7 @@ __device__ __forceinline__ void walk_rows_lds(bool rv, int64_t row, int64_t lo64
     const int we = nvalid ? __builtin_amdgcn_readlane(hi, nvalid - 1) : 0;
     for (int c0 = wb; c0 < we; c0 += WCAP) {
         const int c1 = we - c0 > WCAP ? c0 + WCAP : we;
+        if (ballot64(is_short && hi > c0 && lo < c1) == 0ull) continue;   // a stretch inside one long row: nothing to stage
         stage_pair_to_lds(col_idx + c0, val + c0, s_col, s_val, c1 - c0, lane);
         const int a = lo > c0 ? lo : c0, b = hi < c1 ? hi : c1;
         const int cnt = (is_short && b > a) ? b - a : 0;
@@ -493,7 +494,8 @@ __global__ __launch_bounds__(FL_B) void k_fill_ell_long(const LongRows *__restri
 // LEN_LDS, flushed once per block); a block owns a contiguous run of rows.
 constexpr int LEN_LDS = 2048;
 
-__global__ __launch_bounds__(CB) void k_len_hist(const int32_t *__restrict__ row_ptr, int64_t m, int64_t rows_per_block,
+// Lengths above cap are counted as cap (the caller needs them only as "at least cap").
+__global__ __launch_bounds__(CB) void k_len_hist(const int32_t *__restrict__ row_ptr, int64_t m, int64_t rows_per_block, int cap,
                                                   uint32_t *__restrict__ lhist)
 {
     __shared__ uint32_t sh[LEN_LDS];
@@ -506,7 +508,8 @@ __global__ __launch_bounds__(CB) void k_len_hist(const int32_t *__restrict__ row
     for (int64_t base = row_begin; base < row_end; base += CB) {
         const int64_t row = base + threadIdx.x;
         const bool rv = row < row_end;
-        const int key = rv ? (row_ptr[row + 1] - row_ptr[row]) : -1;
+        int key = rv ? (row_ptr[row + 1] - row_ptr[row]) : -1;
+        key = key > cap ? cap : key;
         uint64_t todo = ballot64(rv);
         while (todo) {
             const int leader = __ffsll((unsigned long long)todo) - 1;
@@ -1015,15 +1018,22 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         if (fmt == MO_ELL) {
             if (!slab_feasible(K, a.m, a.nnz, p)) return MO_E_FILL;
         } else {
-            // K_H from the histogram of row lengths: largest k with #{len >= k} * den >= m * num.
-            const int64_t nh = an.max_row + 1;
+            // K_H from the histogram of row lengths: largest k with #{len >= k} * den >= m * num.  Since #{len >= k} * k
+            // <= nnz, no k above nnz * den / (m * num) qualifies, so longer rows share the last counter: a matrix with one
+            // row of a million entries does not send a million counters to the host.
+            int64_t cap = an.max_row;
+            if (p.hyb_num > 0) {
+                const __int128 bound = (__int128)a.nnz * (__int128)p.hyb_den / ((__int128)a.m * (__int128)p.hyb_num) + 1;
+                if (bound < (__int128)cap) cap = (int64_t)bound;
+            }
+            const int64_t nh = cap + 1;
             uint32_t *lhist = (uint32_t *)scr.get((size_t)nh * 4);
             if (!lhist) return MO_E_ALLOC;
             hipLaunchKernelGGL(k_fill_i32, dim3(fill_grid(nh)), dim3(CB), 0, s, (int32_t *)lhist, nh, 0);
             MO_LAUNCH_CHECK();
             int64_t rpb = (a.m + 1023) / 1024;                 // at most 1024 blocks, each a multiple of the block size
             rpb = ((rpb + CB - 1) / CB) * CB;
-            hipLaunchKernelGGL(k_len_hist, dim3((unsigned)((a.m + rpb - 1) / rpb)), dim3(CB), 0, s, a.row_ptr, a.m, rpb, lhist);
+            hipLaunchKernelGGL(k_len_hist, dim3((unsigned)((a.m + rpb - 1) / rpb)), dim3(CB), 0, s, a.row_ptr, a.m, rpb, (int)cap, lhist);
             MO_LAUNCH_CHECK();
             std::vector<uint32_t> hh((size_t)nh);
             MO_HIP(hipMemcpyAsync(hh.data(), lhist, (size_t)nh * 4, hipMemcpyDeviceToHost, s));
@@ -1031,12 +1041,15 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
             const __int128 need = (__int128)a.m * (__int128)p.hyb_num;
             int64_t rows_ge = 0;   // rows with len >= k, walking k downwards
             K = 0;
-            for (int64_t k = an.max_row; k >= 1; --k) {
+            for (int64_t k = cap; k >= 1; --k) {
                 rows_ge += hh[(size_t)k];
                 if ((__int128)rows_ge * (__int128)p.hyb_den >= need) { K = k; break; }
             }
-            int64_t surplus = 0;
-            for (int64_t len = K + 1; len <= an.max_row; ++len) surplus += (int64_t)hh[(size_t)len] * (len - K);
+            // entries beyond slot K: all entries minus min(len, K) per row (rows counted at cap are longer than K, or
+            // cap is the longest row)
+            int64_t kept = 0;
+            for (int64_t len = 1; len <= cap; ++len) kept += (int64_t)hh[(size_t)len] * (len < K ? len : K);
+            const int64_t surplus = a.nnz - kept;
             h->nnz_coo = surplus;
             h->hyb_max_surplus = an.max_row > K ? an.max_row - K : 0;
             const size_t e = (size_t)(surplus > 0 ? surplus : 1);
