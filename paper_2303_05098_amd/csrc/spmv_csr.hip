@@ -223,11 +223,33 @@ __global__ __launch_bounds__(CSR_B) void k_csr_split(const int32_t *__restrict__
         if (threadIdx.x == 0) carry_val[tile] = total;
     }
     if (threadIdx.x == 0) carry_row[tile] = seg > 0 ? (int32_t)(ra - 1) : -1;
-    for (int64_t base = 0; base < nrows; base += RPB) {
-        const int64_t r = ra + base + threadIdx.x / G;
-        if (base > 0) {
+    // A tile that owns far more rows than it has entries (a long stretch of empty rows: the remainder of an HDC matrix
+    // whose scattered entries sit in a few rows) walks only the rows between its first and its last entry; the empty
+    // rows around them are zeroed without a look at row_ptr, or left alone when accumulating (half a million of them
+    // in one tile took 1.8 ms).
+    int64_t r_lo = ra, r_hi = rb;
+    if (nrows > 4 * (int64_t)TILE) {   // uniform
+        __shared__ int64_t s_rng[2];
+        if (threadIdx.x == 0) {
+            if (cnt > seg) {
+                s_rng[0] = row_of_entry(row_ptr, ra, rb - 1, t0 + seg);
+                s_rng[1] = row_of_entry(row_ptr, ra, rb - 1, t0 + cnt - 1) + 1;
+            } else {
+                s_rng[0] = rb; s_rng[1] = rb;
+            }
+        }
+        __syncthreads();
+        r_lo = s_rng[0]; r_hi = s_rng[1];
+        if (!ACC) {
+            for (int64_t r = ra + threadIdx.x; r < r_lo; r += CSR_B) y[r] = (T)0;
+            for (int64_t r = r_hi + threadIdx.x; r < rb; r += CSR_B) y[r] = (T)0;
+        }
+    }
+    for (int64_t base = 0; base < r_hi - r_lo; base += RPB) {
+        const int64_t r = r_lo + base + threadIdx.x / G;
+        if (base > 0 || r_lo != ra) {
             lo = hi = 0;
-            if (r < rb) { lo = row_ptr[r] - (int32_t)t0; hi = row_ptr[r + 1] - (int32_t)t0; }
+            if (r < r_hi) { lo = row_ptr[r] - (int32_t)t0; hi = row_ptr[r + 1] - (int32_t)t0; }
         }
         hi = hi < cnt ? hi : cnt;
         const bool is_long = hi - lo > CSR_LONG_SEG;
@@ -235,7 +257,7 @@ __global__ __launch_bounds__(CSR_B) void k_csr_split(const int32_t *__restrict__
         if (!is_long)
             for (int e = lo + sub; e < hi; e += G) sum += ps[e];
         if (G > 1) sum = group_sum_down(sum, G);
-        if (sub == 0 && r < rb) {
+        if (sub == 0 && r < r_hi) {
             if (is_long) s_long[atomicAdd(&s_nlong, 1)] = (int)(r - ra);
             else if (ACC) y[r] += sum;
             else y[r] = sum;
