@@ -535,6 +535,19 @@ __global__ __launch_bounds__(CB) void k_surplus(const int32_t *__restrict__ row_
     cnt[row] = (int32_t)(len > K ? len - K : 0);
 }
 
+// Row pointers of the HDC remainder relative to the first entry of the row's block of `rows` rows (see mo_matrix::hdc_rp16).
+__global__ __launch_bounds__(CB) void k_hdc_rp16(const int32_t *__restrict__ rest_ptr, int64_t m, int rows, int32_t *__restrict__ blk,
+                                                 uint16_t *__restrict__ rp16)
+{
+    const int64_t row = (int64_t)blockIdx.x * CB + threadIdx.x;
+    if (row > m) return;
+    if (row == m) { blk[(m + rows - 1) / rows] = rest_ptr[m]; return; }
+    const int64_t b = row / rows;
+    const int32_t base = rest_ptr[b * rows];
+    if (row == b * rows) blk[b] = base;
+    rp16[row] = (uint16_t)(rest_ptr[row] - base);
+}
+
 // ------------------------------------------------------------------ HDC remainder
 // The entries of a row that are on no kept diagonal are written, in row order, to the CSR part starting at
 // rest_ptr[row] (their number per row was counted while the DIA part was filled).  Same staging and the same merge
@@ -887,10 +900,11 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         // SpMV: 512 threads per block, one row per lane in fp64 and two in fp32 (8 bytes per lane and load either way):
         // measured best of {256, 512} x {1, 2} on the stencil and band configurations.  Matrices of fewer than 2^17
         // rows get 256-thread blocks: twice as many, shorter blocks on a chip they cannot fill anyway.
-        const int block = a.m < 131072 ? 256 : 512, rows = sizeof(T) == 4 ? 2 : 1;
+        const int block = a.m < 131072 ? 256 : 512, rows = DIA_ROWS_PER_LANE<T>;
         std::vector<int32_t> xpos, cl, mxpos, mcl, mmap;
         int64_t elems = 0, melems = 0;
         const bool have_v = plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems);
+        static_assert(DIA_LDS_BYTES / 4 <= (int64_t)DIA_MAX_RUNS * 256, "runs of the DIA launch plan");
         // the multi-vector product: blocks of SPMM_ROWS rows; kept when a 16-byte piece per row of X fits
         const bool have_m = plan_dia_clusters(hoff, SPMM_ROWS, SPMM_WIN_BYTES / 16, &mxpos, &mcl, &melems);
         if (have_m) {
@@ -909,21 +923,29 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         if (have_v || have_m) {
             b.keep.emplace_back();
             std::vector<int32_t> &all = b.keep.back();   // alive until the conversion's final synchronisation
-            const size_t o_xpos = 0, o_cl = o_xpos + (have_v ? xpos.size() : 0), o_mx = o_cl + (have_v ? cl.size() : 0),
-                         o_map = o_mx + (have_m ? mxpos.size() : 0), total = o_map + (have_m ? mmap.size() : 0);
+            const size_t o_xpos = 0, o_mx = o_xpos + (have_v ? xpos.size() : 0), o_map = o_mx + (have_m ? mxpos.size() : 0),
+                         total = o_map + (have_m ? mmap.size() : 0);
             all.reserve(total);
-            if (have_v) { all.insert(all.end(), xpos.begin(), xpos.end()); all.insert(all.end(), cl.begin(), cl.end()); }
+            if (have_v) all.insert(all.end(), xpos.begin(), xpos.end());
             if (have_m) { all.insert(all.end(), mxpos.begin(), mxpos.end()); all.insert(all.end(), mmap.begin(), mmap.end()); }
             int32_t *dev = (int32_t *)b.own(total * 4);
             if (b.failed) return MO_E_ALLOC;
             MO_HIP(hipMemcpyAsync(dev, all.data(), total * 4, hipMemcpyHostToDevice, s));
             if (have_v) {
                 h->dia_xpos = dev + o_xpos;
-                h->dia_clusters = dev + o_cl;
                 h->dia_block = block;
                 h->dia_rows = rows;
-                h->dia_ncl = (int32_t)(cl.size() / 3);
-                h->dia_lds_elems = elems;
+                DiaPlan &pl = h->dia_plan;
+                pl.elems = (int32_t)elems;
+                size_t q = 0;   // window that holds the first position of the run
+                for (int u = 0; (int64_t)u * block < elems; ++u) {
+                    while (q + 5 < cl.size() && (int64_t)cl[q + 5] <= (int64_t)u * block) q += 3;
+                    const bool more = q + 5 < cl.size();
+                    pl.bnd[u] = more ? cl[q + 5] : INT32_MAX;
+                    pl.d0[u] = cl[q] - cl[q + 2];
+                    pl.d1[u] = more ? cl[q + 3] - cl[q + 5] : 0;
+                }
+                for (size_t k = 0; k < xpos.size() && k < (size_t)DIA_PRE; ++k) pl.xpos[k] = xpos[k];
             }
             if (have_m) {
                 h->mm_xpos = dev + o_mx;
@@ -1125,6 +1147,16 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         }
         h->csr_row_ptr = rest_ptr; h->csr_col = rcol; h->csr_val = rval;
         MO_TRY(plan_csr(b, rest_ptr, a.m, total, an.max_row));
+        if (total > 0 && h->dia_block && an.max_row <= HDC_FUSED_MAX_ROW) {
+            // a block of the fused kernel holds at most 1024 rows of at most 64 entries: offsets inside it fit 16 bits
+            static_assert(1023 * HDC_FUSED_MAX_ROW <= 65535, "remainder offsets inside a row block");
+            const int rows = h->dia_block * h->dia_rows;
+            h->hdc_blk = (int32_t *)b.own((size_t)((a.m + rows - 1) / rows + 1) * 4);
+            h->hdc_rp16 = (uint16_t *)b.own((size_t)a.m * 2);
+            if (b.failed) return MO_E_ALLOC;
+            hipLaunchKernelGGL(k_hdc_rp16, dim3(blocks_for(a.m + 1)), dim3(CB), 0, s, rest_ptr, a.m, rows, h->hdc_blk, h->hdc_rp16);
+            MO_LAUNCH_CHECK();
+        }
         break;
     }
     default:

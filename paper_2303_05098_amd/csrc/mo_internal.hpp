@@ -88,6 +88,24 @@ struct XPlan {
 
 }  // namespace mo
 
+namespace mo {
+// Launch plan of the LDS-staged DIA / HDC kernel, passed by value in the kernel arguments (scalar registers: no
+// load to wait for).  The x windows of a block are contiguous in LDS, elems positions in all, and every window is at
+// least as long as the block has threads, so a run of `block` positions u * block .. (u + 1) * block - 1 lies in at most
+// two windows: position i of run u holds x[row0 + i + (i < bnd[u] ? d0[u] : d1[u])], row0 being the block's first
+// row.  xpos[k] is the position of x[row0 + off_k] for the first DIA_PRE diagonals (all of them are in the device
+// array mo_matrix::dia_xpos).
+constexpr int DIA_MAX_RUNS = 48;   // 48 KB of LDS / (256 threads x 4 bytes)
+constexpr int DIA_PRE = 12;
+struct DiaPlan {
+    int32_t elems = 0;
+    int32_t bnd[DIA_MAX_RUNS] = {};
+    int32_t d0[DIA_MAX_RUNS] = {};
+    int32_t d1[DIA_MAX_RUNS] = {};
+    int32_t xpos[DIA_PRE] = {};
+};
+}  // namespace mo
+
 struct mo_matrix {
     mo_format fmt = MO_CSR;
     mo_dtype dtype = MO_F64;
@@ -99,9 +117,14 @@ struct mo_matrix {
     // x windows the DIA kernels stage in LDS (launch data, derived from dia_off at conversion time)
     int32_t dia_block = 0;            // threads per block of the LDS kernel; 0 = direct kernel
     int32_t dia_rows = 1;             // rows per thread of the LDS kernel
-    int32_t dia_ncl = 0;
-    int64_t dia_lds_elems = 0;
-    int32_t *dia_xpos = nullptr, *dia_clusters = nullptr;
+    mo::DiaPlan dia_plan;             // its windows
+    int32_t *dia_xpos = nullptr;      // per diagonal: LDS position that the block's first row reads
+    // HDC run as one kernel: the remainder's row pointers in the form that kernel reads (launch data; the exported
+    // csr_row_ptr stays as it is).  hdc_blk[b] = first remainder entry of row block b (blocks of dia_block * dia_rows
+    // rows; one entry more than blocks), hdc_rp16[row] = csr_row_ptr[row] - hdc_blk[block of row]: 2 bytes per row
+    // streamed instead of 4.  Null when the fused kernel is not the one that runs.
+    int32_t *hdc_blk = nullptr;
+    uint16_t *hdc_rp16 = nullptr;
     // the same kind of plan for blocks of SPMM_ROWS rows: windows of X for the multi-vector product
     int64_t mm_lds_elems = 0;         // staged rows of X per block; 0 = no plan (windows too large), direct kernel
     int32_t *mm_xpos = nullptr;       // per diagonal: staged row that the block's first matrix row reads
@@ -214,6 +237,8 @@ mo_status spmv_hdc_fused(const mo_matrix &a, const void *x, void *y, hipStream_t
 bool plan_dia_clusters(const std::vector<int32_t> &off, int block, int64_t max_elems, std::vector<int32_t> *xpos,
                        std::vector<int32_t> *clusters, int64_t *total_elems);
 constexpr int64_t DIA_LDS_BYTES = 48 * 1024;  // LDS budget for staged x windows per block
+// rows per lane of the LDS-staged DIA kernel: a lane moves 8 bytes per slab load in either precision
+template <typename T> constexpr int DIA_ROWS_PER_LANE = sizeof(T) == 4 ? 2 : 1;
 constexpr int SPMM_ROWS = 64;                 // matrix rows per block of the DIA multi-vector kernel with staged windows of X
 constexpr int64_t SPMM_WIN_BYTES = 64 * 1024; // its LDS budget per block (two blocks per CU at least; four below 40 KB)
 // column slices of a CSR handle: from an x of this size on (one XCD's L2 is 4 MB), so many that a slice is at most

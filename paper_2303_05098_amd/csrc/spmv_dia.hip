@@ -61,10 +61,19 @@ __global__ __launch_bounds__(DIA_B) void k_hdc_fused(const int32_t *__restrict__
 }
 
 // ---------------------------------------------------------------------------------------------- LDS-staged kernels
-// cl[3c] = lowest offset of cluster c, cl[3c+1] = staged length (span + rows per block), cl[3c+2] = LDS base.
-// xpos[k] = LDS position of x[row0 + off_k] for the block's first row.
+// The launch plan (DiaPlan) travels in the kernel arguments, so a block reads it from scalar registers.  The windows
+// are contiguous in LDS, so staging is one flat loop over positions, B at a time; such a run of positions lies in at
+// most two windows, and the plan names, per run, where the second one starts and which x each of them holds.
+// xpos[k] is the LDS position of x[row0 + off_k] for the block's first row.
 //
 // Every thread owns R consecutive rows (R = 1 for fp64, 2 for fp32 so that a lane still moves 8 bytes per load).
+//
+// A block's loads are issued as one batch before its barrier: the first DIA_WB positions per thread of the
+// windows, the row pointers (HDC), the slab values of the first DIA_PRE diagonals, and the first chunk of the HDC
+// remainder with its x gathers.  A block then pays one memory latency for all of them instead of one per window
+// piece and per group of four diagonals; blocks are short-lived (a few thousand slab values), so a block that waits
+// for one load at a time keeps almost nothing in flight for much of its life.  Further diagonals follow in batches
+// of DIA_PRE after the barrier.
 //
 // HDC: the CSR remainder of the block's rows is one contiguous run of entries.  It is handled entry-parallel, not
 // row by row: the block multiplies those entries with their gathered x values into an LDS buffer (in chunks of
@@ -90,81 +99,139 @@ __device__ __forceinline__ void load_rows(const T *p, T (&out)[R])
 }
 
 template <typename T, int B, int R, bool HDC>
-__global__ __launch_bounds__(B) void k_dia_lds(const int32_t *__restrict__ xpos, const int32_t *__restrict__ cl, int ncl,
-                                               const T *__restrict__ val, int64_t m, int64_t n, int64_t nd, int64_t ld,
-                                               const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
-                                               const T *__restrict__ cval, const T *__restrict__ x, T *__restrict__ y)
+__global__ __launch_bounds__(B) void k_dia_lds(const DiaPlan pl, const int32_t *__restrict__ xpos, const T *__restrict__ val, int64_t m,
+                                               int64_t n, int64_t nd, int64_t ld, const int32_t *__restrict__ blk_ptr,
+                                               const uint16_t *__restrict__ rp16, const int32_t *__restrict__ col_idx, const T *__restrict__ cval,
+                                               const T *__restrict__ x, T *__restrict__ y)
 {
     constexpr int ROWS = B * R;
+    constexpr int WB = sizeof(T) == 8 ? 8 : 12;   // window positions per thread and batch
     extern __shared__ __align__(16) unsigned char s_raw[];
     T *xs = reinterpret_cast<T *>(s_raw);
     __shared__ int32_t rps[HDC ? ROWS + 1 : 1];
     __shared__ T prod[HDC ? HDC_CHUNK : 1];
+    const int tid = (int)threadIdx.x;
     const int64_t lb = xcd_block(blockIdx.x, gridDim.x);
     const int64_t row0 = lb * ROWS;
-    const int64_t row = row0 + (int64_t)threadIdx.x * R;
-    // HDC: the remainder entries of this block are [blk_lo, blk_lo + nrem).  The first chunk's columns and values are
-    // requested right away, their x values right after the barrier, and the products are only needed after the
-    // diagonal stream, so none of these latencies is exposed on its own.
-    int32_t blk_lo = 0, nrem = 0, first_c = 0;
+    const int64_t row = row0 + (int64_t)tid * R;
+    const int64_t rl = row < m ? row : 0;   // rows past the end load row 0's slab values and drop them
+    // HDC: the remainder entries of this block are [blk_lo, blk_lo + nrem)
+    int32_t blk_lo = 0, nrem = 0;
+    if (HDC) {
+        blk_lo = blk_ptr[lb];
+        nrem = blk_ptr[lb + 1] - blk_lo;
+    }
+    // x for window positions tid + u * B, u = u0 .. u0 + WB - 1 (0 outside [0, n), as the slabs hold +0 there).  The
+    // loads stand alone behind conditions that are the same for every thread; whatever consumes a loaded value
+    // comes after all loads of the batch have been issued.
+    T w[WB];
+    uint32_t w_in = 0;
+    auto window_loads = [&](int u0) {
+        int64_t jj[WB];
+        w_in = 0;
+#pragma unroll
+        for (int u = 0; u < WB; ++u) {
+            const int r = u0 + u < DIA_MAX_RUNS ? u0 + u : DIA_MAX_RUNS - 1;
+            const int64_t s0 = row0 + (int64_t)r * B + pl.d0[r], s1 = row0 + (int64_t)r * B + pl.d1[r];   // scalar
+            const int64_t j = (tid + r * B < pl.bnd[r] ? s0 : s1) + tid;
+            const bool in = (uint64_t)j < (uint64_t)n;
+            jj[u] = in ? j : 0;
+            w_in |= in ? 1u << u : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < WB; ++u)
+            if ((u0 + u) * B < pl.elems) w[u] = x[jj[u]];
+    };
+    auto window_stores = [&](int u0) {
+#pragma unroll
+        for (int u = 0; u < WB; ++u) {
+            const int i = tid + (u0 + u) * B;
+            if (i < pl.elems) xs[i] = (w_in >> u & 1u) ? w[u] : (T)0;
+        }
+    };
+    // Issue order (loads return in order): the remainder's columns first, so that their x gathers can follow as
+    // soon as they arrive and while everything else is still on its way.
+    uint32_t first_c = 0;
     T first_v = (T)0;
-    bool first_on = false;
-    if (HDC) {
-        const int64_t rend = row0 + ROWS < m ? row0 + ROWS : m;
-        blk_lo = row_ptr[row0];
-        nrem = row_ptr[rend] - blk_lo;
-        first_on = (int)threadIdx.x < nrem && (int)threadIdx.x < HDC_CHUNK;
-        if (first_on) { first_c = col_idx[blk_lo + threadIdx.x]; first_v = cval[blk_lo + threadIdx.x]; }
+    const bool first_on = HDC && tid < nrem;
+    if (HDC && nrem > 0) {   // entry e0 for this thread (clamped: every thread loads, the surplus ones drop it)
+        const int e0 = tid < nrem ? tid : nrem - 1;
+        first_c = (uint32_t)col_idx[blk_lo + e0];
+        first_v = cval[blk_lo + e0];
     }
-    for (int c = 0; c < ncl; ++c) {
-        const int64_t first = row0 + cl[3 * c];
-        const int len = cl[3 * c + 1], base = cl[3 * c + 2];
-        for (int i = threadIdx.x; i < len; i += B) {
-            const int64_t j = first + i;
-            xs[base + i] = (j >= 0 && j < n) ? x[j] : (T)0;
+    __builtin_amdgcn_sched_barrier(0);
+    window_loads(0);
+    int32_t rp_mine[R];
+    if (HDC) {
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+            const int64_t r = row0 + tid + u * B;
+            rp_mine[u] = r < m ? (int32_t)rp16[r] : nrem;   // relative to blk_lo
         }
     }
+    T a[DIA_PRE][R];
+    const T *v0 = val + rl;
+#pragma unroll
+    for (int k = 0; k < DIA_PRE; ++k)
+        if (k < nd) load_rows<T, R>(v0 + k * ld, a[k]);
+    __builtin_amdgcn_sched_barrier(0);
+    T x_first = (T)0;
+    if (HDC && nrem > 0) x_first = x[first_c];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll 1
+    for (int u0 = WB; u0 * B < pl.elems; u0 += WB) {   // more window positions than one batch holds: rare
+        window_stores(u0 - WB);
+        window_loads(u0);
+    }
+    window_stores(((pl.elems + B - 1) / B - 1) / WB * WB);
     if (HDC) {
-        for (int i = threadIdx.x; i <= ROWS; i += B) {
-            const int64_t r = row0 + i;
-            rps[i] = row_ptr[r < m ? r : m];
-        }
+#pragma unroll
+        for (int u = 0; u < R; ++u) rps[tid + u * B] = rp_mine[u];
+        if (tid == 0) rps[ROWS] = nrem;
     }
     __syncthreads();
     T sum[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) sum[j] = (T)0;
-    T p_first = (T)0;
-    if (HDC && first_on) p_first = first_v * x[first_c];
-    if (row < m) {   // ld is a multiple of 64 and row a multiple of R, so a vector of R rows never leaves the slab
-        const T *v = val + row;
-        const T *xl = xs + threadIdx.x * R;
-#pragma unroll 4
-        for (int64_t k = 0; k < nd; ++k) {
-            T a[R];
-            load_rows<T, R>(v + k * ld, a);
-            const T *xk = xl + xpos[k];
+    const T *xl = xs + tid * R;
 #pragma unroll
-            for (int j = 0; j < R; ++j) sum[j] += a[j] * xk[j];
+    for (int k = 0; k < DIA_PRE; ++k) {
+        if (k < nd) {
+            const T *xk = xl + pl.xpos[k];
+#pragma unroll
+            for (int j = 0; j < R; ++j) sum[j] += a[k][j] * xk[j];
+        }
+    }
+    for (int64_t k0 = DIA_PRE; k0 < nd; k0 += DIA_PRE) {
+#pragma unroll
+        for (int k = 0; k < DIA_PRE; ++k)
+            if (k0 + k < nd) load_rows<T, R>(v0 + (k0 + k) * ld, a[k]);
+#pragma unroll
+        for (int k = 0; k < DIA_PRE; ++k) {
+            if (k0 + k < nd) {
+                const T *xk = xl + xpos[k0 + k];
+#pragma unroll
+                for (int j = 0; j < R; ++j) sum[j] += a[k][j] * xk[j];
+            }
         }
     }
     if (HDC && nrem > 0) {   // nrem is uniform across the block
         for (int32_t c0 = 0; c0 < nrem; c0 += HDC_CHUNK) {
             if (c0 == 0) {
-                if ((int)threadIdx.x < nrem && (int)threadIdx.x < HDC_CHUNK) prod[threadIdx.x] = p_first;
-                for (int e = threadIdx.x + B; e < HDC_CHUNK && e < nrem; e += B) prod[e] = cval[blk_lo + e] * x[col_idx[blk_lo + e]];
+                if (first_on) prod[tid] = first_v * x_first;
+                for (int e = tid + B; e < HDC_CHUNK && e < nrem; e += B) prod[e] = cval[blk_lo + e] * x[col_idx[blk_lo + e]];
             } else {
-                for (int e = threadIdx.x; e < HDC_CHUNK && c0 + e < nrem; e += B) prod[e] = cval[blk_lo + c0 + e] * x[col_idx[blk_lo + c0 + e]];
+                for (int e = tid; e < HDC_CHUNK && c0 + e < nrem; e += B) prod[e] = cval[blk_lo + c0 + e] * x[col_idx[blk_lo + c0 + e]];
             }
             __syncthreads();
 #pragma unroll
             for (int j = 0; j < R; ++j) {
-                int lo = rps[threadIdx.x * R + j] - blk_lo - c0, hi = rps[threadIdx.x * R + j + 1] - blk_lo - c0;
+                int lo = rps[tid * R + j] - c0, hi = rps[tid * R + j + 1] - c0;
                 lo = lo < 0 ? 0 : lo;
                 hi = hi > HDC_CHUNK ? HDC_CHUNK : hi;
                 for (int e = lo; e < hi; ++e) sum[j] += prod[e];
             }
-            __syncthreads();
+            if (c0 + HDC_CHUNK < nrem) __syncthreads();   // the products are replaced by the next chunk's
         }
     }
     if (row < m) {
@@ -185,9 +252,9 @@ static mo_status launch_lds(const mo_matrix &a, const void *x, void *y, hipStrea
 {
     const int64_t rows = (int64_t)B * R;
     const unsigned grid = (unsigned)((a.m + rows - 1) / rows);
-    const size_t lds = (size_t)a.dia_lds_elems * sizeof(T);
-    hipLaunchKernelGGL((k_dia_lds<T, B, R, HDC>), dim3(grid), dim3(B), lds, s, a.dia_xpos, a.dia_clusters, (int)a.dia_ncl,
-                       (const T *)a.dia_val, a.m, a.n, a.nd, a.ld, a.csr_row_ptr, a.csr_col, (const T *)a.csr_val, (const T *)x, (T *)y);
+    const size_t lds = (size_t)a.dia_plan.elems * sizeof(T);
+    hipLaunchKernelGGL((k_dia_lds<T, B, R, HDC>), dim3(grid), dim3(B), lds, s, a.dia_plan, a.dia_xpos, (const T *)a.dia_val, a.m, a.n, a.nd,
+                       a.ld, a.hdc_blk, a.hdc_rp16, a.csr_col, (const T *)a.csr_val, (const T *)x, (T *)y);
     MO_LAUNCH_CHECK();
     return MO_OK;
 }
@@ -195,10 +262,9 @@ static mo_status launch_lds(const mo_matrix &a, const void *x, void *y, hipStrea
 template <typename T, bool HDC>
 static mo_status dia_any(const mo_matrix &a, const void *x, void *y, hipStream_t s)
 {
-    if (a.dia_block == 256 && a.dia_rows == 1) return launch_lds<T, 256, 1, HDC>(a, x, y, s);
-    if (a.dia_block == 512 && a.dia_rows == 1) return launch_lds<T, 512, 1, HDC>(a, x, y, s);
-    if (a.dia_block == 256 && a.dia_rows == 2) return launch_lds<T, 256, 2, HDC>(a, x, y, s);
-    if (a.dia_block == 512 && a.dia_rows == 2) return launch_lds<T, 512, 2, HDC>(a, x, y, s);
+    constexpr int R = DIA_ROWS_PER_LANE<T>;
+    if (a.dia_block == 256 && a.dia_rows == R) return launch_lds<T, 256, R, HDC>(a, x, y, s);
+    if (a.dia_block == 512 && a.dia_rows == R) return launch_lds<T, 512, R, HDC>(a, x, y, s);
     const unsigned grid = (unsigned)((a.m + DIA_B - 1) / DIA_B);
     if (HDC)
         hipLaunchKernelGGL(k_hdc_fused<T>, dim3(grid), dim3(DIA_B), 0, s, a.dia_off, (const T *)a.dia_val, a.m, a.n, a.nd, a.ld,
@@ -211,6 +277,8 @@ static mo_status dia_any(const mo_matrix &a, const void *x, void *y, hipStream_t
 
 mo_status spmv_hdc_fused(const mo_matrix &a, const void *x, void *y, hipStream_t s)
 {
+    if (a.nnz_csr == 0) return spmv_dia(a, x, y, s);   // nothing beside the diagonals: no row pointers to read
+    if (a.dia_block && (!a.hdc_blk || !a.hdc_rp16)) return MO_E_NULL;   // the conversion builds them whenever this path is taken
     return a.dtype == MO_F32 ? dia_any<float, true>(a, x, y, s) : dia_any<double, true>(a, x, y, s);
 }
 
