@@ -936,15 +936,9 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
                 h->dia_block = block;
                 h->dia_rows = rows;
                 DiaPlan &pl = h->dia_plan;
-                pl.elems = (int32_t)elems;
-                size_t q = 0;   // window that holds the first position of the run
-                for (int u = 0; (int64_t)u * block < elems; ++u) {
-                    while (q + 5 < cl.size() && (int64_t)cl[q + 5] <= (int64_t)u * block) q += 3;
-                    const bool more = q + 5 < cl.size();
-                    pl.bnd[u] = more ? cl[q + 5] : INT32_MAX;
-                    pl.d0[u] = cl[q] - cl[q + 2];
-                    pl.d1[u] = more ? cl[q + 3] - cl[q + 5] : 0;
-                }
+                std::vector<int32_t> wlo, wlen;
+                for (size_t q = 0; q < cl.size(); q += 3) { wlo.push_back(cl[q]); wlen.push_back(cl[q + 1]); }
+                if (!plan_window_runs(wlo.data(), wlen.data(), (int)wlo.size(), block, &pl.win)) return MO_E_SHAPE;   // cannot happen: see the static_assert
                 for (size_t k = 0; k < xpos.size() && k < (size_t)DIA_PRE; ++k) pl.xpos[k] = xpos[k];
             }
             if (have_m) {

@@ -117,6 +117,44 @@ __device__ __forceinline__ void stage_pair_to_lds(const A *__restrict__ ga, cons
     }
 }
 
+// Windows of x staged in LDS, B positions ("a run") at a time, after a plan of type WinRuns<NR> (mo_internal.hpp)
+// that the kernel receives as an argument, so all of it sits in scalar registers.
+// Requests x for the positions tid + u * B, u = u0 .. u0 + WB - 1, of a block's windows (clamped into x; bit u of
+// *in tells whether the position lies inside [0, n): outside, the window holds 0).  The loads stand alone behind
+// conditions that are the same for every thread, and nothing here waits for them: a caller issues its other loads
+// next and calls window_stores after that, so a block pays one memory latency for all of them.
+template <typename T, int B, int WB, typename PL>
+__device__ __forceinline__ void window_loads(const PL &pl, int u0, int tid, int64_t row0, int64_t n, const T *__restrict__ x,
+                                             T (&w)[WB], uint32_t *in)
+{
+    int64_t jj[WB];
+    uint32_t bits = 0;
+#pragma unroll
+    for (int u = 0; u < WB; ++u) {
+        constexpr int NR = (int)(sizeof(pl.bnd) / sizeof(pl.bnd[0]));
+        const int r = u0 + u < NR ? u0 + u : NR - 1;
+        const int64_t s0 = row0 + (int64_t)r * B + pl.d0[r], s1 = row0 + (int64_t)r * B + pl.d1[r];   // scalar
+        const int64_t j = (tid + r * B < pl.bnd[r] ? s0 : s1) + tid;
+        const bool ok = (uint64_t)j < (uint64_t)n;
+        jj[u] = ok ? j : 0;
+        bits |= ok ? 1u << u : 0u;
+    }
+#pragma unroll
+    for (int u = 0; u < WB; ++u)
+        if ((u0 + u) * B < pl.elems) w[u] = x[jj[u]];
+    *in = bits;
+}
+
+template <typename T, int B, int WB, typename PL>
+__device__ __forceinline__ void window_stores(const PL &pl, int u0, int tid, const T (&w)[WB], uint32_t in, T *xs)
+{
+#pragma unroll
+    for (int u = 0; u < WB; ++u) {
+        const int i = tid + (u0 + u) * B;
+        if (i < pl.elems) xs[i] = (in >> u & 1u) ? w[u] : (T)0;
+    }
+}
+
 // The row that holds entry p of a CSR matrix: the largest r in [lo, hi] with row_ptr[r] <= p (row_ptr[lo] <= p is
 // given).  Terminates with a result in [lo, hi] whatever row_ptr holds.
 __device__ __forceinline__ int64_t row_of_entry(const int32_t *__restrict__ row_ptr, int64_t lo, int64_t hi, int64_t p)

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cstdint>
 #include <new>
 #include <vector>
@@ -89,19 +90,49 @@ struct XPlan {
 }  // namespace mo
 
 namespace mo {
+// Windows of x staged in LDS, B positions ("a run") at a time.  The windows of a block lie one after the other in
+// LDS, elems positions in all, and every window is at least B long, so run u (positions u * B .. u * B + B - 1) lies
+// in at most two windows: position i of it holds x[row0 + i + (i < bnd[u] ? d0[u] : d1[u])], row0 being the block's
+// first row.  The plan is a kernel argument, so all of this sits in scalar registers.
+template <int NR>
+struct WinRuns {
+    int32_t elems = 0;
+    int32_t bnd[NR] = {};
+    int32_t d0[NR] = {};
+    int32_t d1[NR] = {};
+};
+
+
+// Host side: the runs of B positions for windows given as (first offset, length) in LDS order.
+template <int NR>
+inline bool plan_window_runs(const int32_t *lo, const int32_t *len, int nwin, int B, WinRuns<NR> *out)
+{
+    int64_t total = 0;
+    for (int q = 0; q < nwin; ++q) {
+        if (len[q] < B) return false;
+        total += len[q];
+    }
+    if (total > (int64_t)NR * B) return false;
+    out->elems = (int32_t)total;
+    int q = 0;
+    int64_t base = 0;   // LDS position of window q
+    for (int u = 0; (int64_t)u * B < total; ++u) {
+        while (q + 1 < nwin && base + len[q] <= (int64_t)u * B) { base += len[q]; ++q; }
+        const bool more = q + 1 < nwin;
+        out->bnd[u] = more ? (int32_t)(base + len[q]) : INT32_MAX;
+        out->d0[u] = (int32_t)(lo[q] - base);
+        out->d1[u] = more ? (int32_t)(lo[q + 1] - (base + len[q])) : 0;
+    }
+    return true;
+}
+
 // Launch plan of the LDS-staged DIA / HDC kernel, passed by value in the kernel arguments (scalar registers: no
-// load to wait for).  The x windows of a block are contiguous in LDS, elems positions in all, and every window is at
-// least as long as the block has threads, so a run of `block` positions u * block .. (u + 1) * block - 1 lies in at most
-// two windows: position i of run u holds x[row0 + i + (i < bnd[u] ? d0[u] : d1[u])], row0 being the block's first
-// row.  xpos[k] is the position of x[row0 + off_k] for the first DIA_PRE diagonals (all of them are in the device
-// array mo_matrix::dia_xpos).
+// load to wait for): the x windows of a block as runs of `block` LDS positions (WinRuns), and xpos[k], the position
+// of x[row0 + off_k], for the first DIA_PRE diagonals (all of them are in the device array mo_matrix::dia_xpos).
 constexpr int DIA_MAX_RUNS = 48;   // 48 KB of LDS / (256 threads x 4 bytes)
 constexpr int DIA_PRE = 12;
 struct DiaPlan {
-    int32_t elems = 0;
-    int32_t bnd[DIA_MAX_RUNS] = {};
-    int32_t d0[DIA_MAX_RUNS] = {};
-    int32_t d1[DIA_MAX_RUNS] = {};
+    WinRuns<DIA_MAX_RUNS> win;
     int32_t xpos[DIA_PRE] = {};
 };
 }  // namespace mo

@@ -121,34 +121,8 @@ __global__ __launch_bounds__(B) void k_dia_lds(const DiaPlan pl, const int32_t *
         blk_lo = blk_ptr[lb];
         nrem = blk_ptr[lb + 1] - blk_lo;
     }
-    // x for window positions tid + u * B, u = u0 .. u0 + WB - 1 (0 outside [0, n), as the slabs hold +0 there).  The
-    // loads stand alone behind conditions that are the same for every thread; whatever consumes a loaded value
-    // comes after all loads of the batch have been issued.
-    T w[WB];
+    T w[WB];          // x for the window positions tid + u * B of the current batch of runs
     uint32_t w_in = 0;
-    auto window_loads = [&](int u0) {
-        int64_t jj[WB];
-        w_in = 0;
-#pragma unroll
-        for (int u = 0; u < WB; ++u) {
-            const int r = u0 + u < DIA_MAX_RUNS ? u0 + u : DIA_MAX_RUNS - 1;
-            const int64_t s0 = row0 + (int64_t)r * B + pl.d0[r], s1 = row0 + (int64_t)r * B + pl.d1[r];   // scalar
-            const int64_t j = (tid + r * B < pl.bnd[r] ? s0 : s1) + tid;
-            const bool in = (uint64_t)j < (uint64_t)n;
-            jj[u] = in ? j : 0;
-            w_in |= in ? 1u << u : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < WB; ++u)
-            if ((u0 + u) * B < pl.elems) w[u] = x[jj[u]];
-    };
-    auto window_stores = [&](int u0) {
-#pragma unroll
-        for (int u = 0; u < WB; ++u) {
-            const int i = tid + (u0 + u) * B;
-            if (i < pl.elems) xs[i] = (w_in >> u & 1u) ? w[u] : (T)0;
-        }
-    };
     // Issue order (loads return in order): the remainder's columns first, so that their x gathers can follow as
     // soon as they arrive and while everything else is still on its way.
     uint32_t first_c = 0;
@@ -160,7 +134,7 @@ __global__ __launch_bounds__(B) void k_dia_lds(const DiaPlan pl, const int32_t *
         first_v = cval[blk_lo + e0];
     }
     __builtin_amdgcn_sched_barrier(0);
-    window_loads(0);
+    window_loads<T, B, WB>(pl.win, 0, tid, row0, n, x, w, &w_in);
     int32_t rp_mine[R];
     if (HDC) {
 #pragma unroll
@@ -179,11 +153,11 @@ __global__ __launch_bounds__(B) void k_dia_lds(const DiaPlan pl, const int32_t *
     if (HDC && nrem > 0) x_first = x[first_c];
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll 1
-    for (int u0 = WB; u0 * B < pl.elems; u0 += WB) {   // more window positions than one batch holds: rare
-        window_stores(u0 - WB);
-        window_loads(u0);
+    for (int u0 = WB; u0 * B < pl.win.elems; u0 += WB) {   // more window positions than one batch holds: rare
+        window_stores<T, B, WB>(pl.win, u0 - WB, tid, w, w_in, xs);
+        window_loads<T, B, WB>(pl.win, u0, tid, row0, n, x, w, &w_in);
     }
-    window_stores(((pl.elems + B - 1) / B - 1) / WB * WB);
+    window_stores<T, B, WB>(pl.win, ((pl.win.elems + B - 1) / B - 1) / WB * WB, tid, w, w_in, xs);
     if (HDC) {
 #pragma unroll
         for (int u = 0; u < R; ++u) rps[tid + u * B] = rp_mine[u];
@@ -252,7 +226,7 @@ static mo_status launch_lds(const mo_matrix &a, const void *x, void *y, hipStrea
 {
     const int64_t rows = (int64_t)B * R;
     const unsigned grid = (unsigned)((a.m + rows - 1) / rows);
-    const size_t lds = (size_t)a.dia_plan.elems * sizeof(T);
+    const size_t lds = (size_t)a.dia_plan.win.elems * sizeof(T);
     hipLaunchKernelGGL((k_dia_lds<T, B, R, HDC>), dim3(grid), dim3(B), lds, s, a.dia_plan, a.dia_xpos, (const T *)a.dia_val, a.m, a.n, a.nd,
                        a.ld, a.hdc_blk, a.hdc_rp16, a.csr_col, (const T *)a.csr_val, (const T *)x, (T *)y);
     MO_LAUNCH_CHECK();

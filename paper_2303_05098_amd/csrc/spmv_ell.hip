@@ -10,6 +10,7 @@ constexpr int ELL_B = 256;
 constexpr int ELL_U = 8;   // slots fetched together
 constexpr int ELL_WIN_B = 512;                      // rows per block of the kernel with x windows
 constexpr int64_t ELL_WIN_LDS_BYTES = 40 * 1024;    // LDS budget of its windows
+constexpr int ELL_WIN_RUNS = (int)(ELL_WIN_LDS_BYTES / 4 / ELL_WIN_B);   // runs of ELL_WIN_B staged positions at most
 
 // sum += A(row, slots s, s + step, ...) * x over the slots [s0, s1) of one row.  The loads of ELL_U slots are issued
 // together and unconditionally (a padded slot reads x[0] twice and is masked out of the sum), so that no load waits
@@ -76,7 +77,8 @@ __global__ __launch_bounds__(ELL_B) void k_ell(const int32_t *__restrict__ col, 
 template <typename T, int B, bool HYB>
 __global__ __launch_bounds__(B) void k_ell_win(const int32_t *__restrict__ col, const T *__restrict__ val, int64_t m, int64_t n, int64_t K,
                                                int64_t ld, const int32_t *__restrict__ coo_rp, const int32_t *__restrict__ ccol,
-                                               const T *__restrict__ cval, const T *__restrict__ x, T *__restrict__ y, const XPlan xp)
+                                               const T *__restrict__ cval, const T *__restrict__ x, T *__restrict__ y, const XPlan xp,
+                                               const WinRuns<ELL_WIN_RUNS> runs)
 {
     extern __shared__ __align__(16) unsigned char s_raw[];
     T *xs = reinterpret_cast<T *>(s_raw);
@@ -94,17 +96,20 @@ __global__ __launch_bounds__(B) void k_ell_win(const int32_t *__restrict__ col, 
 #pragma unroll
         for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + u * ld);
     }
+    // the windows: all loads of a batch of runs issued before the first is stored (one memory latency per batch, and a
+    // single batch is the rule)
     {
-        int base = 0;
-        for (int q = 0; q < xp.ncl; ++q) {
-            const int len = xp.span[q] + B - 1;
-            const int64_t first = row0 + xp.lo[q];
-            for (int i = threadIdx.x; i < len; i += B) {
-                const int64_t j = first + i;
-                xs[base + i] = (j >= 0 && j < n) ? x[j] : (T)0;
-            }
-            base += len;
+        constexpr int WB = 8;
+        const int tid = (int)threadIdx.x;
+        T w[WB];
+        uint32_t w_in = 0;
+        window_loads<T, B, WB>(runs, 0, tid, row0, n, x, w, &w_in);
+#pragma unroll 1
+        for (int u0 = WB; u0 * B < runs.elems; u0 += WB) {
+            window_stores<T, B, WB>(runs, u0 - WB, tid, w, w_in, xs);
+            window_loads<T, B, WB>(runs, u0, tid, row0, n, x, w, &w_in);
         }
+        window_stores<T, B, WB>(runs, ((runs.elems + B - 1) / B - 1) / WB * WB, tid, w, w_in, xs);
     }
     __syncthreads();
     // window bounds of this block: the same for all lanes (scalar registers)
@@ -241,8 +246,12 @@ static mo_status ell_win_launch(const mo_matrix &a, const void *x, void *y, size
 {
     constexpr int B = ELL_WIN_B;
     const unsigned grid = (unsigned)((a.m + B - 1) / B);
+    WinRuns<ELL_WIN_RUNS> runs;   // the staging order of the windows, from the plan (a few dozen integer operations)
+    int32_t wlen[XP_MAX_CL];
+    for (int q = 0; q < a.xplan.ncl; ++q) wlen[q] = a.xplan.span[q] + B - 1;
+    if (!plan_window_runs(a.xplan.lo, wlen, a.xplan.ncl, B, &runs) || (size_t)runs.elems * sizeof(T) != lds) return MO_E_SHAPE;
     hipLaunchKernelGGL((k_ell_win<T, B, HYB>), dim3(grid), dim3(B), lds, s, a.ell_col, (const T *)a.ell_val, a.m, a.n, a.k, a.ld, a.coo_rp,
-                       a.coo_col, (const T *)a.coo_val, (const T *)x, (T *)y, a.xplan);
+                       a.coo_col, (const T *)a.coo_val, (const T *)x, (T *)y, a.xplan, runs);
     MO_LAUNCH_CHECK();
     return MO_OK;
 }
