@@ -4,6 +4,8 @@
 #include "dev_common.hpp"
 #include "mo_internal.hpp"
 
+#include <type_traits>
+
 namespace mo {
 
 constexpr int ELL_B = 256;
@@ -13,45 +15,75 @@ constexpr int64_t ELL_WIN_LDS_BYTES = 40 * 1024;    // LDS budget of its windows
 constexpr int ELL_WIN_RUNS = (int)(ELL_WIN_LDS_BYTES / 4 / ELL_WIN_B);   // runs of ELL_WIN_B staged positions at most
 
 // sum += A(row, slots s, s + step, ...) * x over the slots [s0, s1) of one row.  The loads of ELL_U slots are issued
-// together and unconditionally (a padded slot reads x[0] twice and is masked out of the sum), so that no load waits
-// for a branch on the one before it, and the column indices of the next ELL_U slots are requested before the values
-// and x entries of the current ones are waited for: loads return in order of issue, so that wait leaves the next
-// columns in flight and a group of slots costs one memory round trip instead of two.  The order of the additions is
-// the slot order.
-template <typename T>
+// together (a padded slot reads x[0] twice and is masked out of the sum; a slot past s1, in the last group, is skipped
+// by a condition that is the same for every lane), so that no load waits for a branch on the one before it, and the
+// column indices of the next ELL_U slots are requested before the values and x entries of the current ones are waited
+// for: a group of slots costs one memory round trip instead of two, and the ragged end of a row costs one group, not
+// two round trips per slot.  The order of the additions is the slot order.
+//
+// RUN: the row also owns the entries [p0, p1) of a COO part (HYB), which are added after the slots, in order.  The
+// first of them travels with the slots: its column and value are requested with the first group's values, its x entry
+// with the second group's, so a row with a single such entry (the usual case) pays no round trip of its own.
+template <typename T, bool RUN = false>
 __device__ __forceinline__ T ell_row_sum(const int32_t *__restrict__ c, const T *__restrict__ v, int64_t ld, int64_t s0, int64_t s1,
-                                         int64_t step, const T *__restrict__ x)
+                                         int64_t step, const T *__restrict__ x, const int32_t *__restrict__ ccol = nullptr,
+                                         const T *__restrict__ cval = nullptr, int32_t p0 = 0, int32_t p1 = 0)
 {
     T sum = (T)0;
+    int32_t jn[ELL_U];
+    // column indices of the group that starts at slot s: unguarded when the whole group lies below s1
+    auto request_columns = [&](int64_t s) {
+        if (s + (ELL_U - 1) * step < s1) {
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (s + u * step) * ld);
+        } else {
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) {
+                jn[u] = -1;
+                if (s + u * step < s1) jn[u] = ld_stream(c + (s + u * step) * ld);
+            }
+        }
+    };
+    uint32_t cc = 0;
+    T cv = (T)0, xg = (T)0;
+    int groups = 0;
     int64_t s = s0;
-    if (s + (ELL_U - 1) * step < s1) {
-        int32_t jn[ELL_U];
+    auto group = [&](auto ragged) {
+        constexpr bool RG = decltype(ragged)::value;
+        int32_t j[ELL_U];
+        T a[ELL_U], xv[ELL_U];
 #pragma unroll
-        for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (s + u * step) * ld);
-        for (; s + (ELL_U - 1) * step < s1; s += ELL_U * step) {
-            int32_t j[ELL_U];
-            T a[ELL_U], xv[ELL_U];
+        for (int u = 0; u < ELL_U; ++u) { j[u] = jn[u]; a[u] = (T)0; xv[u] = (T)0; }
+        if (RUN && groups == 1) xg = x[cc];
 #pragma unroll
-            for (int u = 0; u < ELL_U; ++u) j[u] = jn[u];
-#pragma unroll
-            for (int u = 0; u < ELL_U; ++u) {   // a padded slot reads x[0] in place of its value: no slab traffic for padding
+        for (int u = 0; u < ELL_U; ++u) {   // a padded slot reads x[0] in place of its value: no slab traffic for padding
+            if (!RG || s + u * step < s1) {
                 a[u] = ld_stream(j[u] >= 0 ? v + (s + u * step) * ld : x);
                 xv[u] = x[j[u] >= 0 ? j[u] : 0];
             }
-            const int64_t sn = s + ELL_U * step;
-            if (sn + (ELL_U - 1) * step < s1) {   // uniform: s1 and step are kernel arguments
-#pragma unroll
-                for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (sn + u * step) * ld);
-            }
-#pragma unroll
-            for (int u = 0; u < ELL_U; ++u) sum += j[u] >= 0 ? a[u] * xv[u] : (T)0;
         }
-    }
-    for (; s < s1; s += step) {
-        const int32_t j = ld_stream(c + s * ld);
-        const T a = ld_stream(j >= 0 ? v + s * ld : x);
-        const T xv = x[j >= 0 ? j : 0];
-        sum += j >= 0 ? a * xv : (T)0;
+        if (RUN && groups == 0) {   // entry p0 of the run, or entry 0 of the part for a row without run (dropped later)
+            const int32_t pc = p0 < p1 ? p0 : 0;
+            cc = (uint32_t)ccol[pc];
+            cv = cval[pc];
+        }
+        if (!RG && s + ELL_U * step < s1) request_columns(s + ELL_U * step);
+#pragma unroll
+        for (int u = 0; u < ELL_U; ++u) sum += j[u] >= 0 ? a[u] * xv[u] : (T)0;
+        ++groups;
+    };
+    if (s < s1) request_columns(s);
+    for (; s + (ELL_U - 1) * step < s1; s += ELL_U * step) group(std::false_type{});
+    if (s < s1) group(std::true_type{});
+    if (RUN) {
+        if (groups == 0) {
+            const int32_t pc = p0 < p1 ? p0 : 0;
+            cc = (uint32_t)ccol[pc];
+            cv = cval[pc];
+        }
+        if (groups < 2) xg = x[cc];
+        if (p0 < p1) sum += cv * xg;
+        for (int32_t p = p0 + 1; p < p1; ++p) sum += cval[p] * x[ccol[p]];
     }
     return sum;
 }
@@ -89,13 +121,24 @@ __global__ __launch_bounds__(B) void k_ell_win(const int32_t *__restrict__ col, 
     const int64_t rr = rv ? row : m - 1;   // lanes past the end walk the last row and store nothing
     const int32_t *c = col + rr;
     const T *v = val + rr;
-    // the first group of column indices is requested before the windows, so that both are on their way together
+    // the first group of column indices is requested before the windows, so that both are on their way together; so
+    // are the bounds of the row's run in the COO part (HYB)
     int32_t jn[ELL_U];
-    const bool any_full = ELL_U <= K;
-    if (any_full) {
+    auto request_columns = [&](int64_t s) {   // unguarded when the whole group lies below K
+        if (s + ELL_U <= K) {
 #pragma unroll
-        for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + u * ld);
-    }
+            for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (s + u) * ld);
+        } else {
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) {
+                jn[u] = -1;
+                if (s + u < K) jn[u] = ld_stream(c + (s + u) * ld);
+            }
+        }
+    };
+    if (K > 0) request_columns(0);
+    int32_t p0 = 0, p1 = 0;
+    if (HYB) { p0 = coo_rp[rr]; p1 = coo_rp[rr + 1]; }
     // the windows: all loads of a batch of runs issued before the first is stored (one memory latency per batch, and a
     // single batch is the rule)
     {
@@ -126,63 +169,64 @@ __global__ __launch_bounds__(B) void k_ell_win(const int32_t *__restrict__ col, 
         }
     }
     T sum = (T)0;
+    uint32_t cc = 0;   // HYB: the first entry of the row's COO run travels with the slots (see ell_row_sum)
+    T cv = (T)0, xg = (T)0;
+    int groups = 0;
     int64_t s = 0;
-    if (any_full) {
-        for (; s + ELL_U <= K; s += ELL_U) {
-            int32_t j[ELL_U];
-            T a[ELL_U], xv[ELL_U];
-            int pos[ELL_U];
-            bool hit[ELL_U];
+    auto group = [&](auto ragged) {   // ragged: the last group of a row whose K is no multiple of ELL_U skips the slots past K
+        constexpr bool RG = decltype(ragged)::value;
+        int32_t j[ELL_U];
+        T a[ELL_U], xv[ELL_U];
+        int pos[ELL_U];
+        bool hit[ELL_U];
 #pragma unroll
-            for (int u = 0; u < ELL_U; ++u) { j[u] = jn[u]; pos[u] = 0; hit[u] = false; }
+        for (int u = 0; u < ELL_U; ++u) { j[u] = jn[u]; pos[u] = 0; hit[u] = false; a[u] = (T)0; xv[u] = (T)0; }
+        if (HYB && groups == 1) xg = x[cc];
 #pragma unroll
-            for (int u = 0; u < ELL_U; ++u) a[u] = ld_stream(j[u] >= 0 ? v + (s + u) * ld : x);   // padding: no slab traffic
-            for (int q = 0; q < xp.ncl; ++q) {                    // uniform trip count
-                const int sh = shift[q], ln = wlen[q], bs = wbase[q];
-#pragma unroll
-                for (int u = 0; u < ELL_U; ++u) {
-                    const unsigned idx = (unsigned)(j[u] - sh);
-                    const bool in = idx < (unsigned)ln;
-                    pos[u] = in ? bs + (int)idx : pos[u];
-                    hit[u] = hit[u] || in;
-                }
-            }
-            bool all = true;
-#pragma unroll
-            for (int u = 0; u < ELL_U; ++u) all = all && (hit[u] || j[u] < 0);
-            if (!all) {
-#pragma unroll
-                for (int u = 0; u < ELL_U; ++u) xv[u] = x[(j[u] >= 0 && !hit[u]) ? j[u] : 0];
-            }
-            if (s + 2 * ELL_U <= K) {
-#pragma unroll
-                for (int u = 0; u < ELL_U; ++u) jn[u] = ld_stream(c + (s + ELL_U + u) * ld);
-            }
+        for (int u = 0; u < ELL_U; ++u)
+            if (!RG || s + u < K) a[u] = ld_stream(j[u] >= 0 ? v + (s + u) * ld : x);   // padding: no slab traffic
+        if (HYB && groups == 0) {
+            const int32_t pc = p0 < p1 ? p0 : 0;
+            cc = (uint32_t)ccol[pc];
+            cv = cval[pc];
+        }
+        for (int q = 0; q < xp.ncl; ++q) {                    // uniform trip count
+            const int sh = shift[q], ln = wlen[q], bs = wbase[q];
 #pragma unroll
             for (int u = 0; u < ELL_U; ++u) {
-                const T xl = xs[pos[u]];
-                const T xu = hit[u] ? xl : (all ? (T)0 : xv[u]);
-                sum += j[u] >= 0 ? a[u] * xu : (T)0;
+                const unsigned idx = (unsigned)(j[u] - sh);
+                const bool in = idx < (unsigned)ln;
+                pos[u] = in ? bs + (int)idx : pos[u];
+                hit[u] = hit[u] || in;
             }
         }
-    }
-    for (; s < K; ++s) {
-        const int32_t j = ld_stream(c + s * ld);
-        const T a = ld_stream(j >= 0 ? v + s * ld : x);
-        int pos = 0;
-        bool hit = false;
-        for (int q = 0; q < xp.ncl; ++q) {
-            const unsigned idx = (unsigned)(j - shift[q]);
-            const bool in = idx < (unsigned)wlen[q];
-            pos = in ? wbase[q] + (int)idx : pos;
-            hit = hit || in;
+        bool all = true;
+#pragma unroll
+        for (int u = 0; u < ELL_U; ++u) all = all && (hit[u] || j[u] < 0);
+        if (!all) {
+#pragma unroll
+            for (int u = 0; u < ELL_U; ++u) xv[u] = x[(j[u] >= 0 && !hit[u]) ? j[u] : 0];
         }
-        const T xu = hit ? xs[pos] : x[j >= 0 ? j : 0];
-        sum += j >= 0 ? a * xu : (T)0;
-    }
+        if (!RG && s + ELL_U < K) request_columns(s + ELL_U);
+#pragma unroll
+        for (int u = 0; u < ELL_U; ++u) {
+            const T xl = xs[pos[u]];
+            const T xu = hit[u] ? xl : (all ? (T)0 : xv[u]);
+            sum += j[u] >= 0 ? a[u] * xu : (T)0;
+        }
+        ++groups;
+    };
+    for (; s + ELL_U <= K; s += ELL_U) group(std::false_type{});
+    if (s < K) group(std::true_type{});
     if (HYB) {
-        const int32_t p0 = coo_rp[rr], p1 = coo_rp[rr + 1];
-        for (int32_t p = p0; p < p1; ++p) sum += cval[p] * x[ccol[p]];
+        if (groups == 0) {
+            const int32_t pc = p0 < p1 ? p0 : 0;
+            cc = (uint32_t)ccol[pc];
+            cv = cval[pc];
+        }
+        if (groups < 2) xg = x[cc];
+        if (p0 < p1) sum += cv * xg;
+        for (int32_t p = p0 + 1; p < p1; ++p) sum += cval[p] * x[ccol[p]];
     }
     if (rv) st_stream(y + row, sum);
 }
@@ -222,9 +266,7 @@ __global__ __launch_bounds__(ELL_B) void k_ell_hyb(const int32_t *__restrict__ c
     const int64_t row = lb * ELL_B + threadIdx.x;
     if (row >= m) return;
     const int32_t p0 = coo_rp[row], p1 = coo_rp[row + 1];
-    T sum = ell_row_sum<T>(col + row, val + row, ld, 0, K, 1, x);
-    for (int32_t p = p0; p < p1; ++p) sum += cval[p] * x[ccol[p]];
-    st_stream(y + row, sum);
+    st_stream(y + row, ell_row_sum<T, true>(col + row, val + row, ld, 0, K, 1, x, ccol, cval, p0, p1));
 }
 
 // LDS bytes of the windows for blocks of B rows, or 0 when the plan does not pay: no plan, windows beyond the budget,
