@@ -47,6 +47,10 @@ __global__ __launch_bounds__(COO_B) void k_coo_tile(const int32_t *__restrict__ 
     // 27-point stencil's pattern.)
     __shared__ int s_row[TILE];
     __shared__ T s_prod[TILE];
+    // the row of the entry before the tile (thread 0 needs it at the very end to tell whether the tile's first run
+    // started earlier): requested with everything else, not when it is needed
+    int row_before = -1;
+    if (t == 0 && base > 0) row_before = row[base - 1];
     {
         int rr[COO_STRIP], cc[COO_STRIP];
         T vv[COO_STRIP], xx[COO_STRIP];
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(COO_B) void k_coo_tile(const int32_t *__restrict__ 
         if (ACC) y[tail_row] += total; else y[tail_row] = total;
     }
     // the run at the start of this strip, when its head is here (or, for thread 0, possibly in an earlier tile)
-    const int before = (t == 0) ? (base > 0 ? row[base - 1] : -1) : s_last[t - 1];
+    const int before = (t == 0) ? row_before : s_last[t - 1];
     const bool head_here = r[0] != before;
     if (r[0] >= 0 && (head_here || t == 0)) {
         T total = lead_sum;
