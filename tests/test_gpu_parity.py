@@ -81,6 +81,12 @@ def small_cases():
     spread = [1500 * k for k in range(-8, 8)]
     out.append(("spread16", *synth.banded_scatter(20000, spread, 0, 100, 15)))
     out.append(("spread16s", *synth.banded_scatter(20000, spread, 2, 100, 16)))
+    # ten diagonals 600 apart on a matrix large enough for 512-thread DIA blocks: more x window positions (fp64: ten
+    # windows of 512; fp32, two rows per lane: one window of 6424) than a block requests in its first batch, so the
+    # staging loop runs a second batch; with scattered entries, HDC adds its remainder through the 2-byte row offsets
+    ten = [600 * k for k in range(-5, 5)]
+    out.append(("spread10", *synth.banded_scatter(140000, ten, 0, 100, 21)))
+    out.append(("spread10s", *synth.banded_scatter(140000, ten, 2, 100, 22)))
     # a band with as many scattered entries as the feature traversal's candidate lists do not survive (30 %): the band's
     # diagonals are then counted entry by entry through the block's table of frequent diagonals
     out.append(("band30s", *synth.banded_scatter(60000, synth.C4_OFFSETS, 30, 100, 17)))
@@ -188,6 +194,27 @@ def test_convert_and_spmv(case, dtype):
         nz = mag > 0
         if nz.any():
             assert np.max(np.abs(ys[fmt][nz] - ys[mo.MO_CSR][nz]) / mag[nz]) <= 2 * TOL[dtype]
+
+
+@pytest.mark.parametrize("scatter", [0, 1], ids=["ell", "hyb"])
+def test_ell_windows_in_two_batches(scatter):
+    """Eight groups of four neighbouring diagonals on 320 000 rows: the ELL / HYB kernel with x windows stages 8 x 515
+    positions per block of 512 rows, more than its first batch of requests holds.  A few scattered entries give HYB a
+    COO part whose first entry per row travels with the slots."""
+    offs = [3000 * g + d for g in range(-4, 4) for d in range(4)]
+    m, n, rp, ci, v = synth.banded_scatter(320000, offs, scatter, 100, 23)
+    a = upload(m, n, rp, ci, v)
+    x = synth.make_x(n, 5)
+    ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, np.float64)
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, xo)
+    for fmt in (mo.MO_ELL, mo.MO_HYB):
+        h = mo.mo_convert(a, fmt, dict(max_fill=256))
+        assert h.kernels().startswith("k_ell_win"), h.kernels()
+        y = gpu_spmv(h, x, m, np.float64)
+        err, zeros_ok = ref.spmv_error(y, y_ref, mag)
+        assert err <= TOL[np.float64] and zeros_ok, (mo.FORMAT_NAMES[fmt], err)
+        assert gpu_spmv(h, x, m, np.float64).tobytes() == y.tobytes()
+        h.free()
 
 
 @pytest.mark.parametrize("case", CASES, ids=IDS)
