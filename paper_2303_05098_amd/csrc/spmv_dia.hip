@@ -68,9 +68,10 @@ __global__ __launch_bounds__(DIA_B) void k_hdc_fused(const int32_t *__restrict__
 //
 // Every thread owns R consecutive rows (R = 1 for fp64, 2 for fp32 so that a lane still moves 8 bytes per load).
 //
-// A block's loads are issued as one batch before its barrier: the first DIA_WB positions per thread of the
-// windows, the row pointers (HDC), the slab values of the first DIA_PRE diagonals, and the first chunk of the HDC
-// remainder with its x gathers.  A block then pays one memory latency for all of them instead of one per window
+// A block's loads are issued as one batch before its barrier: the first WB positions per thread of the windows,
+// the row offsets of the remainder (HDC: 2 bytes per row, relative to the block's first remainder entry, which a
+// table with one entry per block names), the slab values of the first DIA_PRE diagonals, and the first chunk of the
+// HDC remainder with its x gathers.  A block then pays one memory latency for all of them instead of one per window
 // piece and per group of four diagonals; blocks are short-lived (a few thousand slab values), so a block that waits
 // for one load at a time keeps almost nothing in flight for much of its life.  Further diagonals follow in batches
 // of DIA_PRE after the barrier.
