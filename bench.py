@@ -43,46 +43,6 @@ MEASURED_TRAFFIC = {
     (3, "f64", "CSR"): 220.5e6 + 232.8e6 + 1.8e6, (3, "f64", "HDC"): 1333.8e6 + 0.9e6, (3, "f64", "HYB"): 661.4e6 + 659.1e6 + 0.9e6,
     (3, "f64", "COO"): 8.4e6 + 1410.5e6 + 0.9e6,
 }
-REPS = 1000 SpMVs in that format.  The headline value is
-2 * nnz * REPS / t_step.  The one-off rows of the path (conversions, run-first tuning) and the SpMV rate of every
-format are measured in the same run and printed in the same JSON line.
-
-Headline workload: the 3-D 27-point stencil on a 128^3 grid in fp64 (synthetic, seeded), with all inputs resident in
-HBM before the timed region starts.  The other large configurations (lognormal rows, banded + scatter in fp64 and
-fp32) and the small Laplacian are measured after it, each with the per-format table, the run-first and the model's
-choice, one Eq. 2 step and the oracle's error for the chosen format, under "configs" of the same line.
-"""
-from __future__ import annotations
-
-import argparse
-import json
-import math
-import os
-import sys
-import time
-
-ROOT = os.path.dirname(os.path.abspath(__file__))
-if ROOT not in sys.path:
-    sys.path.insert(0, ROOT)
-
-HBM_PEAK_GBS = 8000.0
-# HBM bytes per SpMV launch from the committed rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scale
-# factors a plain 1 GiB copy gives).  Not measured by this run: constants taken from the named summary, keyed by
-# (config, dtype, format); a format whose kernels changed since the summary was made has no entry.
-TRAFFIC_SOURCE = {(2, "f64"): "profiles/spmv_all_formats_stencil27_128_f64.md", (3, "f64"): "profiles/spmv_all_formats_lognormal_f64.md",
-                  (4, "f64"): "profiles/spmv_all_formats_banded_scatter_f64.md", (4, "f32"): "profiles/spmv_all_formats_banded_scatter_f32.md"}
-MEASURED_TRAFFIC = {
-    (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 497.4e6, (2, "f64", "CSR"): 715.1e6, (2, "f64", "ELL"): 710.3e6,
-    (2, "f64", "HYB"): 710.3e6, (2, "f64", "COO"): 930.7e6 + 4.5e6,
-    (4, "f64", "HDC"): 535.3e6, (4, "f64", "CSR"): 688.7e6, (4, "f64", "ELL"): 784.4e6, (4, "f64", "HYB"): 684.9e6,
-    (4, "f64", "COO"): 827.5e6 + 3.0e6,
-    (4, "f32", "HDC"): 331.4e6, (4, "f32", "HYB"): 482.4e6, (4, "f32", "CSR"): 483.5e6, (4, "f32", "ELL"): 565.9e6,
-    (4, "f32", "COO"): 624.3e6 + 2.9e6,
-    # lognormal rows: bytes counted at the L2 boundary (x gathers that miss L2 move a 128-byte line each); CSR = two passes
-    # over column slices, HDC (no true diagonal) = the one-pass CSR kernel
-    (3, "f64", "CSR"): 220.3e6 + 232.6e6 + 1.8e6, (3, "f64", "HDC"): 1333.7e6 + 0.9e6, (3, "f64", "HYB"): 658.8e6 + 659.8e6 + 0.9e6,
-    (3, "f64", "COO"): 8.4e6 + 1410.5e6 + 0.9e6,
-}
 REPS = 1000
 LLC_BYTES = 256 << 20     # last-level (Infinity) cache of the MI355X
 MODEL_PATH = os.path.join(ROOT, "paper_2303_05098_amd", "models", "mi355x_forest.bin")
