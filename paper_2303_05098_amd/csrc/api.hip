@@ -195,7 +195,11 @@ static const char *ell_kernel(const mo_matrix &a)
     if (a.m <= ELL_SPLIT_MAX_ROWS && a.k >= ELL_SPLIT_MIN_K) return "k_ell_split";
     return ell_uses_windows(a) ? "k_ell_win" : "k_ell";
 }
-static const char *dia_kernel(const mo_matrix &a, bool hdc) { return a.dia_block ? "k_dia_lds" : (hdc ? "k_hdc_fused" : "k_dia"); }
+static const char *dia_kernel(const mo_matrix &a, bool hdc)
+{
+    if (a.dia_batch) return "k_dia_batch";
+    return a.dia_block ? "k_dia_lds" : (hdc ? "k_hdc_fused" : "k_dia");
+}
 
 mo_status mo_spmv_kernels(const mo_matrix *a, char *buf, size_t cap)
 {

@@ -904,7 +904,6 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         std::vector<int32_t> xpos, cl, mxpos, mcl, mmap;
         int64_t elems = 0, melems = 0;
         const bool have_v = plan_dia_clusters(hoff, block * rows, DIA_LDS_BYTES / (int64_t)sizeof(T), &xpos, &cl, &elems);
-        static_assert(DIA_LDS_BYTES / 4 <= (int64_t)DIA_MAX_RUNS * 256, "runs of the DIA launch plan");
         // the multi-vector product: blocks of SPMM_ROWS rows; kept when a 16-byte piece per row of X fits
         const bool have_m = plan_dia_clusters(hoff, SPMM_ROWS, SPMM_WIN_BYTES / 16, &mxpos, &mcl, &melems);
         if (have_m) {
@@ -923,23 +922,31 @@ mo_status build_dia_part(const mo_csr &a, const mo_params &p, const Analysis &an
         if (have_v || have_m) {
             b.keep.emplace_back();
             std::vector<int32_t> &all = b.keep.back();   // alive until the conversion's final synchronisation
-            const size_t o_xpos = 0, o_mx = o_xpos + (have_v ? xpos.size() : 0), o_map = o_mx + (have_m ? mxpos.size() : 0),
-                         total = o_map + (have_m ? mmap.size() : 0);
+            const size_t o_xpos = 0, o_cl = o_xpos + (have_v ? xpos.size() : 0), o_mx = o_cl + (have_v ? cl.size() : 0),
+                         o_map = o_mx + (have_m ? mxpos.size() : 0), total = o_map + (have_m ? mmap.size() : 0);
             all.reserve(total);
-            if (have_v) all.insert(all.end(), xpos.begin(), xpos.end());
+            if (have_v) { all.insert(all.end(), xpos.begin(), xpos.end()); all.insert(all.end(), cl.begin(), cl.end()); }
             if (have_m) { all.insert(all.end(), mxpos.begin(), mxpos.end()); all.insert(all.end(), mmap.begin(), mmap.end()); }
             int32_t *dev = (int32_t *)b.own(total * 4);
             if (b.failed) return MO_E_ALLOC;
             MO_HIP(hipMemcpyAsync(dev, all.data(), total * 4, hipMemcpyHostToDevice, s));
             if (have_v) {
                 h->dia_xpos = dev + o_xpos;
+                h->dia_clusters = dev + o_cl;
                 h->dia_block = block;
                 h->dia_rows = rows;
-                DiaPlan &pl = h->dia_plan;
-                std::vector<int32_t> wlo, wlen;
-                for (size_t q = 0; q < cl.size(); q += 3) { wlo.push_back(cl[q]); wlen.push_back(cl[q + 1]); }
-                if (!plan_window_runs(wlo.data(), wlen.data(), (int)wlo.size(), block, &pl.win)) return MO_E_SHAPE;   // cannot happen: see the static_assert
-                for (size_t k = 0; k < xpos.size() && k < (size_t)DIA_PRE; ++k) pl.xpos[k] = xpos[k];
+                h->dia_ncl = (int32_t)(cl.size() / 3);
+                h->dia_lds_elems = elems;
+                // large matrices with few diagonals: the batched kernel, whose plan travels in the kernel arguments
+                if (a.m >= DIA_BATCH_MIN_ROWS && block == DIA_BATCH_BLOCK && nd <= DIA_PRE && elems <= (int64_t)DIA_MAX_RUNS * block) {
+                    DiaPlan &pl = h->dia_plan;
+                    std::vector<int32_t> wlo, wlen;
+                    for (size_t q = 0; q < cl.size(); q += 3) { wlo.push_back(cl[q]); wlen.push_back(cl[q + 1]); }
+                    if (plan_window_runs(wlo.data(), wlen.data(), (int)wlo.size(), block, &pl.win)) {
+                        for (size_t k = 0; k < xpos.size(); ++k) pl.xpos[k] = xpos[k];
+                        h->dia_batch = true;
+                    }
+                }
             }
             if (have_m) {
                 h->mm_xpos = dev + o_mx;
@@ -1141,7 +1148,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
         }
         h->csr_row_ptr = rest_ptr; h->csr_col = rcol; h->csr_val = rval;
         MO_TRY(plan_csr(b, rest_ptr, a.m, total, an.max_row));
-        if (total > 0 && h->dia_block && an.max_row <= HDC_FUSED_MAX_ROW) {
+        if (total > 0 && h->dia_batch && an.max_row <= HDC_FUSED_MAX_ROW) {
             // a block of the fused kernel holds at most 1024 rows of at most 64 entries: offsets inside it fit 16 bits
             static_assert(1023 * HDC_FUSED_MAX_ROW <= 65535, "remainder offsets inside a row block");
             const int rows = h->dia_block * h->dia_rows;

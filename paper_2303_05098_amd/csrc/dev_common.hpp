@@ -141,7 +141,7 @@ __device__ __forceinline__ void window_loads(const PL &pl, int u0, int tid, int6
     }
 #pragma unroll
     for (int u = 0; u < WB; ++u)
-        if ((u0 + u) * B < pl.elems) w[u] = x[jj[u]];
+        if (u0 + u == 0 || (u0 + u) * B < pl.elems) w[u] = x[jj[u]];   // run 0 always exists: a window is at least B long
     *in = bits;
 }
 

@@ -126,11 +126,13 @@ inline bool plan_window_runs(const int32_t *lo, const int32_t *len, int nwin, in
     return true;
 }
 
-// Launch plan of the LDS-staged DIA / HDC kernel, passed by value in the kernel arguments (scalar registers: no
-// load to wait for): the x windows of a block as runs of `block` LDS positions (WinRuns), and xpos[k], the position
-// of x[row0 + off_k], for the first DIA_PRE diagonals (all of them are in the device array mo_matrix::dia_xpos).
-constexpr int DIA_MAX_RUNS = 48;   // 48 KB of LDS / (256 threads x 4 bytes)
-constexpr int DIA_PRE = 12;
+// Launch plan of the batched DIA / HDC kernel (large matrices with at most DIA_PRE diagonals), passed by value in the
+// kernel arguments (scalar registers: no load to wait for): the x windows of a block as runs of DIA_BATCH_BLOCK LDS
+// positions (WinRuns), and xpos[k], the position of x[row0 + off_k] for the block's first row row0.
+constexpr int DIA_MAX_RUNS = 16;
+constexpr int DIA_PRE = 12;                        // diagonals the batched kernel takes at most: all loaded as one batch
+constexpr int DIA_BATCH_BLOCK = 512;               // its threads per block
+constexpr int64_t DIA_BATCH_MIN_ROWS = 1 << 19;    // below, the streaming kernel is as fast or faster (measured)
 struct DiaPlan {
     WinRuns<DIA_MAX_RUNS> win;
     int32_t xpos[DIA_PRE] = {};
@@ -148,12 +150,15 @@ struct mo_matrix {
     // x windows the DIA kernels stage in LDS (launch data, derived from dia_off at conversion time)
     int32_t dia_block = 0;            // threads per block of the LDS kernel; 0 = direct kernel
     int32_t dia_rows = 1;             // rows per thread of the LDS kernel
-    mo::DiaPlan dia_plan;             // its windows
-    int32_t *dia_xpos = nullptr;      // per diagonal: LDS position that the block's first row reads
-    // HDC run as one kernel: the remainder's row pointers in the form that kernel reads (launch data; the exported
-    // csr_row_ptr stays as it is).  hdc_blk[b] = first remainder entry of row block b (blocks of dia_block * dia_rows
-    // rows; one entry more than blocks), hdc_rp16[row] = csr_row_ptr[row] - hdc_blk[block of row]: 2 bytes per row
-    // streamed instead of 4.  Null when the fused kernel is not the one that runs.
+    int32_t dia_ncl = 0;
+    int64_t dia_lds_elems = 0;
+    int32_t *dia_xpos = nullptr, *dia_clusters = nullptr;
+    bool dia_batch = false;           // the batched kernel runs (large matrix, few diagonals), with this plan:
+    mo::DiaPlan dia_plan;
+    // HDC run by the batched kernel: the remainder's row pointers in the form that kernel reads (launch data; the
+    // exported csr_row_ptr stays as it is).  hdc_blk[b] = first remainder entry of row block b (blocks of dia_block *
+    // dia_rows rows; one entry more than blocks), hdc_rp16[row] = csr_row_ptr[row] - hdc_blk[block of row]: 2 bytes per
+    // row streamed instead of 4.  Null when that kernel is not the one that runs.
     int32_t *hdc_blk = nullptr;
     uint16_t *hdc_rp16 = nullptr;
     // the same kind of plan for blocks of SPMM_ROWS rows: windows of X for the multi-vector product

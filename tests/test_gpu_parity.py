@@ -81,9 +81,8 @@ def small_cases():
     spread = [1500 * k for k in range(-8, 8)]
     out.append(("spread16", *synth.banded_scatter(20000, spread, 0, 100, 15)))
     out.append(("spread16s", *synth.banded_scatter(20000, spread, 2, 100, 16)))
-    # ten diagonals 600 apart on a matrix large enough for 512-thread DIA blocks: more x window positions (fp64: ten
-    # windows of 512; fp32, two rows per lane: one window of 6424) than a block requests in its first batch, so the
-    # staging loop runs a second batch; with scattered entries, HDC adds its remainder through the 2-byte row offsets
+    # ten diagonals 600 apart on a matrix large enough for 512-thread DIA blocks: ten x windows per block in fp64, one
+    # wide window in fp32 (two rows per lane); with scattered entries, HDC adds its remainder
     ten = [600 * k for k in range(-5, 5)]
     out.append(("spread10", *synth.banded_scatter(140000, ten, 0, 100, 21)))
     out.append(("spread10s", *synth.banded_scatter(140000, ten, 2, 100, 22)))
@@ -194,6 +193,33 @@ def test_convert_and_spmv(case, dtype):
         nz = mag > 0
         if nz.any():
             assert np.max(np.abs(ys[fmt][nz] - ys[mo.MO_CSR][nz]) / mag[nz]) <= 2 * TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32], ids=["f64", "f32"])
+@pytest.mark.parametrize("scatter", [0, 2], ids=["dia", "hdc"])
+def test_batched_dia_kernel(scatter, dtype):
+    """Half a million rows (plus a ragged tail) with ten diagonals 600 apart: the batched DIA / HDC kernel runs, and its
+    x windows (fp64: ten of 512 positions; fp32, two rows per lane: one of 6424) exceed what a block requests in its first
+    batch, so the staging loop runs a second one.  With scattered entries HDC adds its remainder through the 2-byte row
+    offsets per row block."""
+    m, n, rp, ci, v = synth.banded_scatter((1 << 19) + 77, [600 * k for k in range(-5, 5)], scatter, 100, 24)
+    a = upload(m, n, rp, ci, v, dtype)
+    x = synth.make_x(n, 6)
+    ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, dtype)
+    y_ref, mag = ref.spmv(m, n, ti, tj, ta, xo)
+    for fmt in ((mo.MO_DIA, mo.MO_HDC) if scatter == 0 else (mo.MO_HDC,)):
+        h = mo.mo_convert(a, fmt)
+        assert h.kernels() == "k_dia_batch", h.kernels()
+        y = gpu_spmv(h, x, m, dtype)
+        err, zeros_ok = ref.spmv_error(y, y_ref, mag)
+        assert err <= TOL[dtype] and zeros_ok, (mo.FORMAT_NAMES[fmt], err)
+        assert gpu_spmv(h, x, m, dtype).tobytes() == y.tobytes()
+        if fmt == mo.MO_HDC and scatter:
+            e = h.export()
+            assert e["nnz_csr"] > 0 and e["nd"] == 10
+            hd = ref.to_hdc(m, n, ti, tj, ta)
+            assert np.array_equal(e["csr_row_ptr"], hd["csr_row_ptr"]) and np.array_equal(e["csr_col"], hd["csr_col"])
+        h.free()
 
 
 @pytest.mark.parametrize("scatter", [0, 1], ids=["ell", "hyb"])
