@@ -222,6 +222,30 @@ def test_batched_dia_kernel(scatter, dtype):
         h.free()
 
 
+@pytest.mark.parametrize("offsets", [[0], [-2, -1, 0, 1], [-3000, -2, -1, 0, 1, 2, 3000], [700 * k for k in range(-6, 6)]],
+                         ids=["nd1", "nd4", "nd7", "nd12"])
+def test_batched_dia_kernel_by_number_of_diagonals(offsets):
+    """The batched kernel is instantiated per number of diagonals (1 .. 12): one diagonal, one window of four, three
+    windows of seven, twelve windows of twelve, each as HDC with 1 % scattered entries in fp64 and as DIA / HDC without
+    them in fp32 (where the twelve merge into one window that is too long for the batched kernel's plan)."""
+    for scatter, dtype in ((1, np.float64), (0, np.float32)):
+        m, n, rp, ci, v = synth.banded_scatter((1 << 19) + 5, offsets, scatter, 100, 25 + len(offsets))
+        a = upload(m, n, rp, ci, v, dtype)
+        x = synth.make_x(n, 7)
+        ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, dtype)
+        y_ref, mag = ref.spmv(m, n, ti, tj, ta, xo)
+        for fmt in ((mo.MO_HDC,) if scatter else (mo.MO_DIA, mo.MO_HDC)):
+            h = mo.mo_convert(a, fmt)
+            # twelve diagonals 700 apart in fp32 (two rows per lane: blocks of 1024 rows) merge into one window of 8724
+            # positions, more than the plan in the kernel arguments holds: the streaming kernel runs
+            want = "k_dia_lds" if len(offsets) == 12 and dtype == np.float32 else "k_dia_batch"
+            assert h.kernels() == want and h.view().nd == len(offsets), (h.kernels(), h.view().nd)
+            y = gpu_spmv(h, x, m, dtype)
+            err, zeros_ok = ref.spmv_error(y, y_ref, mag)
+            assert err <= TOL[dtype] and zeros_ok, (mo.FORMAT_NAMES[fmt], len(offsets), err)
+            h.free()
+
+
 @pytest.mark.parametrize("scatter", [0, 1], ids=["ell", "hyb"])
 def test_ell_windows_in_two_batches(scatter):
     """Eight groups of four neighbouring diagonals on 320 000 rows: the ELL / HYB kernel with x windows stages 8 x 515
