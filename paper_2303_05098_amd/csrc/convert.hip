@@ -973,6 +973,18 @@ void setup_coo_tiles(Builder &b, size_t sv)
     h->coo_carry_val = b.own((size_t)t * sv);
 }
 
+// Leading dimension of the DIA / ELL slabs: M rounded up to whole groups of 64 rows; when that makes consecutive slabs
+// lie a multiple of 64 KB apart (a matrix whose row count is a power of two, say), 576 rows more.  A row block reads
+// the same rows of every slab at once, and with slabs a large power of two apart those reads fall on the same memory
+// channels: measured with 2^21 rows x 27 diagonals 77.5 us as it is and 75.8 us with the extra rows, with 2^22 rows x 9
+// diagonals 75.0 / 73.4 us (fp32 47.1 / 46.0 us); 128 .. 2368 extra rows all help, 576 most evenly.
+static int64_t slab_ld(int64_t m, size_t sv)
+{
+    int64_t ld = (m + 63) & ~(int64_t)63;
+    if (ld > 0 && (ld * (int64_t)sv) % 65536 == 0) ld += 576;
+    return ld;
+}
+
 template <typename T>
 mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, const Analysis &an, mo_matrix **out, hipStream_t s)
 {
@@ -981,7 +993,7 @@ mo_status convert_typed(const mo_csr &a, mo_format fmt, const mo_params &p, cons
     mo_matrix *h = b.h;
     Scratch scr(s);
     h->fmt = fmt; h->dtype = a.dtype; h->m = a.m; h->n = a.n; h->nnz = a.nnz;
-    h->ld = (a.m + 63) & ~(int64_t)63;
+    h->ld = slab_ld(a.m, sizeof(T));
     const T *aval = (const T *)a.val;
     const unsigned row_blocks = blocks_for(a.m);
 
