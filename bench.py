@@ -34,9 +34,9 @@ TRAFFIC_SOURCE = {(2, "f64"): "profiles/spmv_all_formats_stencil27_128_f64.md", 
 MEASURED_TRAFFIC = {
     (2, "f64", "DIA"): 488.4e6, (2, "f64", "HDC"): 488.4e6, (2, "f64", "CSR"): 715.1e6, (2, "f64", "ELL"): 710.3e6,
     (2, "f64", "HYB"): 710.3e6, (2, "f64", "COO"): 931.1e6 + 4.6e6,
-    (4, "f64", "HDC"): 525.7e6, (4, "f64", "CSR"): 688.8e6, (4, "f64", "ELL"): 784.7e6, (4, "f64", "HYB"): 685.5e6,
-    (4, "f64", "COO"): 827.7e6 + 3.0e6,
-    (4, "f32", "HDC"): 321.7e6, (4, "f32", "HYB"): 483.3e6, (4, "f32", "CSR"): 483.5e6, (4, "f32", "ELL"): 566.4e6,
+    (4, "f64", "HDC"): 525.6e6, (4, "f64", "CSR"): 688.8e6, (4, "f64", "ELL"): 784.7e6, (4, "f64", "HYB"): 685.5e6,
+    (4, "f64", "COO"): 827.8e6 + 3.0e6,
+    (4, "f32", "HDC"): 321.9e6, (4, "f32", "HYB"): 483.3e6, (4, "f32", "CSR"): 483.4e6, (4, "f32", "ELL"): 566.4e6,
     (4, "f32", "COO"): 624.5e6 + 2.9e6,
     # lognormal rows: bytes counted at the L2 boundary (x gathers that miss L2 move a 128-byte line each); CSR = two passes
     # over column slices, HDC (no true diagonal) = the one-pass CSR kernel
