@@ -171,14 +171,14 @@ __global__ __launch_bounds__(256) void k_atomic(const int32_t *__restrict__ idx,
 
 // ------------------------------------------------------------------ 5. nine slabs + scattered gathers
 template <typename T, bool GATHER>
-__global__ __launch_bounds__(512) void k_slabs(const T *__restrict__ val, long m, const T *__restrict__ x, const int32_t *__restrict__ gcol,
-                                               T *__restrict__ y)
+__global__ __launch_bounds__(512) void k_slabs(const T *__restrict__ val, long m, long ld, const T *__restrict__ x,
+                                               const int32_t *__restrict__ gcol, T *__restrict__ y)
 {
     const long row = (long)blockIdx.x * 512 + threadIdx.x;
     if (row >= m) return;
     T s = (T)0;
 #pragma unroll
-    for (int k = 0; k < 9; ++k) s += __builtin_nontemporal_load(val + k * m + row) * x[row];
+    for (int k = 0; k < 9; ++k) s += __builtin_nontemporal_load(val + k * ld + row) * x[row];
     if (GATHER) {
         const int32_t c = __builtin_nontemporal_load(gcol + row);   // -1: this row has no scattered entry
         if (c >= 0) s += x[c];
@@ -186,14 +186,16 @@ __global__ __launch_bounds__(512) void k_slabs(const T *__restrict__ val, long m
     __builtin_nontemporal_store(s, y + row);
 }
 
+// skew: rows between the end of one slab and the start of the next.  With 0 the slabs lie 2^22 elements apart and the
+// nine loads of a row fall on the same memory channels; the library's conversions add 576 rows in that case.
 template <typename T>
-static void run_slabs(const char *name)
+static void run_slabs(const char *name, long skew)
 {
-    const long m = 4194304, scattered = 1167106;
+    const long m = 4194304, scattered = 1167106, ld = m + skew;
     T *val, *x, *y;
     int32_t *gcol;
-    CK(hipMalloc(&val, 9 * m * sizeof(T))); CK(hipMalloc(&x, m * sizeof(T))); CK(hipMalloc(&y, m * sizeof(T))); CK(hipMalloc(&gcol, m * 4));
-    CK(hipMemset(val, 0, 9 * m * sizeof(T))); CK(hipMemset(x, 0, m * sizeof(T)));
+    CK(hipMalloc(&val, 9 * ld * sizeof(T))); CK(hipMalloc(&x, m * sizeof(T))); CK(hipMalloc(&y, m * sizeof(T))); CK(hipMalloc(&gcol, m * 4));
+    CK(hipMemset(val, 0, 9 * ld * sizeof(T))); CK(hipMemset(x, 0, m * sizeof(T)));
     std::vector<int32_t> h((size_t)m, -1);
     uint64_t z = 777;
     for (long i = 0; i < scattered; ++i) {   // rows i * m / scattered carry one gather each, to a random column
@@ -202,11 +204,12 @@ static void run_slabs(const char *name)
     }
     CK(hipMemcpy(gcol, h.data(), m * 4, hipMemcpyHostToDevice));
     const double bytes = (9.0 + 2.0) * m * sizeof(T) + m * 4.0;
-    float ms = time_ms([&] { k_slabs<T, false><<<(unsigned)(m / 512), 512>>>(val, m, x, gcol, y); });
-    std::printf("5 %s: nine slabs, x, y                       : %7.1f us  %7.1f GB/s\n", name, ms * 1e3, (bytes - m * 4.0) / ms / 1e6);
-    ms = time_ms([&] { k_slabs<T, true><<<(unsigned)(m / 512), 512>>>(val, m, x, gcol, y); });
-    std::printf("5 %s: + gather flags and %ld random gathers : %7.1f us  %7.1f GB/s (without the lines the gathers move)\n", name, scattered,
-                ms * 1e3, bytes / ms / 1e6);
+    float ms = time_ms([&] { k_slabs<T, false><<<(unsigned)(m / 512), 512>>>(val, m, ld, x, gcol, y); });
+    std::printf("5 %s, slabs %4ld rows apart: nine slabs, x, y                       : %7.1f us  %7.1f GB/s\n", name, skew, ms * 1e3,
+                (bytes - m * 4.0) / ms / 1e6);
+    ms = time_ms([&] { k_slabs<T, true><<<(unsigned)(m / 512), 512>>>(val, m, ld, x, gcol, y); });
+    std::printf("5 %s, slabs %4ld rows apart: + gather flags and %ld random gathers : %7.1f us  %7.1f GB/s (without the lines the gathers move)\n",
+                name, skew, scattered, ms * 1e3, bytes / ms / 1e6);
     CK(hipFree(val)); CK(hipFree(x)); CK(hipFree(y)); CK(hipFree(gcol));
 }
 
@@ -318,8 +321,10 @@ int main()
         CK(hipFree(table));
         CK(hipFree(idx));
     }
-    run_slabs<double>("fp64");
-    run_slabs<float>("fp32");
+    run_slabs<double>("fp64", 0);
+    run_slabs<double>("fp64", 576);
+    run_slabs<float>("fp32", 0);
+    run_slabs<float>("fp32", 576);
     {
         void *table;
         CK(hipMalloc(&table, (size_t)4 << 20));   // 1024 regions of 2 KB or 31 of 64 KB
