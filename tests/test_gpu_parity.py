@@ -246,6 +246,26 @@ def test_batched_dia_kernel_by_number_of_diagonals(offsets):
             h.free()
 
 
+@pytest.mark.parametrize("m,dtype,skewed", [(1 << 16, np.float64, True), (1 << 16, np.float32, True), ((1 << 16) + 64, np.float64, False),
+                                            (1 << 13, np.float32, False)], ids=["2^16-f64", "2^16-f32", "2^16+64-f64", "2^13-f32"])
+def test_slab_stride_off_powers_of_two(m, dtype, skewed):
+    """Slabs that would lie a multiple of 64 KB apart get 576 rows more each (the exported ld says so), every other
+    matrix keeps ld = M rounded up to 64; the arrays over [:, :m] and the product are the oracle's either way."""
+    mm, n, rp, ci, v = synth.banded_scatter(m, [-1, 0, 1], 0, 100, 31)
+    a = upload(mm, n, rp, ci, v, dtype)
+    x = synth.make_x(n, 8)
+    ti, tj, ta, xo = oracle_inputs(rp, ci, v, x, dtype)
+    y_ref, mag = ref.spmv(mm, n, ti, tj, ta, xo)
+    for fmt in (mo.MO_DIA, mo.MO_ELL):
+        h = mo.mo_convert(a, fmt)
+        e = h.export()
+        assert e["ld"] == (mm + 63) // 64 * 64 + (576 if skewed else 0), e["ld"]
+        check_arrays("stride", e, mm, n, ti, tj, ta, None)
+        err, zeros_ok = ref.spmv_error(gpu_spmv(h, x, mm, dtype), y_ref, mag)
+        assert err <= TOL[dtype] and zeros_ok, (mo.FORMAT_NAMES[fmt], err)
+        h.free()
+
+
 @pytest.mark.parametrize("scatter", [0, 1], ids=["ell", "hyb"])
 def test_ell_windows_in_two_batches(scatter):
     """Eight groups of four neighbouring diagonals on 320 000 rows: the ELL / HYB kernel with x windows stages 8 x 515
